@@ -1,0 +1,168 @@
+/*
+ * knnssd.h - C ABI of the MI355X-native KNN-SSD decode path.
+ *
+ * KNN-SSD (paper Sec. 4): a decoder-only LLM M with L = 2*n_blocks skippable
+ * sublayers (attention and MLP counted separately, Sec. 3.1) drafts tokens with
+ * a subset of its own sublayers, M(z), and verifies them with the full model in
+ * one forward pass (Sec. 4.2). Which skip set z is used is decided per sample
+ * by a nearest-neighbour search of the prompt's last hidden vector among stored
+ * anchor vectors (Sec. 4.2, Eq. 4-6). Decoding is greedy, so the emitted tokens
+ * are exactly the full model's own greedy continuation (Sec. 3.1).
+ *
+ * Conventions
+ *   - "dev" pointers are device (HBM) addresses, "host" pointers host addresses.
+ *   - The caller owns every device buffer (weights, KV cache, workspace, anchor
+ *     table) and the HIP stream; the library allocates no device memory. All
+ *     buffers must stay valid until knnssd_destroy.
+ *   - Every matrix is row-major [out_features][in_features]; weight_dtype says
+ *     whether matrices hold fp32 or bf16 values. RMSNorm gains are always fp32.
+ *   - Skip mask layout: mask[2*b] = 1 skips the attention sublayer of block b,
+ *     mask[2*b+1] = 1 skips its MLP sublayer (z_i = 1 means "skip", Sec. 3.1).
+ *   - Activations, residual stream, RoPE, softmax and all accumulators are fp32;
+ *     keys/values are rounded to kv_dtype (nearest-even) when they are cached.
+ *   - Every call returns KNNSSD_OK (0) or a negative error code. Arguments are
+ *     validated before anything is launched. Calls are synchronous with respect
+ *     to their host outputs (the stream is drained before scalars are returned).
+ *     A context is not thread-safe.
+ */
+#ifndef KNNSSD_H
+#define KNNSSD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define KNNSSD_OK 0
+#define KNNSSD_EINVAL (-1)      /* null pointer or malformed argument                     */
+#define KNNSSD_ESHAPE (-2)      /* shape not supported by the kernels                     */
+#define KNNSSD_ERANGE (-3)      /* position / length / token id outside the valid range   */
+#define KNNSSD_EDEGENERATE (-4) /* zero-norm or non-finite query / anchor (cosine undefined) */
+#define KNNSSD_ESTATE (-5)      /* call made in the wrong order                           */
+#define KNNSSD_EHIP (-6)        /* a HIP runtime call failed                              */
+
+#define KNNSSD_FP32 0
+#define KNNSSD_BF16 1
+
+#define KNNSSD_MAX_ROWS 16  /* rows one verification pass can carry: max_draft + 1 <= 16 */
+
+typedef struct knnssd_model_cfg {
+    int32_t n_blocks, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab;
+    int32_t max_seq;      /* KV-cache capacity in positions                          */
+    int32_t max_anchors;  /* largest anchor table knnssd_set_anchors will be given   */
+    float rope_base;      /* RoPE: rotate-half pairs (i, i+head_dim/2), angle pos*base^(-2i/head_dim) */
+    float rms_eps;
+    int32_t weight_dtype; /* KNNSSD_FP32 | KNNSSD_BF16 */
+    int32_t kv_dtype;     /* KNNSSD_FP32 | KNNSSD_BF16 */
+} knnssd_model_cfg;
+
+/* Device pointers to the model. The four per-block members are HOST arrays of
+ * n_blocks DEVICE pointers (the arrays are copied by knnssd_create).
+ *   wqkv[b]  : [(n_heads + 2*n_kv_heads)*head_dim][d_model]  rows: all q heads, then k heads, then v heads
+ *   wo[b]    : [d_model][n_heads*head_dim]
+ *   wgu[b]   : [2*d_ffn][d_model]                            rows: gate rows, then up rows
+ *   wdown[b] : [d_model][d_ffn]                                                            */
+typedef struct knnssd_weights {
+    const void *embed;          /* [vocab][d_model] */
+    const void *lm_head;        /* [vocab][d_model] */
+    const float *final_norm;    /* [d_model] */
+    const float *const *attn_norm;
+    const void *const *wqkv;
+    const void *const *wo;
+    const float *const *mlp_norm;
+    const void *const *wgu;
+    const void *const *wdown;
+} knnssd_weights;
+
+typedef struct knnssd_gen_cfg {
+    int32_t max_new;       /* tokens to emit after the prompt (the prefill's own token included) */
+    int32_t max_draft;     /* K: draft tokens per round, 0 = plain autoregressive decoding, <= 15 */
+    float conf_threshold;  /* > 0: stop drafting after the first draft whose top-1 probability is
+                              below it (that token is still verified); <= 0 disables the rule    */
+} knnssd_gen_cfg;
+
+/* Counters of one knnssd_generate call. Mean generated length M = (emitted-1)/rounds and
+ * acceptance rate alpha = accepted/drafted are the paper's App. C.2 metrics. Times are GPU
+ * time from HIP events on the context's stream. */
+typedef struct knnssd_stats {
+    int64_t rounds, drafted, accepted, emitted;
+    int64_t ns_prefill, ns_knn, ns_draft, ns_verify, ns_total;
+    int64_t draft_passes, verify_passes;
+} knnssd_stats;
+
+typedef struct knnssd_ctx knnssd_ctx;
+
+/* Bytes of device workspace / KV cache a context of this shape needs (0 if cfg is invalid). */
+size_t knnssd_workspace_bytes(const knnssd_model_cfg *cfg);
+size_t knnssd_kvcache_bytes(const knnssd_model_cfg *cfg);
+
+/* Create a context over caller-owned device memory. kv_dev and ws_dev must be 256-byte
+ * aligned and at least as large as the two size queries say. hip_stream is a hipStream_t
+ * (NULL = the null stream). Launches one set-up kernel (RoPE table) on the stream. */
+int32_t knnssd_create(const knnssd_model_cfg *cfg, const knnssd_weights *w, void *kv_dev, void *ws_dev,
+                      void *hip_stream, knnssd_ctx **out);
+int32_t knnssd_destroy(knnssd_ctx *ctx);
+
+/* Anchor table for the KNN routing step (Sec. 4.1: anchors a_ij with their domain label i and
+ * one stored skip set z*_i per domain). anchors_dev: fp32 [n_anchors][dim], dim must equal
+ * d_model; labels_dev: int32 [n_anchors] in [0, n_domains); masks_host: uint8
+ * [n_domains][2*n_blocks], copied. n_anchors <= cfg.max_anchors. */
+int32_t knnssd_set_anchors(knnssd_ctx *ctx, const float *anchors_dev, const int32_t *labels_dev,
+                           int32_t n_anchors, int32_t dim, const uint8_t *masks_host, int32_t n_domains);
+
+/* Prefill (Sec. 4.2 "extract its last hidden vector v from the model"): the full model over
+ * n prompt tokens at positions 0..n-1. Resets the KV cache length to n. Outputs: the first
+ * generated token (host) and, if last_hidden_dev is not NULL, the final-RMSNorm hidden state of
+ * the last prompt token (fp32 [d_model], device) - the vector the KNN step is queried with. */
+int32_t knnssd_prefill(knnssd_ctx *ctx, const int32_t *tokens_host, int32_t n, float *last_hidden_dev,
+                       int32_t *first_token_out);
+
+/* Eq. 4-6: cosine-similarity arg-max of query_dev (fp32 [d_model], device) over all anchors
+ * (lowest index wins a tie), domain = that anchor's label, and the domain's stored skip set
+ * becomes the context's draft mask. Host outputs may be NULL. mask_out: 2*n_blocks bytes. */
+int32_t knnssd_select_skipset(knnssd_ctx *ctx, const float *query_dev, int32_t *anchor_idx_out,
+                              int32_t *domain_out, uint8_t *mask_out);
+
+/* Install a draft mask directly (2*n_blocks bytes on the host; NULL = skip nothing). */
+int32_t knnssd_set_skipset(knnssd_ctx *ctx, const uint8_t *mask_host);
+
+/* One draft step (Eq. 7): token_in at position pos through M(z) with the installed mask; only
+ * retained attention sublayers read and write the KV cache. Returns the arg-max token (lowest
+ * index on ties) and its softmax probability at temperature 1. pos must be < max_seq. */
+int32_t knnssd_draft_step(knnssd_ctx *ctx, int32_t token_in, int32_t pos, int32_t *token_out,
+                          float *top1_prob_out);
+
+/* Verification (Sec. 4.2): the full model over n rows tokens_host = [x_last, d_1..d_k]
+ * (n = k+1 <= KNNSSD_MAX_ROWS) at positions start_pos..start_pos+k in ONE pass; every block
+ * overwrites its KV entries at those positions; row i attends to positions 0..start_pos+i.
+ * Greedy acceptance: *n_accepted_out = j, the number of leading drafts equal to the model's own
+ * token; *next_token_out = the model's token after the accepted prefix; *new_cache_len_out =
+ * start_pos + j + 1 (cache entries beyond it are dead: rollback is this counter). */
+int32_t knnssd_verify(knnssd_ctx *ctx, const int32_t *tokens_host, int32_t n, int32_t start_pos,
+                      int32_t *n_accepted_out, int32_t *next_token_out, int32_t *new_cache_len_out);
+
+/* The whole per-sample path: prefill, KNN routing (query_dev, or the prompt's own last hidden
+ * vector when query_dev is NULL; skipped when no anchor table is set or max_draft = 0, in which
+ * case the installed mask is used), then draft/verify rounds until max_new tokens are out.
+ * out_tokens_host must hold max_new entries; *n_out receives the count. n_prompt + max_new +
+ * max_draft must not exceed max_seq. stats may be NULL. */
+int32_t knnssd_generate(knnssd_ctx *ctx, const int32_t *prompt_host, int32_t n_prompt,
+                        const float *query_dev, const knnssd_gen_cfg *gen, int32_t *out_tokens_host,
+                        int32_t *n_out, knnssd_stats *stats);
+
+/* Parity/debug: fp32 logits of row `row` of the most recent pass (draft: row 0). */
+int32_t knnssd_get_logits(knnssd_ctx *ctx, int32_t row, float *logits_host);
+
+/* Parity/debug: cached key and value (as fp32) of one block at one position,
+ * each [n_kv_heads*head_dim] on the host. */
+int32_t knnssd_read_kv(knnssd_ctx *ctx, int32_t block, int32_t pos, float *k_host, float *v_host);
+
+/* Message for an error code; for KNNSSD_EHIP the text of the last HIP error of this thread. */
+const char *knnssd_strerror(int32_t code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KNNSSD_H */

@@ -1,0 +1,261 @@
+"""Thin ctypes binding of libknnssd.so: argument marshalling only.
+
+Every step of the decode path runs in the library's HIP kernels. PyTorch is used
+here for two things: owning device memory (weights, KV cache, workspace, anchor
+table) and naming the HIP stream the kernels are put on. There is no CPU or
+PyTorch fallback: if the library is missing or a call fails, an exception is
+raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Dict, List, Optional, Sequence
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libknnssd.so")
+
+KNNSSD_MAX_ROWS = 16
+_DT = {"fp32": 0, "bf16": 1}
+
+EXPORTS = [
+    "knnssd_workspace_bytes", "knnssd_kvcache_bytes", "knnssd_create", "knnssd_destroy",
+    "knnssd_set_anchors", "knnssd_prefill", "knnssd_select_skipset", "knnssd_set_skipset",
+    "knnssd_draft_step", "knnssd_verify", "knnssd_generate", "knnssd_get_logits", "knnssd_read_kv",
+    "knnssd_strerror",
+]
+
+
+class ModelCfg(ctypes.Structure):
+    _fields_ = [("n_blocks", ctypes.c_int32), ("d_model", ctypes.c_int32), ("n_heads", ctypes.c_int32),
+                ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32), ("d_ffn", ctypes.c_int32),
+                ("vocab", ctypes.c_int32), ("max_seq", ctypes.c_int32), ("max_anchors", ctypes.c_int32),
+                ("rope_base", ctypes.c_float), ("rms_eps", ctypes.c_float),
+                ("weight_dtype", ctypes.c_int32), ("kv_dtype", ctypes.c_int32)]
+
+
+class Weights(ctypes.Structure):
+    _fields_ = [("embed", ctypes.c_void_p), ("lm_head", ctypes.c_void_p), ("final_norm", ctypes.c_void_p),
+                ("attn_norm", ctypes.c_void_p), ("wqkv", ctypes.c_void_p), ("wo", ctypes.c_void_p),
+                ("mlp_norm", ctypes.c_void_p), ("wgu", ctypes.c_void_p), ("wdown", ctypes.c_void_p)]
+
+
+class GenCfg(ctypes.Structure):
+    _fields_ = [("max_new", ctypes.c_int32), ("max_draft", ctypes.c_int32), ("conf_threshold", ctypes.c_float)]
+
+
+class Stats(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int64) for n in
+                ("rounds", "drafted", "accepted", "emitted", "ns_prefill", "ns_knn", "ns_draft", "ns_verify",
+                 "ns_total", "draft_passes", "verify_passes")]
+
+    def as_dict(self) -> Dict[str, int]:
+        return {n: int(getattr(self, n)) for n, _ in self._fields_}
+
+
+class KnnSsdError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"knnssd error {code}: {msg}")
+        self.code = code
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load the built library; fails loudly when it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2505_16162_amd.build` "
+            "(there is no fallback path)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_float
+    lib.knnssd_workspace_bytes.restype = ctypes.c_size_t
+    lib.knnssd_workspace_bytes.argtypes = [ctypes.POINTER(ModelCfg)]
+    lib.knnssd_kvcache_bytes.restype = ctypes.c_size_t
+    lib.knnssd_kvcache_bytes.argtypes = [ctypes.POINTER(ModelCfg)]
+    lib.knnssd_create.restype = i32
+    lib.knnssd_create.argtypes = [ctypes.POINTER(ModelCfg), ctypes.POINTER(Weights), vp, vp, vp, ctypes.POINTER(vp)]
+    lib.knnssd_destroy.restype = i32
+    lib.knnssd_destroy.argtypes = [vp]
+    lib.knnssd_set_anchors.restype = i32
+    lib.knnssd_set_anchors.argtypes = [vp, vp, vp, i32, i32, vp, i32]
+    lib.knnssd_prefill.restype = i32
+    lib.knnssd_prefill.argtypes = [vp, vp, i32, vp, ctypes.POINTER(i32)]
+    lib.knnssd_select_skipset.restype = i32
+    lib.knnssd_select_skipset.argtypes = [vp, vp, ctypes.POINTER(i32), ctypes.POINTER(i32), vp]
+    lib.knnssd_set_skipset.restype = i32
+    lib.knnssd_set_skipset.argtypes = [vp, vp]
+    lib.knnssd_draft_step.restype = i32
+    lib.knnssd_draft_step.argtypes = [vp, i32, i32, ctypes.POINTER(i32), ctypes.POINTER(f32)]
+    lib.knnssd_verify.restype = i32
+    lib.knnssd_verify.argtypes = [vp, vp, i32, i32, ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(i32)]
+    lib.knnssd_generate.restype = i32
+    lib.knnssd_generate.argtypes = [vp, vp, i32, vp, ctypes.POINTER(GenCfg), vp, ctypes.POINTER(i32), ctypes.POINTER(Stats)]
+    lib.knnssd_get_logits.restype = i32
+    lib.knnssd_get_logits.argtypes = [vp, i32, vp]
+    lib.knnssd_read_kv.restype = i32
+    lib.knnssd_read_kv.argtypes = [vp, i32, i32, vp, vp]
+    lib.knnssd_strerror.restype = ctypes.c_char_p
+    lib.knnssd_strerror.argtypes = [i32]
+    _lib = lib
+    return lib
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise KnnSsdError(rc, load_library().knnssd_strerror(rc).decode())
+
+
+def make_cfg(shape, max_anchors: int = 0) -> ModelCfg:
+    return ModelCfg(shape.n_blocks, shape.d_model, shape.n_heads, shape.n_kv_heads, shape.head_dim, shape.d_ffn,
+                    shape.vocab, shape.max_seq, max_anchors, float(shape.rope_base), float(shape.rms_eps),
+                    _DT[shape.weight_dtype], _DT[shape.kv_dtype])
+
+
+def _i32_array(values: Sequence[int]):
+    arr = (ctypes.c_int32 * len(values))(*[int(v) for v in values])
+    return arr
+
+
+class KnnSsd:
+    """A library context over torch-owned device memory. Method names follow the C ABI."""
+
+    def __init__(self, shape, weights: Dict, max_anchors: int = 0, device="cuda:0", stream: Optional[torch.cuda.Stream] = None):
+        self.lib = load_library()
+        self.shape = shape
+        self.device = torch.device(device)
+        if self.device.type != "cuda":
+            raise ValueError("the decode path runs on the GPU only")
+        self.cfg = make_cfg(shape, max_anchors)
+        ws_bytes = self.lib.knnssd_workspace_bytes(ctypes.byref(self.cfg))
+        kv_bytes = self.lib.knnssd_kvcache_bytes(ctypes.byref(self.cfg))
+        if ws_bytes == 0 or kv_bytes == 0:
+            raise KnnSsdError(-2, "shape not supported")
+        self._keep: List = []
+        dev = self.device
+
+        def on_dev(t: torch.Tensor) -> torch.Tensor:
+            t = t.to(dev).contiguous()
+            self._keep.append(t)
+            return t
+
+        nb = shape.n_blocks
+        # fused row-major matrices the ABI asks for: [q;k;v] and [gate;up] stacked along rows
+        blocks = weights["blocks"]
+        wqkv, wo, wgu, wdown, an, mn = [], [], [], [], [], []
+        for b in blocks:
+            wqkv.append(on_dev(torch.cat([b["wq"].to(dev), b["wk"].to(dev), b["wv"].to(dev)], 0)))
+            wo.append(on_dev(b["wo"]))
+            wgu.append(on_dev(torch.cat([b["wg"].to(dev), b["wu"].to(dev)], 0)))
+            wdown.append(on_dev(b["wd"]))
+            an.append(on_dev(b["attn_norm"].float()))
+            mn.append(on_dev(b["mlp_norm"].float()))
+        self.embed = on_dev(weights["embed"])
+        self.lm_head = on_dev(weights["lm_head"])
+        self.final_norm = on_dev(weights["final_norm"].float())
+
+        def ptr_array(ts):
+            arr = (ctypes.c_void_p * max(nb, 1))(*[t.data_ptr() for t in ts])
+            self._keep.append(arr)
+            return ctypes.cast(arr, ctypes.c_void_p)
+
+        self.w = Weights(self.embed.data_ptr(), self.lm_head.data_ptr(), self.final_norm.data_ptr(),
+                         ptr_array(an), ptr_array(wqkv), ptr_array(wo), ptr_array(mn), ptr_array(wgu), ptr_array(wdown))
+        self.kv = torch.zeros(kv_bytes, dtype=torch.uint8, device=dev)
+        self.ws = torch.zeros(ws_bytes, dtype=torch.uint8, device=dev)
+        self.stream = stream if stream is not None else torch.cuda.current_stream(dev)
+        h = ctypes.c_void_p()
+        torch.cuda.synchronize(dev)
+        _check(self.lib.knnssd_create(ctypes.byref(self.cfg), ctypes.byref(self.w), self.kv.data_ptr(),
+                                      self.ws.data_ptr(), ctypes.c_void_p(self.stream.cuda_stream), ctypes.byref(h)))
+        self.h = h
+        self.weight_bytes = sum(t.numel() * t.element_size() for t in wqkv + wo + wgu + wdown) + \
+            self.lm_head.numel() * self.lm_head.element_size()
+
+    def close(self):
+        if getattr(self, "h", None):
+            self.lib.knnssd_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- the calls of the C ABI, same names -------------------------------------------------
+    def knnssd_set_anchors(self, anchors: torch.Tensor, labels: torch.Tensor, masks: torch.Tensor):
+        self.anchors = anchors.to(self.device, torch.float32).contiguous()
+        self.labels = labels.to(self.device, torch.int32).contiguous()
+        m = masks.to("cpu", torch.uint8).contiguous()
+        self._masks_host = m
+        _check(self.lib.knnssd_set_anchors(self.h, self.anchors.data_ptr(), self.labels.data_ptr(),
+                                           self.anchors.shape[0], self.anchors.shape[1], m.data_ptr(), m.shape[0]))
+
+    def knnssd_prefill(self, tokens: Sequence[int], want_hidden: bool = True):
+        toks = _i32_array(tokens)
+        hidden = torch.empty(self.shape.d_model, dtype=torch.float32, device=self.device) if want_hidden else None
+        first = ctypes.c_int32()
+        _check(self.lib.knnssd_prefill(self.h, toks, len(tokens), hidden.data_ptr() if want_hidden else None,
+                                       ctypes.byref(first)))
+        return int(first.value), hidden
+
+    def knnssd_select_skipset(self, query: torch.Tensor):
+        q = query.to(self.device, torch.float32).contiguous()
+        idx, dom = ctypes.c_int32(), ctypes.c_int32()
+        mask = (ctypes.c_uint8 * (2 * self.shape.n_blocks))()
+        _check(self.lib.knnssd_select_skipset(self.h, q.data_ptr(), ctypes.byref(idx), ctypes.byref(dom), mask))
+        return int(idx.value), int(dom.value), list(mask)
+
+    def knnssd_set_skipset(self, mask: Optional[Sequence[int]]):
+        if mask is None:
+            _check(self.lib.knnssd_set_skipset(self.h, None))
+        else:
+            arr = (ctypes.c_uint8 * len(mask))(*[int(v) for v in mask])
+            if len(mask) != 2 * self.shape.n_blocks:
+                raise ValueError("mask must have 2*n_blocks entries")
+            _check(self.lib.knnssd_set_skipset(self.h, arr))
+
+    def knnssd_draft_step(self, token_in: int, pos: int):
+        tok, p = ctypes.c_int32(), ctypes.c_float()
+        _check(self.lib.knnssd_draft_step(self.h, int(token_in), int(pos), ctypes.byref(tok), ctypes.byref(p)))
+        return int(tok.value), float(p.value)
+
+    def knnssd_verify(self, tokens: Sequence[int], start_pos: int):
+        toks = _i32_array(tokens)
+        j, nxt, new_len = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32()
+        _check(self.lib.knnssd_verify(self.h, toks, len(tokens), int(start_pos), ctypes.byref(j), ctypes.byref(nxt),
+                                      ctypes.byref(new_len)))
+        return int(j.value), int(nxt.value), int(new_len.value)
+
+    def knnssd_generate(self, prompt: Sequence[int], max_new: int, max_draft: int, conf_threshold: float = 0.0,
+                        query: Optional[torch.Tensor] = None):
+        toks = _i32_array(prompt)
+        gen = GenCfg(int(max_new), int(max_draft), float(conf_threshold))
+        out = (ctypes.c_int32 * max(int(max_new), 1))()
+        n_out = ctypes.c_int32()
+        st = Stats()
+        q = None
+        if query is not None:
+            q = query.to(self.device, torch.float32).contiguous()
+        _check(self.lib.knnssd_generate(self.h, toks, len(prompt), q.data_ptr() if q is not None else None,
+                                        ctypes.byref(gen), out, ctypes.byref(n_out), ctypes.byref(st)))
+        return list(out[:n_out.value]), st.as_dict()
+
+    def knnssd_get_logits(self, row: int = 0) -> torch.Tensor:
+        out = torch.empty(self.shape.vocab, dtype=torch.float32)
+        _check(self.lib.knnssd_get_logits(self.h, int(row), out.data_ptr()))
+        return out
+
+    def knnssd_read_kv(self, block: int, pos: int):
+        kvd = self.shape.n_kv_heads * self.shape.head_dim
+        k = torch.empty(kvd, dtype=torch.float32)
+        v = torch.empty(kvd, dtype=torch.float32)
+        _check(self.lib.knnssd_read_kv(self.h, int(block), int(pos), k.data_ptr(), v.data_ptr()))
+        return k, v

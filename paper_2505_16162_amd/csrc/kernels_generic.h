@@ -1,0 +1,451 @@
+// Generic (any shape, fp32 or bf16 storage) kernels of the decode path, written for gfx950:
+// 64-wide wavefronts, 16-byte coalesced weight loads, wavefront reductions.
+// These are the kernels of the fp32 path and the building blocks the tuned bf16 kernels
+// fall back to when a shape does not fit their tiling.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "device_types.h"
+
+namespace ks {
+
+typedef uint16_t bf16_t;  // raw bit pattern
+
+__device__ __forceinline__ float bf16_to_float(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// fp32 -> bf16, round to nearest even (inf/nan pass through with the payload truncated)
+__device__ __forceinline__ bf16_t float_to_bf16_rne(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7f800000u) == 0x7f800000u) return (bf16_t)(u >> 16);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float load_as_float(const float *p, size_t i) { return p[i]; }
+__device__ __forceinline__ float load_as_float(const bf16_t *p, size_t i) { return bf16_to_float(p[i]); }
+__device__ __forceinline__ void store_rounded(float *p, size_t i, float v) { p[i] = v; }
+__device__ __forceinline__ void store_rounded(bf16_t *p, size_t i, float v) { p[i] = float_to_bf16_rne(v); }
+
+// One 16-byte chunk of a weight row as floats.
+template <typename WT> struct WChunk;
+template <> struct WChunk<float> {
+    static constexpr int N = 4;
+    float v[4];
+    __device__ __forceinline__ void load(const float *p) {
+        float4 t = *reinterpret_cast<const float4 *>(p);
+        v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+    }
+};
+template <> struct WChunk<bf16_t> {
+    static constexpr int N = 8;
+    float v[8];
+    __device__ __forceinline__ void load(const bf16_t *p) {
+        uint4 t = *reinterpret_cast<const uint4 *>(p);
+        v[0] = __uint_as_float(t.x << 16); v[1] = __uint_as_float(t.x & 0xffff0000u);
+        v[2] = __uint_as_float(t.y << 16); v[3] = __uint_as_float(t.y & 0xffff0000u);
+        v[4] = __uint_as_float(t.z << 16); v[5] = __uint_as_float(t.z & 0xffff0000u);
+        v[6] = __uint_as_float(t.w << 16); v[7] = __uint_as_float(t.w & 0xffff0000u);
+    }
+};
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+    return v;
+}
+
+// ------------------------------------------------------------------------------------------
+// pass control
+// ------------------------------------------------------------------------------------------
+struct TokArgs { int32_t t[KS_MAX_ROWS]; };
+
+__global__ void set_pass_kernel(PassCtl *ctl, int active, int n_rows, int start, int head_from, TokArgs toks) {
+    if (threadIdx.x == 0) {
+        ctl->active = active; ctl->n_rows = n_rows; ctl->start = start; ctl->head_from = head_from;
+    }
+    if (threadIdx.x < KS_MAX_ROWS) ctl->tok[threadIdx.x] = toks.t[threadIdx.x];
+}
+
+// ------------------------------------------------------------------------------------------
+// RoPE table: cos/sin of pos * base^(-2i/head_dim), evaluated in double, stored fp32
+// ------------------------------------------------------------------------------------------
+__global__ void rope_table_kernel(float *cos_t, float *sin_t, int max_seq, int half, int head_dim, double base) {
+    int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= max_seq * half) return;
+    int pos = idx / half, i = idx % half;
+    double ang = (double)pos * pow(base, -2.0 * (double)i / (double)head_dim);
+    cos_t[idx] = (float)cos(ang);
+    sin_t[idx] = (float)sin(ang);
+}
+
+// ------------------------------------------------------------------------------------------
+// embedding gather: x[r][:] = E[tok[r]][:]
+// ------------------------------------------------------------------------------------------
+template <typename WT>
+__global__ void embed_kernel(const PassCtl *ctl, const WT *E, float *x, int d) {
+    if (!ctl->active) return;
+    int r = blockIdx.x;
+    if (r >= ctl->n_rows) return;
+    const WT *row = E + (size_t)ctl->tok[r] * d;
+    for (int i = threadIdx.x; i < d; i += blockDim.x) x[(size_t)r * d + i] = load_as_float(row, i);
+}
+
+// ------------------------------------------------------------------------------------------
+// RMSNorm: out[r][:] = x[r][:] * rsqrt(mean(x^2) + eps) * gain       (one workgroup per row)
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const PassCtl *ctl, const float *x, const float *gain,
+                                                      float *out, int d, float eps) {
+    if (!ctl->active) return;
+    int r = blockIdx.x;
+    if (r >= ctl->n_rows) return;
+    __shared__ float part[4];
+    const float *xr = x + (size_t)r * d;
+    float ss = 0.f;
+    for (int i = threadIdx.x; i < d; i += 256) { float v = xr[i]; ss = fmaf(v, v, ss); }
+    ss = wave_sum(ss);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    float tot = (part[0] + part[1]) + (part[2] + part[3]);
+    float rs = 1.0f / sqrtf(tot / (float)d + eps);
+    for (int i = threadIdx.x; i < d; i += 256) out[(size_t)r * d + i] = xr[i] * rs * gain[i];
+}
+
+// ------------------------------------------------------------------------------------------
+// Y = X W^T for up to MR rows of X, one output feature per wavefront (lanes stride over K in
+// 16-byte chunks of the weight row), with the epilogues the decoder needs.
+// ------------------------------------------------------------------------------------------
+enum { EPI_STORE = 0, EPI_RESID = 1, EPI_SWIGLU = 2 };
+
+template <typename WT, int MR, int EPI>
+__global__ __launch_bounds__(256) void gemm_rows_kernel(const PassCtl *ctl, const WT *__restrict__ W,
+                                                        const WT *__restrict__ W2, const float *__restrict__ X,
+                                                        int ldx, float *Y, int ldy, int N, int K, int use_head_from) {
+    if (!ctl->active) return;
+    const int n_rows = min(ctl->n_rows, MR);
+    const int row_lo = use_head_from ? ctl->head_from : 0;
+    if (row_lo >= n_rows) return;
+    const int lane = threadIdx.x & 63;
+    const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int n_waves = (gridDim.x * blockDim.x) >> 6;
+    constexpr int VEC = WChunk<WT>::N;
+
+    for (int o = wave; o < N; o += n_waves) {
+        float acc[MR], acc2[MR];
+#pragma unroll
+        for (int r = 0; r < MR; ++r) { acc[r] = 0.f; acc2[r] = 0.f; }
+        const WT *wrow = W + (size_t)o * K;
+        const WT *wrow2 = (EPI == EPI_SWIGLU) ? (W2 + (size_t)o * K) : nullptr;
+        for (int k = lane * VEC; k < K; k += 64 * VEC) {
+            WChunk<WT> w, w2;
+            w.load(wrow + k);
+            if (EPI == EPI_SWIGLU) w2.load(wrow2 + k);
+#pragma unroll
+            for (int r = 0; r < MR; ++r) {
+                if (r >= row_lo && r < n_rows) {
+                    const float *xp = X + (size_t)r * ldx + k;
+#pragma unroll
+                    for (int j = 0; j < VEC; j += 4) {
+                        float4 xv = *reinterpret_cast<const float4 *>(xp + j);
+                        acc[r] = fmaf(w.v[j + 0], xv.x, acc[r]);
+                        acc[r] = fmaf(w.v[j + 1], xv.y, acc[r]);
+                        acc[r] = fmaf(w.v[j + 2], xv.z, acc[r]);
+                        acc[r] = fmaf(w.v[j + 3], xv.w, acc[r]);
+                        if (EPI == EPI_SWIGLU) {
+                            acc2[r] = fmaf(w2.v[j + 0], xv.x, acc2[r]);
+                            acc2[r] = fmaf(w2.v[j + 1], xv.y, acc2[r]);
+                            acc2[r] = fmaf(w2.v[j + 2], xv.z, acc2[r]);
+                            acc2[r] = fmaf(w2.v[j + 3], xv.w, acc2[r]);
+                        }
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < MR; ++r) {
+            if (r >= row_lo && r < n_rows) {
+                float a = wave_sum(acc[r]);
+                float b = (EPI == EPI_SWIGLU) ? wave_sum(acc2[r]) : 0.f;
+                if (lane == 0) {
+                    float *yp = Y + (size_t)r * ldy + o;
+                    if (EPI == EPI_STORE) *yp = a;
+                    if (EPI == EPI_RESID) *yp = *yp + a;
+                    if (EPI == EPI_SWIGLU) *yp = (a / (1.0f + expf(-a))) * b;
+                }
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// RoPE on q (in place) and k, then k and v into the cache (rounded to the cache type).
+// qkv: [rows][(H + 2 Hkv) * hd] fp32.  cache layout: [2 (k,v)][Hkv][max_seq][hd]
+// ------------------------------------------------------------------------------------------
+template <typename KT>
+__global__ __launch_bounds__(256) void rope_kv_kernel(const PassCtl *ctl, float *qkv, KT *kv_block,
+                                                      const float *cos_t, const float *sin_t, int H, int Hkv,
+                                                      int hd, int max_seq) {
+    if (!ctl->active) return;
+    const int r = blockIdx.x;
+    if (r >= ctl->n_rows) return;
+    const int pos = ctl->start + r;
+    const int half = hd >> 1;
+    const int ld = (H + 2 * Hkv) * hd;
+    float *row = qkv + (size_t)r * ld;
+    const float *cs = cos_t + (size_t)pos * half, *sn = sin_t + (size_t)pos * half;
+    KT *kc = kv_block;
+    KT *vc = kv_block + (size_t)Hkv * max_seq * hd;
+    for (int idx = threadIdx.x; idx < (H + Hkv) * half; idx += blockDim.x) {
+        int h = idx / half, i = idx % half;
+        float c = cs[i], s = sn[i];
+        float a = row[h * hd + i], b = row[h * hd + i + half];
+        float ra = a * c - b * s, rb = b * c + a * s;
+        if (h < H) {
+            row[h * hd + i] = ra; row[h * hd + i + half] = rb;
+        } else {
+            size_t base = ((size_t)(h - H) * max_seq + pos) * hd;
+            store_rounded(kc, base + i, ra);
+            store_rounded(kc, base + i + half, rb);
+        }
+    }
+    const float *vrow = row + (size_t)(H + Hkv) * hd;
+    for (int idx = threadIdx.x; idx < Hkv * hd; idx += blockDim.x) {
+        int h = idx / hd, i = idx % hd;
+        store_rounded(vc, ((size_t)h * max_seq + pos) * hd + i, vrow[idx]);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Attention of one (row, head): softmax(q K^T / sqrt(hd)) V over positions 0..start+r.
+// One workgroup per (head, row); scores are kept in LDS (max_seq floats of dynamic LDS).
+// ------------------------------------------------------------------------------------------
+template <typename KT>
+__global__ __launch_bounds__(256) void attention_kernel(const PassCtl *ctl, const float *qkv, const KT *kv_block,
+                                                        float *att, int H, int Hkv, int hd, int max_seq) {
+    if (!ctl->active) return;
+    const int h = blockIdx.x, r = blockIdx.y;
+    if (r >= ctl->n_rows) return;
+    extern __shared__ float lds[];
+    float *scores = lds;                 // [len]
+    __shared__ float red[8];
+    __shared__ float outp[4][128];
+    const int len = ctl->start + r + 1;
+    const int kvh = h / (H / Hkv);
+    const int ld = (H + 2 * Hkv) * hd;
+    const float *q = qkv + (size_t)r * ld + h * hd;
+    const KT *kc = kv_block + (size_t)kvh * max_seq * hd;
+    const KT *vc = kv_block + ((size_t)Hkv + kvh) * max_seq * hd;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const float scale = 1.0f / sqrtf((float)hd);
+
+    float q0 = (lane < hd) ? q[lane] : 0.f;
+    float q1 = (lane + 64 < hd) ? q[lane + 64] : 0.f;
+    float lmax = -INFINITY;
+    for (int t = wave; t < len; t += 4) {
+        const KT *kt = kc + (size_t)t * hd;
+        float p = 0.f;
+        if (lane < hd) p = q0 * load_as_float(kt, lane);
+        if (lane + 64 < hd) p = fmaf(q1, load_as_float(kt, lane + 64), p);
+        p = wave_sum(p) * scale;
+        if (lane == 0) scores[t] = p;
+        lmax = fmaxf(lmax, p);
+    }
+    if (lane == 0) red[wave] = lmax;
+    __syncthreads();
+    const float mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    float lsum = 0.f;
+    for (int t = threadIdx.x; t < len; t += 256) {
+        float e = expf(scores[t] - mx);
+        scores[t] = e;
+        lsum += e;
+    }
+    lsum = wave_sum(lsum);
+    if (lane == 0) red[4 + wave] = lsum;
+    __syncthreads();
+    const float den = (red[4] + red[5]) + (red[6] + red[7]);
+    // output: thread (part, i) sums its share of positions for dimension i
+    const int nparts = 256 / hd;   // hd 64 -> 4 parts, hd 128 -> 2 parts
+    const int i = threadIdx.x % hd, part = threadIdx.x / hd;
+    float acc = 0.f;
+    if (part < nparts)
+        for (int t = part; t < len; t += nparts) acc = fmaf(scores[t], load_as_float(vc, (size_t)t * hd + i), acc);
+    if (part < 4) outp[part][i] = acc;
+    __syncthreads();
+    if (threadIdx.x < hd) {
+        float s = 0.f;
+        for (int p = 0; p < nparts; ++p) s += outp[p][threadIdx.x];
+        att[(size_t)r * (H * hd) + h * hd + threadIdx.x] = s / den;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// arg-max (lowest index on ties) and top-1 softmax probability of each logits row
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ bool better(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
+
+__global__ __launch_bounds__(1024) void argmax_kernel(const PassCtl *ctl, const float *logits, int V, HeadResult *res) {
+    if (!ctl->active) return;
+    const int r = blockIdx.x;
+    if (r >= ctl->n_rows || r < ctl->head_from) return;
+    __shared__ float sv[16];
+    __shared__ int si[16];
+    __shared__ float ssum[16];
+    const float *row = logits + (size_t)r * V;
+    float bv = -INFINITY; int bi = 0x7fffffff;
+    for (int i = threadIdx.x; i < V; i += 1024) { float v = row[i]; if (better(v, i, bv, bi)) { bv = v; bi = i; } }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        float ov = __shfl_xor(bv, off, 64); int oi = __shfl_xor(bi, off, 64);
+        if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+    }
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) { sv[wave] = bv; si[wave] = bi; }
+    __syncthreads();
+    bv = sv[0]; bi = si[0];
+    for (int w = 1; w < 16; ++w) if (better(sv[w], si[w], bv, bi)) { bv = sv[w]; bi = si[w]; }
+    float s = 0.f;
+    for (int i = threadIdx.x; i < V; i += 1024) s += expf(row[i] - bv);
+    s = wave_sum(s);
+    if (lane == 0) ssum[wave] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float tot = 0.f;
+        for (int w = 0; w < 16; ++w) tot += ssum[w];
+        res->tok[r] = bi;
+        res->prob[r] = 1.0f / tot;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// KNN routing, Eq. 4: score_n = (v . a_n) / |a_n|  (|v| is a common positive factor), then arg-max
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void knn_scores_kernel(const float *__restrict__ query, const float *__restrict__ anchors,
+                                                         int N, int D, float *scores) {
+    const int lane = threadIdx.x & 63;
+    const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int n_waves = (gridDim.x * blockDim.x) >> 6;
+    for (int n = wave; n < N; n += n_waves) {
+        const float *a = anchors + (size_t)n * D;
+        float dot = 0.f, nn = 0.f;
+        for (int k = lane * 4; k < D; k += 256) {
+            float4 av = *reinterpret_cast<const float4 *>(a + k);
+            float4 qv = *reinterpret_cast<const float4 *>(query + k);
+            dot = fmaf(av.x, qv.x, dot); dot = fmaf(av.y, qv.y, dot);
+            dot = fmaf(av.z, qv.z, dot); dot = fmaf(av.w, qv.w, dot);
+            nn = fmaf(av.x, av.x, nn); nn = fmaf(av.y, av.y, nn);
+            nn = fmaf(av.z, av.z, nn); nn = fmaf(av.w, av.w, nn);
+        }
+        dot = wave_sum(dot);
+        nn = wave_sum(nn);
+        // a zero or non-finite anchor norm leaves a NaN score, which the arg-max kernel reports
+        if (lane == 0) scores[n] = (nn > 0.f && isfinite(nn)) ? dot / sqrtf(nn) : NAN;
+    }
+}
+
+__global__ __launch_bounds__(1024) void knn_argmax_kernel(const float *scores, const float *query, const int32_t *labels,
+                                                          int N, int D, KnnResult *res) {
+    __shared__ float sv[16];
+    __shared__ int si[16];
+    __shared__ int bad;
+    __shared__ float qn[16];
+    if (threadIdx.x == 0) bad = 0;
+    __syncthreads();
+    float bv = -INFINITY; int bi = 0x7fffffff; int mybad = 0;
+    for (int i = threadIdx.x; i < N; i += 1024) {
+        float v = scores[i];
+        if (!isfinite(v)) mybad = 1;
+        else if (better(v, i, bv, bi)) { bv = v; bi = i; }
+    }
+    float q2 = 0.f;
+    for (int i = threadIdx.x; i < D; i += 1024) { float v = query[i]; q2 = fmaf(v, v, q2); }
+    q2 = wave_sum(q2);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        float ov = __shfl_xor(bv, off, 64); int oi = __shfl_xor(bi, off, 64);
+        if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+    }
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (mybad) atomicOr(&bad, 1);
+    if (lane == 0) { sv[wave] = bv; si[wave] = bi; qn[wave] = q2; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        bv = sv[0]; bi = si[0];
+        float qtot = qn[0];
+        for (int w = 1; w < 16; ++w) { if (better(sv[w], si[w], bv, bi)) { bv = sv[w]; bi = si[w]; } qtot += qn[w]; }
+        int degenerate = bad || !(qtot > 0.f) || !isfinite(qtot) || bi == 0x7fffffff;
+        res->degenerate = degenerate;
+        res->idx = degenerate ? -1 : bi;
+        res->label = degenerate ? -1 : labels[bi];
+        res->score = bv;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// draft / verify round control (Sec. 4.2), advanced on the device
+// ------------------------------------------------------------------------------------------
+__global__ void gen_init_kernel(GenState *st, int cache_len, int x_last, int max_new, int max_draft, float thr,
+                                int32_t *out_tokens) {
+    st->cache_len = cache_len; st->x_last = x_last; st->emitted = 1; st->max_new = max_new;
+    st->max_draft = max_draft; st->conf_thr = thr; st->kmax = 0; st->k = 0; st->done = (max_new <= 1);
+    st->n_accepted = 0; st->rounds = 0; st->drafted = 0; st->accepted = 0; st->draft_passes = 0;
+    out_tokens[0] = x_last;
+}
+
+__global__ void round_begin_kernel(GenState *st, PassCtl *draft) {
+    int remaining = st->max_new - st->emitted;
+    int kmax = st->done ? 0 : min(st->max_draft, remaining - 1);
+    if (kmax < 0) kmax = 0;
+    st->kmax = kmax; st->k = 0;
+    draft->active = kmax > 0; draft->n_rows = 1; draft->start = st->cache_len; draft->head_from = 0;
+    draft->tok[0] = st->x_last;
+}
+
+__global__ void draft_end_kernel(GenState *st, PassCtl *draft, const HeadResult *res) {
+    if (!draft->active) return;
+    int k = st->k;
+    int d = res->tok[0]; float p = res->prob[0];
+    st->drafts[k] = d; st->draft_p[k] = p;
+    k += 1; st->k = k; st->draft_passes += 1;
+    bool stop = (k >= st->kmax) || (st->conf_thr > 0.f && p < st->conf_thr);
+    draft->active = stop ? 0 : 1;
+    draft->tok[0] = d;
+    draft->start = st->cache_len + k;
+}
+
+__global__ void verify_begin_kernel(const GenState *st, PassCtl *ver) {
+    ver->active = st->done ? 0 : 1;
+    ver->n_rows = st->k + 1; ver->start = st->cache_len; ver->head_from = 0;
+    ver->tok[0] = st->x_last;
+    for (int i = 0; i < st->k; ++i) ver->tok[i + 1] = st->drafts[i];
+}
+
+// Greedy acceptance and rollback: keep the leading drafts that equal the full model's own
+// token, emit the model's next token after them, move the cache length behind the last kept row.
+__global__ void accept_kernel(GenState *st, const HeadResult *res, int32_t *out_tokens) {
+    if (st->done) return;
+    int k = st->k, j = 0;
+    while (j < k && st->drafts[j] == res->tok[j]) ++j;
+    int e = st->emitted;
+    for (int i = 0; i < j; ++i) out_tokens[e + i] = st->drafts[i];
+    out_tokens[e + j] = res->tok[j];
+    st->emitted = e + j + 1;
+    st->cache_len += j + 1;
+    st->x_last = res->tok[j];
+    st->n_accepted = j;
+    st->rounds += 1; st->drafted += k; st->accepted += j;
+    if (st->emitted >= st->max_new) st->done = 1;
+}
+
+// Acceptance for a stand-alone verification call: rows tok[0..n-1] = [x_last, d_1..d_k].
+__global__ void verify_accept_kernel(const PassCtl *ver, const HeadResult *res, int32_t *out3) {
+    int k = ver->n_rows - 1, j = 0;
+    while (j < k && ver->tok[j + 1] == res->tok[j]) ++j;
+    out3[0] = j; out3[1] = res->tok[j]; out3[2] = ver->start + j + 1;
+}
+
+}  // namespace ks

@@ -1,0 +1,562 @@
+// Host side of the KNN-SSD C ABI: argument checks, workspace layout, and the order in which the
+// kernels of a draft step, a verification pass and a generation are put on the stream.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/knnssd.h"
+#include "device_types.h"
+#include "kernels_generic.h"
+
+using namespace ks;
+
+static thread_local char g_hip_err[256] = "no HIP error recorded";
+
+#define HIP_TRY(expr)                                                                              \
+    do {                                                                                           \
+        hipError_t e_ = (expr);                                                                    \
+        if (e_ != hipSuccess) {                                                                    \
+            snprintf(g_hip_err, sizeof(g_hip_err), "%s at %s:%d", hipGetErrorString(e_), __FILE__, __LINE__); \
+            return KNNSSD_EHIP;                                                                    \
+        }                                                                                          \
+    } while (0)
+
+#define KS_TRY(expr)                    \
+    do {                                \
+        int32_t rc_ = (expr);           \
+        if (rc_ != KNNSSD_OK) return rc_; \
+    } while (0)
+
+static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Workspace layout (byte offsets, all 256-byte aligned).
+struct WsLayout {
+    size_t draft_ctl, ver_ctl, gen, head, knn, out3;
+    size_t x, xn, qkv, att, u, logits, hidden_last, rope_cos, rope_sin, knn_scores, out_tokens;
+    size_t total;
+};
+
+static bool cfg_valid(const knnssd_model_cfg *c) {
+    if (!c) return false;
+    if (c->n_blocks < 0 || c->d_model <= 0 || c->n_heads <= 0 || c->n_kv_heads <= 0 || c->head_dim <= 0 ||
+        c->d_ffn <= 0 || c->vocab <= 0 || c->max_seq <= 0 || c->max_anchors < 0)
+        return false;
+    if (c->weight_dtype != KNNSSD_FP32 && c->weight_dtype != KNNSSD_BF16) return false;
+    if (c->kv_dtype != KNNSSD_FP32 && c->kv_dtype != KNNSSD_BF16) return false;
+    if (!(c->rope_base > 0.f) || !(c->rms_eps >= 0.f)) return false;
+    return true;
+}
+
+static bool cfg_supported(const knnssd_model_cfg *c) {
+    if (c->head_dim != 64 && c->head_dim != 128) return false;
+    if (c->n_heads % c->n_kv_heads) return false;
+    if (c->d_model % 8 || c->d_ffn % 8) return false;
+    if (c->max_seq > 15360) return false;  // attention scores of one row are kept in LDS (60 KB)
+    return true;
+}
+
+static WsLayout ws_layout(const knnssd_model_cfg *c) {
+    WsLayout L{};
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    const size_t R = KS_MAX_ROWS;
+    const size_t qkv_dim = (size_t)(c->n_heads + 2 * c->n_kv_heads) * c->head_dim;
+    L.draft_ctl = take(sizeof(PassCtl));
+    L.ver_ctl = take(sizeof(PassCtl));
+    L.gen = take(sizeof(GenState));
+    L.head = take(sizeof(HeadResult));
+    L.knn = take(sizeof(KnnResult));
+    L.out3 = take(4 * sizeof(int32_t));
+    L.x = take(R * c->d_model * 4);
+    L.xn = take(R * c->d_model * 4);
+    L.qkv = take(R * qkv_dim * 4);
+    L.att = take(R * (size_t)c->n_heads * c->head_dim * 4);
+    L.u = take(R * (size_t)c->d_ffn * 4);
+    L.logits = take(R * (size_t)c->vocab * 4);
+    L.hidden_last = take((size_t)c->d_model * 4);
+    L.rope_cos = take((size_t)c->max_seq * (c->head_dim / 2) * 4);
+    L.rope_sin = take((size_t)c->max_seq * (c->head_dim / 2) * 4);
+    L.knn_scores = take((size_t)(c->max_anchors > 0 ? c->max_anchors : 1) * 4);
+    L.out_tokens = take((size_t)c->max_seq * 4);
+    L.total = off;
+    return L;
+}
+
+struct knnssd_ctx {
+    knnssd_model_cfg cfg;
+    WsLayout L;
+    hipStream_t stream;
+    char *ws;
+    char *kv;
+    size_t kv_block_bytes;
+    const void *embed, *lm_head;
+    const float *final_norm;
+    std::vector<const float *> attn_norm, mlp_norm;
+    std::vector<const void *> wqkv, wo, wgu, wdown;
+    // anchors
+    const float *anchors;
+    const int32_t *labels;
+    int32_t n_anchors, n_domains;
+    std::vector<uint8_t> masks;       // [n_domains][2*n_blocks]
+    std::vector<uint8_t> draft_mask;  // installed mask
+    bool prefilled;
+    int32_t cache_len;
+    // pinned host staging for small read-backs
+    int32_t *h_stage;
+    std::vector<hipEvent_t> events;
+
+    template <typename T> T *wsp(size_t off) { return reinterpret_cast<T *>(ws + off); }
+};
+
+extern "C" size_t knnssd_workspace_bytes(const knnssd_model_cfg *cfg) {
+    if (!cfg_valid(cfg) || !cfg_supported(cfg)) return 0;
+    return ws_layout(cfg).total;
+}
+
+extern "C" size_t knnssd_kvcache_bytes(const knnssd_model_cfg *cfg) {
+    if (!cfg_valid(cfg)) return 0;
+    size_t elt = cfg->kv_dtype == KNNSSD_BF16 ? 2 : 4;
+    size_t per_block = align_up((size_t)2 * cfg->n_kv_heads * cfg->max_seq * cfg->head_dim * elt, 256);
+    return per_block * (size_t)(cfg->n_blocks > 0 ? cfg->n_blocks : 1);
+}
+
+extern "C" const char *knnssd_strerror(int32_t code) {
+    switch (code) {
+        case KNNSSD_OK: return "ok";
+        case KNNSSD_EINVAL: return "invalid argument";
+        case KNNSSD_ESHAPE: return "shape not supported";
+        case KNNSSD_ERANGE: return "position, length or token id out of range";
+        case KNNSSD_EDEGENERATE: return "zero-norm or non-finite vector: cosine similarity undefined";
+        case KNNSSD_ESTATE: return "call made in the wrong order";
+        case KNNSSD_EHIP: return g_hip_err;
+        default: return "unknown error code";
+    }
+}
+
+extern "C" int32_t knnssd_create(const knnssd_model_cfg *cfg, const knnssd_weights *w, void *kv_dev, void *ws_dev,
+                                 void *hip_stream, knnssd_ctx **out) {
+    if (!out) return KNNSSD_EINVAL;
+    *out = nullptr;
+    if (!cfg_valid(cfg) || !w || !kv_dev || !ws_dev) return KNNSSD_EINVAL;
+    if (!cfg_supported(cfg)) return KNNSSD_ESHAPE;
+    if (((uintptr_t)kv_dev & 255) || ((uintptr_t)ws_dev & 255)) return KNNSSD_EINVAL;
+    if (!w->embed || !w->lm_head || !w->final_norm) return KNNSSD_EINVAL;
+    const int nb = cfg->n_blocks;
+    if (nb > 0 && (!w->attn_norm || !w->wqkv || !w->wo || !w->mlp_norm || !w->wgu || !w->wdown)) return KNNSSD_EINVAL;
+    for (int b = 0; b < nb; ++b) {
+        if (!w->attn_norm[b] || !w->wqkv[b] || !w->wo[b] || !w->mlp_norm[b] || !w->wgu[b] || !w->wdown[b])
+            return KNNSSD_EINVAL;
+        // 16-byte loads of weight rows
+        if (((uintptr_t)w->wqkv[b] | (uintptr_t)w->wo[b] | (uintptr_t)w->wgu[b] | (uintptr_t)w->wdown[b]) & 15)
+            return KNNSSD_EINVAL;
+    }
+    if (((uintptr_t)w->embed | (uintptr_t)w->lm_head) & 15) return KNNSSD_EINVAL;
+
+    knnssd_ctx *c = new (std::nothrow) knnssd_ctx();
+    if (!c) return KNNSSD_EINVAL;
+    c->cfg = *cfg;
+    c->L = ws_layout(cfg);
+    c->stream = (hipStream_t)hip_stream;
+    c->ws = (char *)ws_dev;
+    c->kv = (char *)kv_dev;
+    c->kv_block_bytes = knnssd_kvcache_bytes(cfg) / (size_t)(nb > 0 ? nb : 1);
+    c->embed = w->embed; c->lm_head = w->lm_head; c->final_norm = w->final_norm;
+    for (int b = 0; b < nb; ++b) {
+        c->attn_norm.push_back(w->attn_norm[b]); c->mlp_norm.push_back(w->mlp_norm[b]);
+        c->wqkv.push_back(w->wqkv[b]); c->wo.push_back(w->wo[b]);
+        c->wgu.push_back(w->wgu[b]); c->wdown.push_back(w->wdown[b]);
+    }
+    c->anchors = nullptr; c->labels = nullptr; c->n_anchors = 0; c->n_domains = 0;
+    c->draft_mask.assign((size_t)2 * nb, 0);
+    c->prefilled = false; c->cache_len = 0;
+    c->h_stage = nullptr;
+    hipError_t e = hipHostMalloc((void **)&c->h_stage, 4096, hipHostMallocDefault);
+    if (e != hipSuccess) {
+        snprintf(g_hip_err, sizeof(g_hip_err), "%s (hipHostMalloc)", hipGetErrorString(e));
+        delete c;
+        return KNNSSD_EHIP;
+    }
+    const int half = cfg->head_dim / 2;
+    const int n = cfg->max_seq * half;
+    hipLaunchKernelGGL(rope_table_kernel, dim3((n + 255) / 256), dim3(256), 0, c->stream, c->wsp<float>(c->L.rope_cos),
+                       c->wsp<float>(c->L.rope_sin), cfg->max_seq, half, cfg->head_dim, (double)cfg->rope_base);
+    e = hipGetLastError();
+    if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+    if (e != hipSuccess) {
+        snprintf(g_hip_err, sizeof(g_hip_err), "%s (rope table)", hipGetErrorString(e));
+        hipHostFree(c->h_stage);
+        delete c;
+        return KNNSSD_EHIP;
+    }
+    *out = c;
+    return KNNSSD_OK;
+}
+
+extern "C" int32_t knnssd_destroy(knnssd_ctx *ctx) {
+    if (!ctx) return KNNSSD_EINVAL;
+    hipStreamSynchronize(ctx->stream);
+    for (hipEvent_t ev : ctx->events) hipEventDestroy(ev);
+    if (ctx->h_stage) hipHostFree(ctx->h_stage);
+    delete ctx;
+    return KNNSSD_OK;
+}
+
+extern "C" int32_t knnssd_set_anchors(knnssd_ctx *ctx, const float *anchors_dev, const int32_t *labels_dev,
+                                      int32_t n_anchors, int32_t dim, const uint8_t *masks_host, int32_t n_domains) {
+    if (!ctx || !anchors_dev || !labels_dev || !masks_host) return KNNSSD_EINVAL;
+    if (n_anchors <= 0 || n_domains <= 0) return KNNSSD_EINVAL;
+    if (dim != ctx->cfg.d_model) return KNNSSD_ESHAPE;
+    if (n_anchors > ctx->cfg.max_anchors) return KNNSSD_ERANGE;
+    if ((uintptr_t)anchors_dev & 15) return KNNSSD_EINVAL;
+    const size_t ml = (size_t)2 * ctx->cfg.n_blocks;
+    for (size_t i = 0; i < ml * n_domains; ++i)
+        if (masks_host[i] > 1) return KNNSSD_EINVAL;
+    ctx->anchors = anchors_dev; ctx->labels = labels_dev;
+    ctx->n_anchors = n_anchors; ctx->n_domains = n_domains;
+    ctx->masks.assign(masks_host, masks_host + ml * n_domains);
+    return KNNSSD_OK;
+}
+
+extern "C" int32_t knnssd_set_skipset(knnssd_ctx *ctx, const uint8_t *mask_host) {
+    if (!ctx) return KNNSSD_EINVAL;
+    const size_t ml = (size_t)2 * ctx->cfg.n_blocks;
+    if (!mask_host) { ctx->draft_mask.assign(ml, 0); return KNNSSD_OK; }
+    for (size_t i = 0; i < ml; ++i)
+        if (mask_host[i] > 1) return KNNSSD_EINVAL;
+    ctx->draft_mask.assign(mask_host, mask_host + ml);
+    return KNNSSD_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// one forward pass: every retained sublayer in order, then the head
+// ------------------------------------------------------------------------------------------
+template <typename WT, int MR>
+static void launch_gemm(knnssd_ctx *c, const PassCtl *ctl, int epi, const void *W, const void *W2, const float *X, int ldx,
+                        float *Y, int ldy, int N, int K, int use_head_from) {
+    int wgs = (N + 3) / 4;
+    if (wgs > 2048) wgs = 2048;
+    const WT *w = (const WT *)W, *w2 = (const WT *)W2;
+    if (epi == EPI_STORE)
+        hipLaunchKernelGGL((gemm_rows_kernel<WT, MR, EPI_STORE>), dim3(wgs), dim3(256), 0, c->stream, ctl, w, w2, X, ldx, Y, ldy, N, K, use_head_from);
+    else if (epi == EPI_RESID)
+        hipLaunchKernelGGL((gemm_rows_kernel<WT, MR, EPI_RESID>), dim3(wgs), dim3(256), 0, c->stream, ctl, w, w2, X, ldx, Y, ldy, N, K, use_head_from);
+    else
+        hipLaunchKernelGGL((gemm_rows_kernel<WT, MR, EPI_SWIGLU>), dim3(wgs), dim3(256), 0, c->stream, ctl, w, w2, X, ldx, Y, ldy, N, K, use_head_from);
+}
+
+template <typename WT, typename KT, int MR>
+static int32_t run_pass_t(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask) {
+    const knnssd_model_cfg &g = c->cfg;
+    const int d = g.d_model, H = g.n_heads, Hkv = g.n_kv_heads, hd = g.head_dim, F = g.d_ffn;
+    const int qd = H * hd, qkvd = (H + 2 * Hkv) * hd;
+    float *x = c->wsp<float>(c->L.x), *xn = c->wsp<float>(c->L.xn), *qkv = c->wsp<float>(c->L.qkv);
+    float *att = c->wsp<float>(c->L.att), *u = c->wsp<float>(c->L.u), *logits = c->wsp<float>(c->L.logits);
+    const float *cos_t = c->wsp<float>(c->L.rope_cos), *sin_t = c->wsp<float>(c->L.rope_sin);
+    hipStream_t s = c->stream;
+    const int rows = MR;  // grid rows; kernels drop rows >= n_rows
+
+    hipLaunchKernelGGL((embed_kernel<WT>), dim3(rows), dim3(256), 0, s, ctl, (const WT *)c->embed, x, d);
+    for (int b = 0; b < g.n_blocks; ++b) {
+        KT *kvb = (KT *)(c->kv + (size_t)b * c->kv_block_bytes);
+        if (!(mask && mask[2 * b])) {
+            hipLaunchKernelGGL(rmsnorm_kernel, dim3(rows), dim3(256), 0, s, ctl, x, c->attn_norm[b], xn, d, g.rms_eps);
+            launch_gemm<WT, MR>(c, ctl, EPI_STORE, c->wqkv[b], nullptr, xn, d, qkv, qkvd, qkvd, d, 0);
+            hipLaunchKernelGGL((rope_kv_kernel<KT>), dim3(rows), dim3(256), 0, s, ctl, qkv, kvb, cos_t, sin_t, H, Hkv, hd, g.max_seq);
+            hipLaunchKernelGGL((attention_kernel<KT>), dim3(H, rows), dim3(256), (size_t)g.max_seq * 4, s, ctl, qkv, kvb, att, H, Hkv, hd, g.max_seq);
+            launch_gemm<WT, MR>(c, ctl, EPI_RESID, c->wo[b], nullptr, att, qd, x, d, d, qd, 0);
+        }
+        if (!(mask && mask[2 * b + 1])) {
+            hipLaunchKernelGGL(rmsnorm_kernel, dim3(rows), dim3(256), 0, s, ctl, x, c->mlp_norm[b], xn, d, g.rms_eps);
+            const WT *wg = (const WT *)c->wgu[b];
+            launch_gemm<WT, MR>(c, ctl, EPI_SWIGLU, wg, wg + (size_t)F * d, xn, d, u, F, F, d, 0);
+            launch_gemm<WT, MR>(c, ctl, EPI_RESID, c->wdown[b], nullptr, u, F, x, d, d, F, 0);
+        }
+    }
+    hipLaunchKernelGGL(rmsnorm_kernel, dim3(rows), dim3(256), 0, s, ctl, x, c->final_norm, xn, d, g.rms_eps);
+    launch_gemm<WT, MR>(c, ctl, EPI_STORE, c->lm_head, nullptr, xn, d, logits, g.vocab, g.vocab, d, 1);
+    hipLaunchKernelGGL(argmax_kernel, dim3(rows), dim3(1024), 0, s, ctl, logits, g.vocab, c->wsp<HeadResult>(c->L.head));
+    HIP_TRY(hipGetLastError());
+    return KNNSSD_OK;
+}
+
+// mr: 1 for a draft step, KS_MAX_ROWS for verification / prefill
+static int32_t run_pass(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, int mr) {
+    const bool wb = c->cfg.weight_dtype == KNNSSD_BF16, kb = c->cfg.kv_dtype == KNNSSD_BF16;
+    if (mr == 1) {
+        if (wb && kb) return run_pass_t<bf16_t, bf16_t, 1>(c, ctl, mask);
+        if (wb && !kb) return run_pass_t<bf16_t, float, 1>(c, ctl, mask);
+        if (!wb && kb) return run_pass_t<float, bf16_t, 1>(c, ctl, mask);
+        return run_pass_t<float, float, 1>(c, ctl, mask);
+    }
+    if (wb && kb) return run_pass_t<bf16_t, bf16_t, KS_MAX_ROWS>(c, ctl, mask);
+    if (wb && !kb) return run_pass_t<bf16_t, float, KS_MAX_ROWS>(c, ctl, mask);
+    if (!wb && kb) return run_pass_t<float, bf16_t, KS_MAX_ROWS>(c, ctl, mask);
+    return run_pass_t<float, float, KS_MAX_ROWS>(c, ctl, mask);
+}
+
+static int32_t set_pass(knnssd_ctx *c, PassCtl *ctl, int active, int n_rows, int start, int head_from, const int32_t *toks) {
+    TokArgs ta;
+    for (int i = 0; i < KS_MAX_ROWS; ++i) ta.t[i] = (i < n_rows) ? toks[i] : 0;
+    hipLaunchKernelGGL(set_pass_kernel, dim3(1), dim3(64), 0, c->stream, ctl, active, n_rows, start, head_from, ta);
+    HIP_TRY(hipGetLastError());
+    return KNNSSD_OK;
+}
+
+// copy `bytes` from device to the pinned staging area and wait for it
+static int32_t read_back(knnssd_ctx *c, const void *dev, size_t bytes) {
+    HIP_TRY(hipMemcpyAsync(c->h_stage, dev, bytes, hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(hipStreamSynchronize(c->stream));
+    return KNNSSD_OK;
+}
+
+static int32_t prefill_impl(knnssd_ctx *c, const int32_t *tokens, int32_t n, float *last_hidden_dev, int32_t *first_token) {
+    PassCtl *ver = c->wsp<PassCtl>(c->L.ver_ctl);
+    for (int s = 0; s < n; s += KS_MAX_ROWS) {
+        int rows = n - s < KS_MAX_ROWS ? n - s : KS_MAX_ROWS;
+        bool last = s + rows >= n;
+        KS_TRY(set_pass(c, ver, 1, rows, s, last ? rows - 1 : rows, tokens + s));
+        KS_TRY(run_pass(c, ver, nullptr, KS_MAX_ROWS));
+        if (last) {
+            const float *xn_last = c->wsp<float>(c->L.xn) + (size_t)(rows - 1) * c->cfg.d_model;
+            HIP_TRY(hipMemcpyAsync(c->wsp<float>(c->L.hidden_last), xn_last, (size_t)c->cfg.d_model * 4,
+                                   hipMemcpyDeviceToDevice, c->stream));
+            if (last_hidden_dev)
+                HIP_TRY(hipMemcpyAsync(last_hidden_dev, xn_last, (size_t)c->cfg.d_model * 4, hipMemcpyDeviceToDevice, c->stream));
+            KS_TRY(read_back(c, &c->wsp<HeadResult>(c->L.head)->tok[rows - 1], 4));
+            *first_token = c->h_stage[0];
+        }
+    }
+    c->prefilled = true;
+    c->cache_len = n;
+    return KNNSSD_OK;
+}
+
+static int32_t check_tokens(const knnssd_ctx *c, const int32_t *t, int32_t n) {
+    for (int i = 0; i < n; ++i)
+        if (t[i] < 0 || t[i] >= c->cfg.vocab) return KNNSSD_ERANGE;
+    return KNNSSD_OK;
+}
+
+extern "C" int32_t knnssd_prefill(knnssd_ctx *ctx, const int32_t *tokens_host, int32_t n, float *last_hidden_dev,
+                                  int32_t *first_token_out) {
+    if (!ctx || !tokens_host || !first_token_out) return KNNSSD_EINVAL;
+    if (n <= 0 || n > ctx->cfg.max_seq) return KNNSSD_ERANGE;
+    KS_TRY(check_tokens(ctx, tokens_host, n));
+    return prefill_impl(ctx, tokens_host, n, last_hidden_dev, first_token_out);
+}
+
+static int32_t select_impl(knnssd_ctx *c, const float *query_dev, int32_t *idx_out, int32_t *dom_out) {
+    const int N = c->n_anchors, D = c->cfg.d_model;
+    int wgs = (N + 3) / 4;
+    if (wgs > 1024) wgs = 1024;
+    float *scores = c->wsp<float>(c->L.knn_scores);
+    KnnResult *res = c->wsp<KnnResult>(c->L.knn);
+    hipLaunchKernelGGL(knn_scores_kernel, dim3(wgs), dim3(256), 0, c->stream, query_dev, c->anchors, N, D, scores);
+    hipLaunchKernelGGL(knn_argmax_kernel, dim3(1), dim3(1024), 0, c->stream, scores, query_dev, c->labels, N, D, res);
+    HIP_TRY(hipGetLastError());
+    KS_TRY(read_back(c, res, sizeof(KnnResult)));
+    KnnResult r;
+    memcpy(&r, c->h_stage, sizeof(r));
+    if (r.degenerate) return KNNSSD_EDEGENERATE;
+    if (r.label < 0 || r.label >= c->n_domains) return KNNSSD_ERANGE;
+    const size_t ml = (size_t)2 * c->cfg.n_blocks;
+    c->draft_mask.assign(c->masks.begin() + ml * r.label, c->masks.begin() + ml * (r.label + 1));
+    *idx_out = r.idx;
+    *dom_out = r.label;
+    return KNNSSD_OK;
+}
+
+extern "C" int32_t knnssd_select_skipset(knnssd_ctx *ctx, const float *query_dev, int32_t *anchor_idx_out,
+                                         int32_t *domain_out, uint8_t *mask_out) {
+    if (!ctx || !query_dev) return KNNSSD_EINVAL;
+    if (!ctx->anchors) return KNNSSD_ESTATE;
+    if ((uintptr_t)query_dev & 15) return KNNSSD_EINVAL;
+    int32_t idx = -1, dom = -1;
+    KS_TRY(select_impl(ctx, query_dev, &idx, &dom));
+    if (anchor_idx_out) *anchor_idx_out = idx;
+    if (domain_out) *domain_out = dom;
+    if (mask_out) memcpy(mask_out, ctx->draft_mask.data(), ctx->draft_mask.size());
+    return KNNSSD_OK;
+}
+
+extern "C" int32_t knnssd_draft_step(knnssd_ctx *ctx, int32_t token_in, int32_t pos, int32_t *token_out,
+                                     float *top1_prob_out) {
+    if (!ctx || !token_out) return KNNSSD_EINVAL;
+    if (!ctx->prefilled) return KNNSSD_ESTATE;
+    if (pos < 0 || pos >= ctx->cfg.max_seq) return KNNSSD_ERANGE;
+    if (token_in < 0 || token_in >= ctx->cfg.vocab) return KNNSSD_ERANGE;
+    PassCtl *dr = ctx->wsp<PassCtl>(ctx->L.draft_ctl);
+    KS_TRY(set_pass(ctx, dr, 1, 1, pos, 0, &token_in));
+    KS_TRY(run_pass(ctx, dr, ctx->draft_mask.data(), 1));
+    KS_TRY(read_back(ctx, ctx->wsp<HeadResult>(ctx->L.head), sizeof(HeadResult)));
+    HeadResult hr;
+    memcpy(&hr, ctx->h_stage, sizeof(hr));
+    *token_out = hr.tok[0];
+    if (top1_prob_out) *top1_prob_out = hr.prob[0];
+    return KNNSSD_OK;
+}
+
+extern "C" int32_t knnssd_verify(knnssd_ctx *ctx, const int32_t *tokens_host, int32_t n, int32_t start_pos,
+                                 int32_t *n_accepted_out, int32_t *next_token_out, int32_t *new_cache_len_out) {
+    if (!ctx || !tokens_host || !n_accepted_out || !next_token_out) return KNNSSD_EINVAL;
+    if (!ctx->prefilled) return KNNSSD_ESTATE;
+    if (n <= 0 || n > KS_MAX_ROWS) return KNNSSD_ERANGE;
+    if (start_pos < 0 || start_pos + n > ctx->cfg.max_seq) return KNNSSD_ERANGE;
+    KS_TRY(check_tokens(ctx, tokens_host, n));
+    PassCtl *ver = ctx->wsp<PassCtl>(ctx->L.ver_ctl);
+    KS_TRY(set_pass(ctx, ver, 1, n, start_pos, 0, tokens_host));
+    KS_TRY(run_pass(ctx, ver, nullptr, KS_MAX_ROWS));
+    int32_t *out3 = ctx->wsp<int32_t>(ctx->L.out3);
+    hipLaunchKernelGGL(verify_accept_kernel, dim3(1), dim3(1), 0, ctx->stream, ver, ctx->wsp<HeadResult>(ctx->L.head), out3);
+    HIP_TRY(hipGetLastError());
+    KS_TRY(read_back(ctx, out3, 12));
+    *n_accepted_out = ctx->h_stage[0];
+    *next_token_out = ctx->h_stage[1];
+    if (new_cache_len_out) *new_cache_len_out = ctx->h_stage[2];
+    ctx->cache_len = ctx->h_stage[2];
+    return KNNSSD_OK;
+}
+
+static int32_t get_event(knnssd_ctx *c, size_t i, hipEvent_t *ev) {
+    while (c->events.size() <= i) {
+        hipEvent_t e;
+        HIP_TRY(hipEventCreate(&e));
+        c->events.push_back(e);
+    }
+    *ev = c->events[i];
+    return KNNSSD_OK;
+}
+
+static int32_t mark(knnssd_ctx *c, size_t i) {
+    hipEvent_t ev;
+    KS_TRY(get_event(c, i, &ev));
+    HIP_TRY(hipEventRecord(ev, c->stream));
+    return KNNSSD_OK;
+}
+
+static int64_t elapsed_ns(knnssd_ctx *c, size_t a, size_t b) {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, c->events[a], c->events[b]) != hipSuccess) return 0;
+    return (int64_t)((double)ms * 1e6);
+}
+
+extern "C" int32_t knnssd_generate(knnssd_ctx *ctx, const int32_t *prompt_host, int32_t n_prompt, const float *query_dev,
+                                   const knnssd_gen_cfg *gen, int32_t *out_tokens_host, int32_t *n_out, knnssd_stats *stats) {
+    if (!ctx || !prompt_host || !gen || !out_tokens_host || !n_out) return KNNSSD_EINVAL;
+    if (n_prompt <= 0 || gen->max_new <= 0) return KNNSSD_ERANGE;
+    if (gen->max_draft < 0 || gen->max_draft > KS_MAX_ROWS - 1) return KNNSSD_ERANGE;
+    if ((int64_t)n_prompt + gen->max_new + gen->max_draft > ctx->cfg.max_seq) return KNNSSD_ERANGE;
+    if (query_dev && ((uintptr_t)query_dev & 15)) return KNNSSD_EINVAL;
+    KS_TRY(check_tokens(ctx, prompt_host, n_prompt));
+
+    size_t ev = 0;
+    KS_TRY(mark(ctx, ev++));  // 0
+    int32_t first = 0;
+    KS_TRY(prefill_impl(ctx, prompt_host, n_prompt, nullptr, &first));
+    KS_TRY(mark(ctx, ev++));  // 1
+    if (ctx->anchors && gen->max_draft > 0) {
+        int32_t idx, dom;
+        KS_TRY(select_impl(ctx, query_dev ? query_dev : ctx->wsp<float>(ctx->L.hidden_last), &idx, &dom));
+    }
+    KS_TRY(mark(ctx, ev++));  // 2
+
+    GenState *st = ctx->wsp<GenState>(ctx->L.gen);
+    PassCtl *dr = ctx->wsp<PassCtl>(ctx->L.draft_ctl), *ver = ctx->wsp<PassCtl>(ctx->L.ver_ctl);
+    HeadResult *head = ctx->wsp<HeadResult>(ctx->L.head);
+    int32_t *out_dev = ctx->wsp<int32_t>(ctx->L.out_tokens);
+    hipStream_t s = ctx->stream;
+    hipLaunchKernelGGL(gen_init_kernel, dim3(1), dim3(1), 0, s, st, n_prompt, first, gen->max_new, gen->max_draft,
+                       gen->conf_threshold, out_dev);
+    int64_t n_draft_passes = 0, n_verify_passes = 0;
+    std::vector<size_t> round_ev;  // triples of event indices
+    bool done = gen->max_new <= 1;
+    while (!done) {
+        hipLaunchKernelGGL(round_begin_kernel, dim3(1), dim3(1), 0, s, st, dr);
+        size_t ea = ev++;
+        KS_TRY(mark(ctx, ea));
+        for (int i = 0; i < gen->max_draft; ++i) {
+            KS_TRY(run_pass(ctx, dr, ctx->draft_mask.data(), 1));
+            hipLaunchKernelGGL(draft_end_kernel, dim3(1), dim3(1), 0, s, st, dr, head);
+            ++n_draft_passes;
+            // the host decides whether to enqueue another draft pass
+            KS_TRY(read_back(ctx, &dr->active, 4));
+            if (!ctx->h_stage[0]) break;
+        }
+        size_t eb = ev++;
+        KS_TRY(mark(ctx, eb));
+        hipLaunchKernelGGL(verify_begin_kernel, dim3(1), dim3(1), 0, s, st, ver);
+        KS_TRY(run_pass(ctx, ver, nullptr, KS_MAX_ROWS));
+        hipLaunchKernelGGL(accept_kernel, dim3(1), dim3(1), 0, s, st, head, out_dev);
+        ++n_verify_passes;
+        size_t ec = ev++;
+        KS_TRY(mark(ctx, ec));
+        round_ev.push_back(ea); round_ev.push_back(eb); round_ev.push_back(ec);
+        KS_TRY(read_back(ctx, &st->done, 4));
+        done = ctx->h_stage[0] != 0;
+    }
+    size_t e_end = ev++;
+    KS_TRY(mark(ctx, e_end));
+    KS_TRY(read_back(ctx, st, sizeof(GenState)));
+    GenState hs;
+    memcpy(&hs, ctx->h_stage, sizeof(hs));
+    const int32_t emitted = hs.emitted < gen->max_new ? hs.emitted : gen->max_new;
+    HIP_TRY(hipMemcpyAsync(out_tokens_host, out_dev, (size_t)emitted * 4, hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    *n_out = emitted;
+    ctx->cache_len = hs.cache_len;
+    if (stats) {
+        memset(stats, 0, sizeof(*stats));
+        stats->rounds = hs.rounds; stats->drafted = hs.drafted; stats->accepted = hs.accepted; stats->emitted = emitted;
+        stats->ns_prefill = elapsed_ns(ctx, 0, 1);
+        stats->ns_knn = elapsed_ns(ctx, 1, 2);
+        for (size_t i = 0; i + 3 <= round_ev.size(); i += 3) {
+            stats->ns_draft += elapsed_ns(ctx, round_ev[i], round_ev[i + 1]);
+            stats->ns_verify += elapsed_ns(ctx, round_ev[i + 1], round_ev[i + 2]);
+        }
+        stats->ns_total = elapsed_ns(ctx, 0, e_end);
+        stats->draft_passes = n_draft_passes; stats->verify_passes = n_verify_passes;
+    }
+    return KNNSSD_OK;
+}
+
+extern "C" int32_t knnssd_get_logits(knnssd_ctx *ctx, int32_t row, float *logits_host) {
+    if (!ctx || !logits_host) return KNNSSD_EINVAL;
+    if (row < 0 || row >= KS_MAX_ROWS) return KNNSSD_ERANGE;
+    const float *src = ctx->wsp<float>(ctx->L.logits) + (size_t)row * ctx->cfg.vocab;
+    HIP_TRY(hipMemcpyAsync(logits_host, src, (size_t)ctx->cfg.vocab * 4, hipMemcpyDeviceToHost, ctx->stream));
+    HIP_TRY(hipStreamSynchronize(ctx->stream));
+    return KNNSSD_OK;
+}
+
+extern "C" int32_t knnssd_read_kv(knnssd_ctx *ctx, int32_t block, int32_t pos, float *k_host, float *v_host) {
+    if (!ctx || !k_host || !v_host) return KNNSSD_EINVAL;
+    const knnssd_model_cfg &g = ctx->cfg;
+    if (block < 0 || block >= g.n_blocks || pos < 0 || pos >= g.max_seq) return KNNSSD_ERANGE;
+    const size_t elt = g.kv_dtype == KNNSSD_BF16 ? 2 : 4;
+    std::vector<char> tmp((size_t)g.head_dim * elt);
+    HIP_TRY(hipStreamSynchronize(ctx->stream));
+    for (int kv = 0; kv < 2; ++kv) {
+        float *dst = kv ? v_host : k_host;
+        for (int h = 0; h < g.n_kv_heads; ++h) {
+            const char *src = ctx->kv + (size_t)block * ctx->kv_block_bytes +
+                              ((((size_t)kv * g.n_kv_heads + h) * g.max_seq + pos) * g.head_dim) * elt;
+            HIP_TRY(hipMemcpy(tmp.data(), src, tmp.size(), hipMemcpyDeviceToHost));
+            for (int i = 0; i < g.head_dim; ++i) {
+                if (elt == 4) {
+                    memcpy(&dst[h * g.head_dim + i], tmp.data() + 4 * i, 4);
+                } else {
+                    uint16_t b;
+                    memcpy(&b, tmp.data() + 2 * i, 2);
+                    uint32_t u = (uint32_t)b << 16;
+                    memcpy(&dst[h * g.head_dim + i], &u, 4);
+                }
+            }
+        }
+    }
+    return KNNSSD_OK;
+}

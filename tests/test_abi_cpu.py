@@ -1,0 +1,56 @@
+"""Host-only checks of the C ABI: the library loads without a GPU, exports every symbol the
+header declares, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2505_16162_amd import binding, synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2505_16162_amd.build import build_library
+        build_library()
+    return binding.load_library()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "knnssd.h")).read()
+    declared = set(re.findall(r"\b(knnssd_[a-z_0-9]+)\s*\(", header))
+    assert declared == set(binding.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_size_queries_and_shape_checks(lib):
+    wl = synth.workload("llama13b")
+    cfg = binding.make_cfg(wl.shape, 1000)
+    kv = lib.knnssd_kvcache_bytes(ctypes.byref(cfg))
+    # 40 blocks x (K and V) x 40 heads x 1552 positions x 128 x 2 bytes
+    assert kv == 40 * 2 * 40 * wl.shape.max_seq * 128 * 2
+    assert lib.knnssd_workspace_bytes(ctypes.byref(cfg)) > 16 * 32000 * 4
+    assert lib.knnssd_workspace_bytes(None) == 0
+    bad = binding.make_cfg(synth.small_shape("x", head_dim=48), 0)
+    assert lib.knnssd_workspace_bytes(ctypes.byref(bad)) == 0
+    bad2 = binding.make_cfg(synth.small_shape("x", n_heads=4, n_kv_heads=3), 0)
+    assert lib.knnssd_workspace_bytes(ctypes.byref(bad2)) == 0
+
+
+def test_null_arguments_are_rejected_without_a_device(lib):
+    h = ctypes.c_void_p()
+    cfg = binding.make_cfg(synth.workload("tiny").shape, 8)
+    w = binding.Weights()
+    assert lib.knnssd_create(ctypes.byref(cfg), ctypes.byref(w), None, None, None, ctypes.byref(h)) == -1
+    assert lib.knnssd_create(None, None, None, None, None, ctypes.byref(h)) == -1
+    assert lib.knnssd_destroy(None) == -1
+    assert lib.knnssd_set_skipset(None, None) == -1
+    assert lib.knnssd_draft_step(None, 0, 0, None, None) == -1
+    assert lib.knnssd_verify(None, None, 0, 0, None, None, None) == -1
+    assert lib.knnssd_generate(None, None, 0, None, None, None, None, None) == -1
+    assert lib.knnssd_strerror(-3).decode().startswith("position")
+    assert lib.knnssd_strerror(0).decode() == "ok"
