@@ -1,0 +1,187 @@
+#!/usr/bin/env python3
+"""Benchmark of the KNN-SSD decode path on one MI355X.
+
+One "step" is one pass of the whole per-sample path over one synthetic sample: prefill of the
+prompt, KNN routing of its last hidden vector, then draft/verify rounds until max_new tokens
+are out. The default workload is the 13B-shaped configuration; weights are seeded random-init
+values of that shape (there are no checkpoints here), generated directly in HBM.
+
+Prints ONE JSON line. `value` is decoded tokens per second of KNN-SSD (tokens emitted after the
+prefill's own token, divided by the GPU time of KNN routing plus all draft and verify passes;
+inputs resident in HBM). The plain autoregressive baseline, the prefill time, the acceptance
+counters and the end-to-end rate are reported beside it, as are the roofline figures of the
+verify pass and the draft pass and the CPU oracle's rate on a bounded sample.
+
+On seeded random-init weights the top-1 probability is far below the 0.6 confidence threshold,
+so every round drafts one token, and acceptance is whatever random weights give: the SSD/AR
+ratio here says nothing about the paper's 1.3-1.6x, which needs trained weights.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def pass_bytes(shape, mask, ctx, rows):
+    """Algorithmic HBM bytes of one forward pass: weights of the retained sublayers and the LM
+    head, the cached keys/values the retained attention sublayers read at context length ctx,
+    the keys/values they write and one embedding row per input row."""
+    wb = 2 if shape.weight_dtype == "bf16" else 4
+    kb = 2 if shape.kv_dtype == "bf16" else 4
+    d, f = shape.d_model, shape.d_ffn
+    qd, kvd = shape.n_heads * shape.head_dim, shape.n_kv_heads * shape.head_dim
+    attn_w = ((qd + 2 * kvd) * d + d * qd) * wb
+    mlp_w = (3 * f * d) * wb
+    total = shape.vocab * d * wb + rows * d * wb
+    for b in range(shape.n_blocks):
+        if not mask[2 * b]:
+            total += attn_w + 2 * kvd * kb * (ctx + rows)
+        if not mask[2 * b + 1]:
+            total += mlp_w
+    return total
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="llama13b")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-tokens", type=int, default=6, help="tokens the CPU oracle decodes for its baseline")
+    ap.add_argument("--max-new", type=int, default=0, help="override the workload's generation length")
+    ap.add_argument("--prompt-len", type=int, default=0, help="override the workload's prompt length")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is a single-GPU path; run with --gpus 1 "
+              "(independent samples would shard round-robin over GPUs with no communication)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2505_16162_amd import binding, synth
+
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2505_16162_amd.build import build_library
+        build_library()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    wl = synth.workload(args.workload)
+    shape = wl.shape
+    max_new = args.max_new or wl.max_new
+    prompt_len = args.prompt_len or wl.prompt_len
+
+    t0 = time.time()
+    w = synth.make_weights(shape, device=dev)
+    gpu = binding.KnnSsd(shape, w, max_anchors=wl.n_anchors)
+    anchors, labels, centres = synth.make_anchors(shape.d_model, wl.n_anchors, wl.n_domains, wl.anchor_sigma,
+                                                  device=dev, clustered=wl.n_domains < wl.n_anchors)
+    masks = synth.make_block_masks(shape.n_blocks, wl.n_domains, wl.skipped_blocks)
+    gpu.knnssd_set_anchors(anchors, labels, masks)
+    prompt = synth.make_prompt(shape.vocab, prompt_len).tolist()
+    torch.cuda.synchronize()
+    t_setup = time.time() - t0
+
+    def one_step():
+        return gpu.knnssd_generate(prompt, max_new, wl.max_draft, wl.conf_threshold)
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+    t1 = time.time()
+    agg = None
+    toks = None
+    for _ in range(args.steps):
+        toks, st = one_step()
+        agg = st if agg is None else {k: agg[k] + v for k, v in st.items()}
+    torch.cuda.synchronize()
+    wall = time.time() - t1
+    ms_per_step = wall * 1e3 / args.steps
+
+    decode_ns = agg["ns_knn"] + agg["ns_draft"] + agg["ns_verify"]
+    new_tokens = agg["emitted"] - args.steps           # the first token of each step is the prefill's
+    ssd_tps = new_tokens / (decode_ns * 1e-9)
+    e2e_tps = agg["emitted"] / wall
+
+    # plain autoregressive baseline through the same entry point (max_draft = 0), same prompt
+    ar_toks, ar_st = gpu.knnssd_generate(prompt, max_new, 0)
+    ar_tps = (ar_st["emitted"] - 1) / (ar_st["ns_verify"] * 1e-9)
+    lossless = ar_toks == toks
+
+    # roofline of the two passes at the mean context of the run
+    idx, dom, mask = gpu.knnssd_select_skipset(gpu.knnssd_prefill(prompt)[1])
+    ctx_mean = prompt_len + max_new // 2
+    full = [0] * (2 * shape.n_blocks)
+    verify_rows = (agg["drafted"] / max(agg["rounds"], 1)) + 1
+    vb = pass_bytes(shape, full, ctx_mean, verify_rows)
+    db = pass_bytes(shape, mask, ctx_mean, 1)
+    verify_ms = agg["ns_verify"] * 1e-6 / max(agg["verify_passes"], 1)
+    draft_ms = agg["ns_draft"] * 1e-6 / max(agg["draft_passes"], 1)
+    verify_gbs = vb / (verify_ms * 1e-3) / 1e9
+    draft_gbs = db / (draft_ms * 1e-3) / 1e9 if agg["draft_passes"] else 0.0
+
+    out = {
+        "metric": "decoded tokens/s at batch 1 (KNN-SSD)", "value": round(ssd_tps, 3), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 weights/KV, f32 activations" if shape.weight_dtype == "bf16" else "f32",
+        "data": "synthetic (seeded random-init weights, uniform random prompt, Gaussian anchor clusters)",
+        "config": {"workload": f"{shape.name}: {shape.n_blocks} blocks d={shape.d_model} H={shape.n_heads}/"
+                               f"{shape.n_kv_heads} ffn={shape.d_ffn} V={shape.vocab}; batch 1, prompt {prompt_len}, "
+                               f"generate {max_new}, max_draft {wl.max_draft}, conf_thr {wl.conf_threshold}, "
+                               f"{wl.skipped_blocks}-block skip masks from 1-NN over {wl.n_anchors} anchors"},
+        "ar_tokens_per_s": round(ar_tps, 3),
+        "ssd_over_ar": round(ssd_tps / ar_tps, 4),
+        "ssd_equals_ar_tokens": bool(lossless),
+        "e2e_tokens_per_s_incl_prefill": round(e2e_tps, 3),
+        "prefill_ms": round(agg["ns_prefill"] * 1e-6 / args.steps, 3),
+        "knn_us": round(agg["ns_knn"] * 1e-3 / args.steps, 2),
+        "mean_generated_length_M": round((agg["emitted"] - args.steps) / max(agg["rounds"], 1), 4),
+        "acceptance_rate_alpha": round(agg["accepted"] / max(agg["drafted"], 1), 4),
+        "drafts_per_round": round(agg["drafted"] / max(agg["rounds"], 1), 3),
+        "verify_pass": {"ms": round(verify_ms, 4), "GB": round(vb / 1e9, 3), "GBps": round(verify_gbs, 1),
+                        "frac_of_peak": round(verify_gbs / HBM_PEAK_GBS, 4)},
+        "draft_pass": {"ms": round(draft_ms, 4), "GB": round(db / 1e9, 3), "GBps": round(draft_gbs, 1),
+                       "frac_of_peak": round(draft_gbs / HBM_PEAK_GBS, 4)},
+        "roofline": {"bound": "hbm", "kernel": "verify pass (full model, weights streamed once for all rows)",
+                     "achieved": round(verify_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(verify_gbs / HBM_PEAK_GBS, 4), "traffic": None},
+        "setup_s": round(t_setup, 1),
+    }
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(shape, w, wl, mask, args.cpu_tokens)
+    print(json.dumps(out))
+    gpu.close()
+
+
+def cpu_baseline(shape, w_dev, wl, mask, n_tokens):
+    """The oracle as it stands, timed on this machine's host cores on a bounded sample: same model
+    and weights, a 16-token prompt, n_tokens decoded by Self-SD rounds with the routed mask."""
+    import numpy as np
+    from oracle import knnssd_oracle as O
+    from paper_2505_16162_amd import synth
+    w_host = synth.weights_to(w_dev, "cpu")
+    prompt = synth.make_prompt(shape.vocab, 16, seed=77).tolist()
+    model = O.OracleModel(shape, w_host)
+    t0 = time.time()
+    first = O.prefill(model, prompt)[0]
+    t_prefill = time.time() - t0
+    t0 = time.time()
+    toks, st, _ = O.ssd_generate(model, prompt, np.asarray(mask, np.uint8), n_tokens + 1, wl.max_draft,
+                                 wl.conf_threshold, first_token=first)
+    dt = time.time() - t0
+    threads = int(os.environ.get("OMP_NUM_THREADS", "0")) or len(os.sched_getaffinity(0))
+    return {"value": round(n_tokens / dt, 4), "unit": "tokens/s", "cores": threads, "kind": "oracle",
+            "sample": f"same {shape.name} weights, 16-token prompt (prefill {t_prefill:.1f}s not counted), "
+                      f"{n_tokens} tokens by Self-SD rounds ({st.rounds} verify + {st.drafted} draft passes) in {dt:.1f}s"}
+
+
+if __name__ == "__main__":
+    main()
