@@ -1,0 +1,751 @@
+// Tuned bf16 kernels of the decode path for gfx950 (MI355X).
+//
+// Everything here is bound by HBM bandwidth: a pass streams every retained weight matrix once.
+// The kernels therefore share one structure: a fixed grid of workgroups, each owning a balanced
+// share of every matrix's rows; inside a workgroup the wavefronts split that share into
+// contiguous 1 KB units (draft: flat row segments; verify: 16-row x 32-column MFMA operand
+// tiles with K split over the wavefronts), keep several 16-byte loads per lane in flight, and
+// meet once in LDS for the reduction and the fused epilogue (RoPE + KV-cache write, residual
+// add + next RMSNorm's operands, SwiGLU, LM-head arg-max partials).
+//
+// RMSNorm is folded in without a pass of its own: the producer of a residual row writes
+// gain (.) x (the next norm's gain applied) plus its share of sum(x^2); the consumer adds the
+// shares up in a fixed order and scales its dot products by rsqrt(mean + eps).
+#pragma once
+#include "kernels_generic.h"
+
+namespace ks {
+
+#ifndef KS_GEMV_DB
+#define KS_GEMV_DB 0
+#endif
+constexpr int NT = 512;        // threads per workgroup
+constexpr int NWV = NT / 64;   // wavefronts per workgroup
+constexpr int MAX_LROWS = 320; // most rows of one matrix a workgroup may own
+constexpr int KSEG = 512;      // bf16 elements one wavefront load covers (64 lanes x 16 bytes)
+constexpr int ATT_CHUNK = 128; // positions per split-KV work item (fixed: results do not depend on context length)
+constexpr int ATT_PG = 4;      // (row, head) pairs per attention work item
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+enum { OP_QKV = 0, OP_RESID = 1, OP_SWIGLU = 2, OP_HEAD = 3, OP_EMBED = 4 };
+
+struct HeadPartial { float maxv; int idx; float sumexp; int pad; };
+
+// One matrix-vector / small-M matrix product with its epilogue.
+struct GemmOp {
+    int type;
+    const bf16_t *W;  // [N][K] row-major; OP_SWIGLU: [2N][K], gate rows then up rows
+    int N, K;
+    const float *act_in;      // draft: fp32 [K], the next norm's gain already applied
+    const bf16_t *planes_in;  // verify: [3][KS_MAX_ROWS][K] bf16 split of the same values
+    const float *ss_in;       // [n_ss][KS_MAX_ROWS] shares of sum(x^2); nullptr: input is not normalised
+    int n_ss;
+    float inv_dim, eps;
+    // OP_RESID / OP_EMBED: residual stream and the operands of the next norm
+    float *x;                 // [KS_MAX_ROWS][N]
+    const float *gain_next;   // [N]
+    float *act_out;           // fp32 [KS_MAX_ROWS][N]  (also OP_SWIGLU's output)
+    bf16_t *planes_out;       // [3][KS_MAX_ROWS][N]
+    float *ss_out;            // [gridDim][KS_MAX_ROWS]
+    // OP_QKV
+    float *q_out;             // [KS_MAX_ROWS][H*hd], rotated
+    bf16_t *kv_block;         // this block's cache: [2][Hkv][max_seq][hd]
+    const float *cos_t, *sin_t;
+    int H, Hkv, hd, max_seq;
+    // OP_HEAD
+    float *logits;            // [KS_MAX_ROWS][N]
+    HeadPartial *head_part;   // [KS_MAX_ROWS][gridDim]
+    // OP_EMBED
+    const bf16_t *embed;
+};
+
+__device__ __forceinline__ float bf_lo(unsigned int u) { return __uint_as_float(u << 16); }
+__device__ __forceinline__ float bf_hi(unsigned int u) { return __uint_as_float(u & 0xffff0000u); }
+
+__device__ __forceinline__ float dot8(u32x4 w, float4 x0, float4 x1, float acc) {
+    acc = fmaf(bf_lo(w.x), x0.x, acc); acc = fmaf(bf_hi(w.x), x0.y, acc);
+    acc = fmaf(bf_lo(w.y), x0.z, acc); acc = fmaf(bf_hi(w.y), x0.w, acc);
+    acc = fmaf(bf_lo(w.z), x1.x, acc); acc = fmaf(bf_hi(w.z), x1.y, acc);
+    acc = fmaf(bf_lo(w.w), x1.z, acc); acc = fmaf(bf_hi(w.w), x1.w, acc);
+    return acc;
+}
+
+// Rows of W a workgroup owns, as a table of global row indices in LDS. Returns the count.
+// OP_QKV orders them [first halves of np rotary pairs][their second halves][nv value rows],
+// OP_SWIGLU [nf gate rows][the matching nf up rows].
+__device__ __forceinline__ int build_row_table(const GemmOp &op, int wg, int nwg, int *rowidx, int *n_first) {
+    int R = 0;
+    if (op.type == OP_QKV) {
+        const int half = op.hd >> 1;
+        const int P = (op.H + op.Hkv) * half, VR = op.Hkv * op.hd;
+        const int p0 = (int)((long long)P * wg / nwg), p1 = (int)((long long)P * (wg + 1) / nwg);
+        const int v0 = (int)((long long)VR * wg / nwg), v1 = (int)((long long)VR * (wg + 1) / nwg);
+        const int np = p1 - p0, nv = v1 - v0;
+        R = 2 * np + nv;
+        for (int t = threadIdx.x; t < R; t += NT) {
+            int row;
+            if (t < 2 * np) {
+                int p = p0 + (t < np ? t : t - np);
+                int head = p / half, i = p - head * half;
+                row = head * op.hd + i + (t < np ? 0 : half);
+            } else {
+                row = (op.H + op.Hkv) * op.hd + v0 + (t - 2 * np);
+            }
+            rowidx[t] = row;
+        }
+        *n_first = np;
+    } else if (op.type == OP_SWIGLU) {
+        const int f0 = (int)((long long)op.N * wg / nwg), f1 = (int)((long long)op.N * (wg + 1) / nwg);
+        const int nf = f1 - f0;
+        R = 2 * nf;
+        for (int t = threadIdx.x; t < R; t += NT) rowidx[t] = (t < nf) ? f0 + t : op.N + f0 + (t - nf);
+        *n_first = nf;
+    } else {
+        const int r0 = (int)((long long)op.N * wg / nwg), r1 = (int)((long long)op.N * (wg + 1) / nwg);
+        R = r1 - r0;
+        for (int t = threadIdx.x; t < R; t += NT) rowidx[t] = r0 + t;
+        *n_first = R;
+    }
+    return R;
+}
+
+// rsqrt(mean(x^2) + eps) of row m from the producers' shares, summed in a fixed order by one wavefront
+__device__ __forceinline__ float rstd_from_shares(const GemmOp &op, int m, int lane) {
+    float s = 0.f;
+    for (int i = lane; i < op.n_ss; i += 64) s += op.ss_in[(size_t)i * KS_MAX_ROWS + m];
+    s = wave_sum(s);
+    return 1.0f / sqrtf(s * op.inv_dim + op.eps);
+}
+
+// workgroup sum of one float per thread (NT threads); scratch: NWV floats of LDS
+__device__ __forceinline__ float block_sum(float v, float *scratch) {
+    v = wave_sum(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) scratch[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float t = 0.f;
+#pragma unroll
+    for (int w = 0; w < NWV; ++w) t += scratch[w];
+    return t;
+}
+
+// ------------------------------------------------------------------------------------------
+// Epilogue shared by the draft (1 row) and verify (n_rows) kernels. vals[lr * ld + m] holds the
+// finished dot product of local row lr and token row m (LDS).
+// ------------------------------------------------------------------------------------------
+template <bool PLANES>
+__device__ __forceinline__ void store_act(const GemmOp &op, int m, int n, int ldn, float v) {
+    if (!PLANES) {
+        op.act_out[(size_t)m * ldn + n] = v;
+    } else {
+        // exact three-way split: v = hi + mid + lo, each a bf16 (truncation keeps every step exact)
+        unsigned int u = __float_as_uint(v);
+        float hi = __uint_as_float(u & 0xffff0000u);
+        float r1 = v - hi;
+        float mid = __uint_as_float(__float_as_uint(r1) & 0xffff0000u);
+        float lo = r1 - mid;
+        const size_t plane = (size_t)KS_MAX_ROWS * ldn;
+        const size_t o = (size_t)m * ldn + n;
+        op.planes_out[o] = (bf16_t)(u >> 16);
+        op.planes_out[plane + o] = (bf16_t)(__float_as_uint(mid) >> 16);
+        op.planes_out[2 * plane + o] = (bf16_t)(__float_as_uint(lo) >> 16);
+    }
+}
+
+template <bool PLANES>
+__device__ __forceinline__ void gemm_epilogue(const GemmOp &op, const PassCtl *ctl, int wg, int nwg, int R, int n_first,
+                                              const int *rowidx, const float *vals, int ld, const float *rstd,
+                                              int row_lo, int n_rows, float *scratch) {
+    const int tid = threadIdx.x;
+    if (op.type == OP_RESID) {
+        float ssq[KS_MAX_ROWS];
+#pragma unroll
+        for (int m = 0; m < KS_MAX_ROWS; ++m) ssq[m] = 0.f;
+        for (int t = tid; t < R; t += NT) {
+            const int n = rowidx[t];
+            const float g = op.gain_next[n];
+#pragma unroll
+            for (int m = 0; m < KS_MAX_ROWS; ++m) {
+                if (m < n_rows) {
+                    float xn = op.x[(size_t)m * op.N + n] + vals[t * ld + m];
+                    op.x[(size_t)m * op.N + n] = xn;
+                    store_act<PLANES>(op, m, n, op.N, g * xn);
+                    ssq[m] = fmaf(xn, xn, ssq[m]);
+                }
+            }
+        }
+#pragma unroll
+        for (int m = 0; m < KS_MAX_ROWS; ++m) {
+            if (m < n_rows) {                               // n_rows is uniform: every thread takes the same branches
+                float s = block_sum(ssq[m], scratch);
+                if (tid == 0) op.ss_out[(size_t)wg * KS_MAX_ROWS + m] = s;
+            }
+        }
+    } else if (op.type == OP_SWIGLU) {
+        for (int t = tid; t < n_first; t += NT) {
+            const int n = rowidx[t];
+            for (int m = 0; m < n_rows; ++m) {
+                float a = vals[t * ld + m] * rstd[m], b = vals[(t + n_first) * ld + m] * rstd[m];
+                store_act<PLANES>(op, m, n, op.N, (a / (1.0f + expf(-a))) * b);
+            }
+        }
+    } else if (op.type == OP_QKV) {
+        const int half = op.hd >> 1, qd = op.H * op.hd;
+        const int np = n_first;
+        bf16_t *kc = op.kv_block;
+        bf16_t *vc = op.kv_block + (size_t)op.Hkv * op.max_seq * op.hd;
+        for (int t = tid; t < R - np; t += NT) {
+            // t < np: rotary pair (row, row + half);  t >= np: value row (local index t + np)
+            const bool is_pair = t < np;
+            const int lr = is_pair ? t : t + np;
+            const int n = rowidx[lr];
+            for (int m = 0; m < n_rows; ++m) {
+                const int pos = ctl->start + m;
+                if (is_pair) {
+                    const int head = n / op.hd, i = n - head * op.hd;
+                    const float c = op.cos_t[(size_t)pos * half + i], s = op.sin_t[(size_t)pos * half + i];
+                    const float a = vals[lr * ld + m] * rstd[m], b = vals[(lr + np) * ld + m] * rstd[m];
+                    const float ra = a * c - b * s, rb = b * c + a * s;
+                    if (head < op.H) {
+                        op.q_out[(size_t)m * qd + n] = ra;
+                        op.q_out[(size_t)m * qd + n + half] = rb;
+                    } else {
+                        const size_t base = ((size_t)(head - op.H) * op.max_seq + pos) * op.hd + i;
+                        kc[base] = float_to_bf16_rne(ra);
+                        kc[base + half] = float_to_bf16_rne(rb);
+                    }
+                } else {
+                    const int vr = n - (op.H + op.Hkv) * op.hd;
+                    const int head = vr / op.hd, i = vr - head * op.hd;
+                    vc[((size_t)head * op.max_seq + pos) * op.hd + i] = float_to_bf16_rne(vals[lr * ld + m] * rstd[m]);
+                }
+            }
+        }
+    } else if (op.type == OP_HEAD) {
+        // logits of this workgroup's rows, plus (max, lowest arg-max, sum exp(l - max)) over them
+        for (int m = row_lo; m < n_rows; ++m) {
+            float bv = -INFINITY; int bi = 0x7fffffff;
+            for (int t = tid; t < R; t += NT) {
+                const int n = rowidx[t];
+                const float l = vals[t * ld + m] * rstd[m];
+                op.logits[(size_t)m * op.N + n] = l;
+                if (better(l, n, bv, bi)) { bv = l; bi = n; }
+            }
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) {
+                float ov = __shfl_xor(bv, off, 64); int oi = __shfl_xor(bi, off, 64);
+                if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+            }
+            __syncthreads();
+            if ((tid & 63) == 0) { scratch[tid >> 6] = bv; scratch[NWV + (tid >> 6)] = __int_as_float(bi); }
+            __syncthreads();
+            bv = scratch[0]; bi = __float_as_int(scratch[NWV]);
+#pragma unroll
+            for (int w = 1; w < NWV; ++w) {
+                float ov = scratch[w]; int oi = __float_as_int(scratch[NWV + w]);
+                if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+            }
+            float se = 0.f;
+            for (int t = tid; t < R; t += NT) se += expf(vals[t * ld + m] * rstd[m] - bv);
+            se = block_sum(se, scratch + 2 * NWV);
+            if (tid == 0) {
+                HeadPartial hp; hp.maxv = bv; hp.idx = bi; hp.sumexp = (R > 0) ? se : 0.f; hp.pad = 0;
+                op.head_part[(size_t)m * nwg + wg] = hp;
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Draft step (one row): y = W x on flat 1 KB units. Each wavefront streams a contiguous range of
+// (row, 512-column segment) units of the workgroup's rows, 8 loads in flight twice over.
+// ------------------------------------------------------------------------------------------
+struct UnitCursor { int lr, ks; };
+
+__device__ __forceinline__ void gemv_device(const GemmOp &op, const PassCtl *ctl, int wg, int nwg, char *lds) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int K = op.K;
+    const int S = (K + KSEG - 1) / KSEG;
+    float *xs = reinterpret_cast<float *>(lds);                 // [S*512]
+    float *part = xs + (size_t)S * KSEG;                        // [MAX_LROWS][NWV]
+    int *rowidx = reinterpret_cast<int *>(part + MAX_LROWS * NWV);
+    float *scratch = reinterpret_cast<float *>(rowidx + MAX_LROWS);  // [4*NWV + KS_MAX_ROWS]
+    float *rstd_s = scratch + 4 * NWV;
+
+    int n_first = 0;
+    const int R = build_row_table(op, wg, nwg, rowidx, &n_first);
+    for (int i = tid; i < R * NWV; i += NT) part[i] = 0.f;
+    __syncthreads();
+
+    const int total = R * S;
+    const int u0 = (int)((long long)total * wave / NWV), u1 = (int)((long long)total * (wave + 1) / NWV);
+    UnitCursor cl, cc;
+    cl.lr = u0 / S; cl.ks = u0 - cl.lr * S; cc = cl;
+    int left_l = u1 - u0, left_c = u1 - u0;
+
+    u32x4 wa[8], wb[8];
+    auto load_batch = [&](u32x4 *w) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            if (left_l > 0) {
+                const int k = cl.ks * KSEG + lane * 8;
+                const bf16_t *p = op.W + (size_t)rowidx[cl.lr] * K + k;
+                u32x4 z = {0u, 0u, 0u, 0u};
+                w[i] = (k < K) ? __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p)) : z;
+                if (++cl.ks == S) { cl.ks = 0; ++cl.lr; }
+                --left_l;
+            }
+        }
+    };
+    float acc = 0.f;
+    auto compute_batch = [&](const u32x4 *w) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            if (left_c > 0) {
+                const float *xp = xs + cc.ks * KSEG + lane * 8;
+                float4 x0 = *reinterpret_cast<const float4 *>(xp), x1 = *reinterpret_cast<const float4 *>(xp + 4);
+                acc = dot8(w[i], x0, x1, acc);
+                if (cc.ks == S - 1 || left_c == 1) {
+                    float s = wave_sum(acc);
+                    if (lane == 0) part[cc.lr * NWV + wave] = s;
+                    acc = 0.f;
+                }
+                if (++cc.ks == S) { cc.ks = 0; ++cc.lr; }
+                --left_c;
+            }
+        }
+    };
+
+    load_batch(wa);                       // weights are in flight while the input vector is staged
+    for (int i = tid * 4; i < S * KSEG; i += NT * 4) {
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (i < K) v = *reinterpret_cast<const float4 *>(op.act_in + i);
+        *reinterpret_cast<float4 *>(xs + i) = v;
+    }
+    if (wave == 0) {
+        float r = op.ss_in ? rstd_from_shares(op, 0, lane) : 1.0f;
+        if (lane == 0) rstd_s[0] = r;
+    }
+    __syncthreads();
+#if KS_GEMV_DB
+    while (left_c > 0) {
+        load_batch(wb);
+        compute_batch(wa);
+        load_batch(wa);
+        compute_batch(wb);
+    }
+#else
+    // one batch of eight 1 KB loads per wavefront at a time: with 16 wavefronts per compute unit that is
+    // 128 KB in flight per compute unit, which measures fastest on MI355X (more in flight is slower)
+    while (left_c > 0) {
+        compute_batch(wa);
+        load_batch(wa);
+    }
+#endif
+    __syncthreads();
+    // finished dot products: vals[lr] = sum over wavefronts, fixed order
+    float *vals = xs;   // the staged input is no longer needed
+    for (int t = tid; t < R; t += NT) {
+        float s = 0.f;
+#pragma unroll
+        for (int w = 0; w < NWV; ++w) s += part[t * NWV + w];
+        vals[t] = s;
+    }
+    __syncthreads();
+    gemm_epilogue<false>(op, ctl, wg, nwg, R, n_first, rowidx, vals, 1, rstd_s, ctl->head_from, 1, scratch);
+}
+
+__host__ __device__ inline size_t gemv_lds_bytes(int K) {
+    const int S = (K + KSEG - 1) / KSEG;
+    return (size_t)S * KSEG * 4 + (size_t)MAX_LROWS * NWV * 4 + MAX_LROWS * 4 + (4 * NWV + KS_MAX_ROWS) * 4;
+}
+
+__global__ __launch_bounds__(NT, 4) void gemv_kernel(GemmOp op, const PassCtl *ctl) {
+    extern __shared__ __align__(16) char lds[];
+    if (!ctl->active) return;
+    gemv_device(op, ctl, blockIdx.x, gridDim.x, lds);
+}
+
+// ------------------------------------------------------------------------------------------
+// Verification (up to 16 rows): Y = W X on the matrix cores. The weights are the A operand of
+// v_mfma_f32_16x16x32_bf16 (lane = (row l%16, 8 columns at 8*(l/16)): one 16-byte load per lane
+// and 16-row x 32-column tile), the token rows the B operand. Activations stay fp32-exact: each
+// value is the sum of three bf16 planes (hi + mid + lo), so a tile takes three MFMAs whose
+// bf16 x bf16 products are exact in the fp32 accumulator. The path is HBM-bound (<= 16 flop per
+// weight byte against a ridge of ~300), so the two extra MFMAs cost nothing.
+// K is split over the workgroup's wavefronts; a token column's result never depends on how
+// many other columns are live.
+// ------------------------------------------------------------------------------------------
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+constexpr int MFMA_TG = 4;   // tiles accumulated together (16 accumulator registers)
+
+__host__ __device__ inline size_t mfma_lds_bytes() {
+    return (size_t)MAX_LROWS * KS_MAX_ROWS * 4 + (size_t)NWV * MFMA_TG * 256 * 4 + MAX_LROWS * 4 + (4 * NWV + KS_MAX_ROWS) * 4;
+}
+
+__device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl *ctl, int wg, int nwg, char *lds) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int K = op.K;
+    float *vals = reinterpret_cast<float *>(lds);                       // [MAX_LROWS][16]
+    float *red = vals + MAX_LROWS * KS_MAX_ROWS;                        // [NWV][MFMA_TG][256]
+    int *rowidx = reinterpret_cast<int *>(red + NWV * MFMA_TG * 256);
+    float *scratch = reinterpret_cast<float *>(rowidx + MAX_LROWS);
+    float *rstd_s = scratch + 4 * NWV;
+    const int n_rows = min(ctl->n_rows, KS_MAX_ROWS);
+
+    int n_first = 0;
+    const int R = build_row_table(op, wg, nwg, rowidx, &n_first);
+    for (int m = wave; m < KS_MAX_ROWS; m += NWV) {
+        float r = (op.ss_in && m < n_rows) ? rstd_from_shares(op, m, lane) : 1.0f;
+        if (lane == 0) rstd_s[m] = r;
+    }
+    __syncthreads();
+
+    const int T = (R + 15) >> 4;
+    const int KS = K >> 5;                                              // 32-column steps
+    const int ks0 = (int)((long long)KS * wave / NWV), ks1 = (int)((long long)KS * (wave + 1) / NWV);
+    const int r16 = lane & 15, kg = lane >> 4;
+    const size_t plane = (size_t)KS_MAX_ROWS * K;
+    const bf16_t *bp = op.planes_in + (size_t)r16 * K + kg * 8;         // this lane's token row / column group
+    const bool b_live = r16 < n_rows;
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+
+    for (int t0 = 0; t0 < T; t0 += MFMA_TG) {
+        const int nt = min(MFMA_TG, T - t0);
+        const bf16_t *ap[MFMA_TG];
+        bool a_live[MFMA_TG];
+#pragma unroll
+        for (int t = 0; t < MFMA_TG; ++t) {
+            const int lr = (t0 + t) * 16 + r16;
+            a_live[t] = (t < nt) && (lr < R);
+            ap[t] = op.W + (size_t)(a_live[t] ? rowidx[lr] : 0) * K + kg * 8;
+        }
+        f32x4 acc[MFMA_TG];
+#pragma unroll
+        for (int t = 0; t < MFMA_TG; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+        // software pipeline over 32-column steps: operands of step s+1 are in flight while step s multiplies
+        u32x4 a_cur[MFMA_TG], b_cur[3], a_nxt[MFMA_TG], b_nxt[3];
+        auto load_step = [&](int s, u32x4 *a, u32x4 *b) {
+            const size_t k = (size_t)s * 32;
+#pragma unroll
+            for (int t = 0; t < MFMA_TG; ++t)
+                a[t] = a_live[t] ? __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(ap[t] + k)) : zero;
+#pragma unroll
+            for (int p = 0; p < 3; ++p)
+                b[p] = b_live ? *reinterpret_cast<const u32x4 *>(bp + p * plane + k) : zero;
+        };
+        auto mma_step = [&](const u32x4 *a, const u32x4 *b) {
+#pragma unroll
+            for (int t = 0; t < MFMA_TG; ++t) {
+                if (t < nt) {
+                    const bf16x8 av = __builtin_bit_cast(bf16x8, a[t]);
+#pragma unroll
+                    for (int p = 0; p < 3; ++p)
+                        acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, b[p]), acc[t], 0, 0, 0);
+                }
+            }
+        };
+        if (ks0 < ks1) load_step(ks0, a_cur, b_cur);
+        for (int s = ks0; s < ks1; s += 2) {
+            if (s + 1 < ks1) load_step(s + 1, a_nxt, b_nxt);
+            mma_step(a_cur, b_cur);
+            if (s + 2 < ks1) load_step(s + 2, a_cur, b_cur);
+            if (s + 1 < ks1) mma_step(a_nxt, b_nxt);
+        }
+        // partial tiles of this wavefront -> LDS; lane holds D[row 4*kg + q][token r16]
+        __syncthreads();    // previous group's reduction reads are done
+#pragma unroll
+        for (int t = 0; t < MFMA_TG; ++t) {
+            if (t < nt) {
+                float *rp = red + ((size_t)wave * MFMA_TG + t) * 256;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) rp[(4 * kg + q) * 16 + r16] = acc[t][q];
+            }
+        }
+        __syncthreads();
+        for (int i = tid; i < nt * 256; i += NT) {
+            const int t = i >> 8, e = i & 255;
+            float s = 0.f;
+#pragma unroll
+            for (int w = 0; w < NWV; ++w) s += red[((size_t)w * MFMA_TG + t) * 256 + e];
+            const int lr = (t0 + t) * 16 + (e >> 4);
+            if (lr < R) vals[lr * KS_MAX_ROWS + (e & 15)] = s;
+        }
+    }
+    __syncthreads();
+    gemm_epilogue<true>(op, ctl, wg, nwg, R, n_first, rowidx, vals, KS_MAX_ROWS, rstd_s,
+                        op.type == OP_HEAD ? ctl->head_from : 0, n_rows, scratch);
+}
+
+__global__ __launch_bounds__(NT, 4) void gemm_mfma_kernel(GemmOp op, const PassCtl *ctl) {
+    extern __shared__ __align__(16) char lds[];
+    if (!ctl->active) return;
+    gemm_mfma_device(op, ctl, blockIdx.x, gridDim.x, lds);
+}
+
+// final-RMSNorm hidden state of one row from the head's operands: gain (.) x (three planes) times rstd
+__global__ __launch_bounds__(NT) void hidden_from_planes_kernel(const bf16_t *planes, const float *ss, int n_ss, int d,
+                                                                float eps, const PassCtl *ctl, float *out0, float *out1) {
+    if (!ctl->active) return;
+    __shared__ float rs;
+    const int m = ctl->n_rows - 1;
+    if (threadIdx.x < 64) {
+        float s = 0.f;
+        for (int i = threadIdx.x; i < n_ss; i += 64) s += ss[(size_t)i * KS_MAX_ROWS + m];
+        s = wave_sum(s);
+        if (threadIdx.x == 0) rs = 1.0f / sqrtf(s / (float)d + eps);
+    }
+    __syncthreads();
+    const size_t plane = (size_t)KS_MAX_ROWS * d;
+    for (int i = blockIdx.x * NT + threadIdx.x; i < d; i += gridDim.x * NT) {
+        const size_t o = (size_t)m * d + i;
+        float v = (bf16_to_float(planes[o]) + bf16_to_float(planes[plane + o])) + bf16_to_float(planes[2 * plane + o]);
+        v *= rs;
+        out0[i] = v;
+        if (out1) out1[i] = v;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Embedding as the first producer: x = E[tok], gain (.) x and the shares of sum(x^2)
+// ------------------------------------------------------------------------------------------
+template <bool PLANES>
+__global__ __launch_bounds__(NT) void embed_producer_kernel(GemmOp op, const PassCtl *ctl) {
+    __shared__ float scratch[NWV];
+    if (!ctl->active) return;
+    const int n_rows = min(ctl->n_rows, KS_MAX_ROWS);
+    const int wg = blockIdx.x, nwg = gridDim.x;
+    const int r0 = (int)((long long)op.N * wg / nwg), r1 = (int)((long long)op.N * (wg + 1) / nwg);
+    for (int m = 0; m < n_rows; ++m) {
+        const bf16_t *row = op.embed + (size_t)ctl->tok[m] * op.N;
+        float ssq = 0.f;
+        for (int n = r0 + threadIdx.x; n < r1; n += NT) {
+            float v = bf16_to_float(row[n]);
+            op.x[(size_t)m * op.N + n] = v;
+            store_act<PLANES>(op, m, n, op.N, op.gain_next[n] * v);
+            ssq = fmaf(v, v, ssq);
+        }
+        float s = block_sum(ssq, scratch);
+        if (threadIdx.x == 0) op.ss_out[(size_t)wg * KS_MAX_ROWS + m] = s;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Split-KV attention over the contiguous bf16 cache. Work item = (kv head, 128-position chunk,
+// group of ATT_PG (row, q-head) pairs). Wavefront w of the workgroup owns 16 positions of the
+// chunk and keeps their K and V fragments in registers (lane = (position, 8-dim slice)); the
+// eight wavefronts' (max, sum, weighted V) are merged in LDS and written as the chunk's partial.
+// ------------------------------------------------------------------------------------------
+struct AttnArgs {
+    const float *q;          // [KS_MAX_ROWS][H*hd] rotated queries
+    const bf16_t *kv_block;  // [2][Hkv][max_seq][hd]
+    float *partial;          // [KS_MAX_ROWS*H][max_chunks][hd + 2]
+    int H, Hkv, hd, max_seq, max_chunks;
+    // combine
+    float *act_out;          // fp32 [KS_MAX_ROWS][H*hd]
+    bf16_t *planes_out;      // [3][KS_MAX_ROWS][H*hd]
+};
+
+template <int HD>
+__device__ __forceinline__ void attn_partial_device(const AttnArgs &a, const PassCtl *ctl, int wg, int nwg, char *lds) {
+    constexpr int LPP = HD / 8;        // lanes per position
+    constexpr int PPS = 64 / LPP;      // positions per step
+    constexpr int STEPS = 16 / PPS;    // steps per wavefront (16 positions)
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int ps = lane / LPP, dg = lane % LPP;
+    const int n_rows = min(ctl->n_rows, KS_MAX_ROWS), start = ctl->start;
+    const int group = a.H / a.Hkv;
+    const int P = n_rows * group;                       // (row, head-in-group) pairs per kv head
+    const int n_pg = (P + ATT_PG - 1) / ATT_PG;
+    const int n_chunks = (start + n_rows + ATT_CHUNK - 1) / ATT_CHUNK;
+    const int n_items = a.Hkv * n_chunks * n_pg;
+    float *qs = reinterpret_cast<float *>(lds);                         // [ATT_PG][HD]
+    float *red = qs + ATT_PG * HD;                                      // [NWV][ATT_PG][HD + 2]
+    const float scale = 1.0f / sqrtf((float)HD);
+    const size_t kv_head_stride = (size_t)a.max_seq * HD;
+
+    for (int item = wg; item < n_items; item += nwg) {
+        const int pg = item % n_pg;
+        const int chunk = (item / n_pg) % n_chunks;
+        const int kvh = item / (n_pg * n_chunks);
+        const int p_base = pg * ATT_PG;
+        const int n_p = min(ATT_PG, P - p_base);
+        __syncthreads();   // previous item's LDS reads are done
+        for (int i = tid; i < n_p * HD; i += NT) {
+            const int pl = i / HD, dim = i - pl * HD, p = p_base + pl;
+            const int m = p / group, h = kvh * group + (p - m * group);
+            qs[pl * HD + dim] = a.q[(size_t)m * a.H * HD + h * HD + dim];
+        }
+        // this wavefront's 16 positions of K and V
+        const int pos0 = chunk * ATT_CHUNK + wave * 16;
+        const bf16_t *kc = a.kv_block + (size_t)kvh * kv_head_stride;
+        const bf16_t *vc = a.kv_block + ((size_t)a.Hkv + kvh) * kv_head_stride;
+        u32x4 kf[STEPS], vf[STEPS];
+#pragma unroll
+        for (int s = 0; s < STEPS; ++s) {
+            const int pos = pos0 + s * PPS + ps;
+            u32x4 z = {0u, 0u, 0u, 0u};
+            kf[s] = z; vf[s] = z;
+            if (pos < start + n_rows) {
+                kf[s] = *reinterpret_cast<const u32x4 *>(kc + (size_t)pos * HD + dg * 8);
+                vf[s] = *reinterpret_cast<const u32x4 *>(vc + (size_t)pos * HD + dg * 8);
+            }
+        }
+        __syncthreads();
+        for (int pl = 0; pl < n_p; ++pl) {
+            const int p = p_base + pl;
+            const int m = p / group;
+            const int len = start + m + 1;          // row m attends positions [0, len)
+            const float *qp = qs + pl * HD + dg * 8;
+            const float4 q0 = *reinterpret_cast<const float4 *>(qp), q1 = *reinterpret_cast<const float4 *>(qp + 4);
+            float sc[STEPS];
+            float mx = -INFINITY;
+#pragma unroll
+            for (int s = 0; s < STEPS; ++s) {
+                float d = dot8(kf[s], q0, q1, 0.f);
+#pragma unroll
+                for (int off = 1; off < LPP; off <<= 1) d += __shfl_xor(d, off, 64);
+                const int pos = pos0 + s * PPS + ps;
+                sc[s] = (pos < len) ? d * scale : -INFINITY;
+                mx = fmaxf(mx, sc[s]);
+            }
+#pragma unroll
+            for (int off = LPP; off < 64; off <<= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+            float l = 0.f;
+            float o[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) o[j] = 0.f;
+#pragma unroll
+            for (int s = 0; s < STEPS; ++s) {
+                const float e = (sc[s] > -INFINITY) ? expf(sc[s] - mx) : 0.f;
+                l += e;
+                o[0] = fmaf(e, bf_lo(vf[s].x), o[0]); o[1] = fmaf(e, bf_hi(vf[s].x), o[1]);
+                o[2] = fmaf(e, bf_lo(vf[s].y), o[2]); o[3] = fmaf(e, bf_hi(vf[s].y), o[3]);
+                o[4] = fmaf(e, bf_lo(vf[s].z), o[4]); o[5] = fmaf(e, bf_hi(vf[s].z), o[5]);
+                o[6] = fmaf(e, bf_lo(vf[s].w), o[6]); o[7] = fmaf(e, bf_hi(vf[s].w), o[7]);
+            }
+#pragma unroll
+            for (int off = LPP; off < 64; off <<= 1) {
+                l += __shfl_xor(l, off, 64);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) o[j] += __shfl_xor(o[j], off, 64);
+            }
+            // l counted every lane of a position LPP times over? no: each lane group of LPP lanes holds the same
+            // score, and the xor-sum above runs over the position groups only, so l is the sum over positions.
+            float *rp = red + ((size_t)wave * ATT_PG + pl) * (HD + 2);
+            if (ps == 0) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) rp[dg * 8 + j] = o[j];
+            }
+            if (lane == 0) { rp[HD] = mx; rp[HD + 1] = l; }
+        }
+        __syncthreads();
+        // merge the wavefronts' partials: thread (pl, dim)
+        for (int i = tid; i < n_p * HD; i += NT) {
+            const int pl = i / HD, dim = i - pl * HD, p = p_base + pl;
+            const int m = p / group, h = kvh * group + (p - m * group);
+            float M = -INFINITY;
+#pragma unroll
+            for (int w = 0; w < NWV; ++w) M = fmaxf(M, red[((size_t)w * ATT_PG + pl) * (HD + 2) + HD]);
+            float L = 0.f, O = 0.f;
+#pragma unroll
+            for (int w = 0; w < NWV; ++w) {
+                const float *rp = red + ((size_t)w * ATT_PG + pl) * (HD + 2);
+                const float f = (rp[HD] > -INFINITY) ? expf(rp[HD] - M) : 0.f;
+                L = fmaf(rp[HD + 1], f, L);
+                O = fmaf(rp[dim], f, O);
+            }
+            float *out = a.partial + (((size_t)m * a.H + h) * a.max_chunks + chunk) * (HD + 2);
+            out[dim] = O;
+            if (dim == 0) { out[HD] = M; out[HD + 1] = L; }
+        }
+    }
+}
+
+__host__ __device__ inline size_t attn_lds_bytes(int hd) { return (size_t)(ATT_PG * hd + NWV * ATT_PG * (hd + 2)) * 4; }
+
+template <int HD>
+__global__ __launch_bounds__(NT) void attn_partial_kernel(AttnArgs a, const PassCtl *ctl) {
+    extern __shared__ __align__(16) char lds[];
+    if (!ctl->active) return;
+    attn_partial_device<HD>(a, ctl, blockIdx.x, gridDim.x, lds);
+}
+
+// merge the chunks of every (row, head) in chunk order and hand the result to the O projection
+template <bool PLANES>
+__device__ __forceinline__ void attn_combine_device(const AttnArgs &a, const PassCtl *ctl, int wg, int nwg) {
+    const int n_rows = min(ctl->n_rows, KS_MAX_ROWS), start = ctl->start;
+    const int hd = a.hd, qd = a.H * hd;
+    const int total = n_rows * qd;
+    GemmOp st{};   // only the fields store_act uses
+    st.act_out = a.act_out; st.planes_out = a.planes_out;
+    for (int i = wg * NT + threadIdx.x; i < total; i += nwg * NT) {
+        const int m = i / qd, c = i - m * qd, h = c / hd, dim = c - h * hd;
+        const int n_chunks = (start + m + 1 + ATT_CHUNK - 1) / ATT_CHUNK;   // chunks row m can see
+        const float *pp = a.partial + ((size_t)m * a.H + h) * a.max_chunks * (hd + 2);
+        float M = -INFINITY;
+        for (int ch = 0; ch < n_chunks; ++ch) M = fmaxf(M, pp[(size_t)ch * (hd + 2) + hd]);
+        float L = 0.f, O = 0.f;
+        for (int ch = 0; ch < n_chunks; ++ch) {
+            const float *cp = pp + (size_t)ch * (hd + 2);
+            const float f = (cp[hd] > -INFINITY) ? expf(cp[hd] - M) : 0.f;
+            L = fmaf(cp[hd + 1], f, L);
+            O = fmaf(cp[dim], f, O);
+        }
+        store_act<PLANES>(st, m, c, qd, O / L);
+    }
+}
+
+template <bool PLANES>
+__global__ __launch_bounds__(NT) void attn_combine_kernel(AttnArgs a, const PassCtl *ctl) {
+    if (!ctl->active) return;
+    attn_combine_device<PLANES>(a, ctl, blockIdx.x, gridDim.x);
+}
+
+// ------------------------------------------------------------------------------------------
+// LM-head final step: merge the workgroups' (max, arg-max, sum-exp) per row in workgroup order
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(NT) void head_final_kernel(const HeadPartial *parts, int n_parts, const PassCtl *ctl,
+                                                        HeadResult *res) {
+    if (!ctl->active) return;
+    __shared__ float sv[NWV];
+    __shared__ int si[NWV];
+    __shared__ float ss[NWV];
+    const int m = blockIdx.x;
+    if (m >= ctl->n_rows || m < ctl->head_from) return;
+    const HeadPartial *pp = parts + (size_t)m * n_parts;
+    float bv = -INFINITY; int bi = 0x7fffffff;
+    for (int i = threadIdx.x; i < n_parts; i += NT) {
+        HeadPartial hp = pp[i];
+        if (hp.idx != 0x7fffffff && better(hp.maxv, hp.idx, bv, bi)) { bv = hp.maxv; bi = hp.idx; }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        float ov = __shfl_xor(bv, off, 64); int oi = __shfl_xor(bi, off, 64);
+        if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+    }
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) { sv[wave] = bv; si[wave] = bi; }
+    __syncthreads();
+    bv = sv[0]; bi = si[0];
+    for (int w = 1; w < NWV; ++w) if (better(sv[w], si[w], bv, bi)) { bv = sv[w]; bi = si[w]; }
+    float s = 0.f;
+    for (int i = threadIdx.x; i < n_parts; i += NT) {
+        HeadPartial hp = pp[i];
+        if (hp.idx != 0x7fffffff) s += hp.sumexp * expf(hp.maxv - bv);
+    }
+    s = wave_sum(s);
+    if (lane == 0) ss[wave] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float tot = 0.f;
+        for (int w = 0; w < NWV; ++w) tot += ss[w];
+        res->tok[m] = bi;
+        res->prob[m] = 1.0f / tot;
+    }
+}
+
+}  // namespace ks

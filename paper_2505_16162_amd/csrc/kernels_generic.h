@@ -230,8 +230,8 @@ __global__ __launch_bounds__(256) void attention_kernel(const PassCtl *ctl, cons
     if (!ctl->active) return;
     const int h = blockIdx.x, r = blockIdx.y;
     if (r >= ctl->n_rows) return;
-    extern __shared__ float lds[];
-    float *scores = lds;                 // [len]
+    extern __shared__ float score_lds[];
+    float *scores = score_lds;           // [len]
     __shared__ float red[8];
     __shared__ float outp[4][128];
     const int len = ctl->start + r + 1;

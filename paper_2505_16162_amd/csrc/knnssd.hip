@@ -12,6 +12,7 @@
 #include "../../include/knnssd.h"
 #include "device_types.h"
 #include "kernels_generic.h"
+#include "kernels_bf16.h"
 
 using namespace ks;
 
@@ -38,6 +39,8 @@ static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 struct WsLayout {
     size_t draft_ctl, ver_ctl, gen, head, knn, out3;
     size_t x, xn, qkv, att, u, logits, hidden_last, rope_cos, rope_sin, knn_scores, out_tokens;
+    // tuned bf16 path
+    size_t act_d, planes_d, qrot, planes_att, planes_u, ss, head_part, attn_part;
     size_t total;
 };
 
@@ -83,9 +86,23 @@ static WsLayout ws_layout(const knnssd_model_cfg *c) {
     L.rope_sin = take((size_t)c->max_seq * (c->head_dim / 2) * 4);
     L.knn_scores = take((size_t)(c->max_anchors > 0 ? c->max_anchors : 1) * 4);
     L.out_tokens = take((size_t)c->max_seq * 4);
+    {
+        const size_t qd = (size_t)c->n_heads * c->head_dim;
+        const size_t max_chunks = ((size_t)c->max_seq + ATT_CHUNK - 1) / ATT_CHUNK;
+        L.act_d = take(R * c->d_model * 4);
+        L.planes_d = take(3 * R * (size_t)c->d_model * 2);
+        L.qrot = take(R * qd * 4);
+        L.planes_att = take(3 * R * qd * 2);
+        L.planes_u = take(3 * R * (size_t)c->d_ffn * 2);
+        L.ss = take((size_t)KS_NWG * R * 4);
+        L.head_part = take(R * (size_t)KS_NWG * sizeof(HeadPartial));
+        L.attn_part = take(R * c->n_heads * max_chunks * (c->head_dim + 2) * 4);
+    }
     L.total = off;
     return L;
 }
+
+static bool tuned_ok(const knnssd_model_cfg &g);
 
 struct knnssd_ctx {
     knnssd_model_cfg cfg;
@@ -105,6 +122,8 @@ struct knnssd_ctx {
     std::vector<uint8_t> masks;       // [n_domains][2*n_blocks]
     std::vector<uint8_t> draft_mask;  // installed mask
     bool prefilled;
+    bool tuned;         // shape fits the tuned bf16 draft kernels
+    bool tuned_verify;  // ... and the matrix-core verification kernels (every K a multiple of 32)
     int32_t cache_len;
     // pinned host staging for small read-backs
     int32_t *h_stage;
@@ -174,6 +193,16 @@ extern "C" int32_t knnssd_create(const knnssd_model_cfg *cfg, const knnssd_weigh
     c->anchors = nullptr; c->labels = nullptr; c->n_anchors = 0; c->n_domains = 0;
     c->draft_mask.assign((size_t)2 * nb, 0);
     c->prefilled = false; c->cache_len = 0;
+    c->tuned = tuned_ok(*cfg);
+    if (c->tuned) {
+        hipError_t ea = hipFuncSetAttribute((const void *)gemv_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+        if (ea != hipSuccess) c->tuned = false;
+    }
+    c->tuned_verify = c->tuned && cfg->d_model % 32 == 0 && cfg->d_ffn % 32 == 0 && (cfg->n_heads * cfg->head_dim) % 32 == 0;
+    if (c->tuned_verify) {
+        hipError_t ea = hipFuncSetAttribute((const void *)gemm_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+        if (ea != hipSuccess) c->tuned_verify = false;
+    }
     c->h_stage = nullptr;
     hipError_t e = hipHostMalloc((void **)&c->h_stage, 4096, hipHostMallocDefault);
     if (e != hipSuccess) {
@@ -284,9 +313,104 @@ static int32_t run_pass_t(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask) {
     return KNNSSD_OK;
 }
 
+// ------------------------------------------------------------------------------------------
+// tuned bf16 passes
+// ------------------------------------------------------------------------------------------
+static bool tuned_ok(const knnssd_model_cfg &g) {
+    if (g.weight_dtype != KNNSSD_BF16 || g.kv_dtype != KNNSSD_BF16) return false;
+    const int nwg = KS_NWG;
+    auto per = [&](long long n) { return (int)((n + nwg - 1) / nwg); };
+    if (per(g.vocab) > MAX_LROWS || 2 * per(g.d_ffn) > MAX_LROWS) return false;
+    if (2 * per((long long)(g.n_heads + g.n_kv_heads) * g.head_dim / 2) + per((long long)g.n_kv_heads * g.head_dim) > MAX_LROWS) return false;
+    if (per(g.d_model) > MAX_LROWS) return false;
+    if (gemv_lds_bytes(g.d_ffn) > 96 * 1024 || gemv_lds_bytes(g.n_heads * g.head_dim) > 96 * 1024) return false;
+    return true;
+}
+
+// gain of the norm that reads the residual stream after sublayer index `after` (-1: after the embedding)
+static const float *next_gain(const knnssd_ctx *c, const uint8_t *mask, int after) {
+    for (int s = after + 1; s < 2 * c->cfg.n_blocks; ++s)
+        if (!(mask && mask[s])) return (s & 1) ? c->mlp_norm[s >> 1] : c->attn_norm[s >> 1];
+    return c->final_norm;
+}
+
+// One pass with the tuned bf16 kernels. rows1 = true: a draft step (one row, vector-ALU GEMV, fp32
+// activations); false: verification / prefill (up to 16 rows on the matrix cores, activations as
+// three bf16 planes). want_head = false skips the LM head (prefill chunks before the last).
+static int32_t run_pass_bf16(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, bool rows1, bool want_head) {
+    const knnssd_model_cfg &g = c->cfg;
+    const int d = g.d_model, H = g.n_heads, Hkv = g.n_kv_heads, hd = g.head_dim, F = g.d_ffn;
+    const int qd = H * hd, qkvd = (H + 2 * Hkv) * hd;
+    float *x = c->wsp<float>(c->L.x), *act_d = c->wsp<float>(c->L.act_d), *qrot = c->wsp<float>(c->L.qrot);
+    float *att = c->wsp<float>(c->L.att), *u = c->wsp<float>(c->L.u), *ss = c->wsp<float>(c->L.ss);
+    bf16_t *planes_d = c->wsp<bf16_t>(c->L.planes_d), *planes_att = c->wsp<bf16_t>(c->L.planes_att);
+    bf16_t *planes_u = c->wsp<bf16_t>(c->L.planes_u);
+    hipStream_t s = c->stream;
+    auto launch = [&](const GemmOp &op) {
+        if (rows1) hipLaunchKernelGGL(gemv_kernel, dim3(KS_NWG), dim3(NT), gemv_lds_bytes(op.K), s, op, ctl);
+        else hipLaunchKernelGGL(gemm_mfma_kernel, dim3(KS_NWG), dim3(NT), mfma_lds_bytes(), s, op, ctl);
+    };
+    GemmOp base{};
+    base.n_ss = KS_NWG; base.inv_dim = 1.0f / (float)d; base.eps = g.rms_eps;
+    base.H = H; base.Hkv = Hkv; base.hd = hd; base.max_seq = g.max_seq;
+    base.cos_t = c->wsp<float>(c->L.rope_cos); base.sin_t = c->wsp<float>(c->L.rope_sin);
+
+    GemmOp e = base;
+    e.type = OP_EMBED; e.N = d; e.embed = (const bf16_t *)c->embed; e.x = x; e.gain_next = next_gain(c, mask, -1);
+    e.act_out = act_d; e.planes_out = planes_d; e.ss_out = ss;
+    if (rows1) hipLaunchKernelGGL((embed_producer_kernel<false>), dim3(KS_NWG), dim3(NT), 0, s, e, ctl);
+    else hipLaunchKernelGGL((embed_producer_kernel<true>), dim3(KS_NWG), dim3(NT), 0, s, e, ctl);
+
+    AttnArgs aa{};
+    aa.q = qrot; aa.partial = c->wsp<float>(c->L.attn_part); aa.H = H; aa.Hkv = Hkv; aa.hd = hd; aa.max_seq = g.max_seq;
+    aa.max_chunks = (g.max_seq + ATT_CHUNK - 1) / ATT_CHUNK; aa.act_out = att; aa.planes_out = planes_att;
+    for (int b = 0; b < g.n_blocks; ++b) {
+        bf16_t *kvb = (bf16_t *)(c->kv + (size_t)b * c->kv_block_bytes);
+        if (!(mask && mask[2 * b])) {
+            GemmOp o = base;
+            o.type = OP_QKV; o.W = (const bf16_t *)c->wqkv[b]; o.N = qkvd; o.K = d; o.act_in = act_d; o.planes_in = planes_d;
+            o.ss_in = ss; o.q_out = qrot; o.kv_block = kvb;
+            launch(o);
+            aa.kv_block = kvb;
+            if (hd == 128) hipLaunchKernelGGL((attn_partial_kernel<128>), dim3(KS_NWG), dim3(NT), attn_lds_bytes(128), s, aa, ctl);
+            else hipLaunchKernelGGL((attn_partial_kernel<64>), dim3(KS_NWG), dim3(NT), attn_lds_bytes(64), s, aa, ctl);
+            if (rows1) hipLaunchKernelGGL((attn_combine_kernel<false>), dim3(16), dim3(NT), 0, s, aa, ctl);
+            else hipLaunchKernelGGL((attn_combine_kernel<true>), dim3(64), dim3(NT), 0, s, aa, ctl);
+            GemmOp r = base;
+            r.type = OP_RESID; r.W = (const bf16_t *)c->wo[b]; r.N = d; r.K = qd; r.act_in = att; r.planes_in = planes_att;
+            r.ss_in = nullptr; r.x = x; r.gain_next = next_gain(c, mask, 2 * b); r.act_out = act_d; r.planes_out = planes_d;
+            r.ss_out = ss;
+            launch(r);
+        }
+        if (!(mask && mask[2 * b + 1])) {
+            GemmOp o = base;
+            o.type = OP_SWIGLU; o.W = (const bf16_t *)c->wgu[b]; o.N = F; o.K = d; o.act_in = act_d; o.planes_in = planes_d;
+            o.ss_in = ss; o.act_out = u; o.planes_out = planes_u;
+            launch(o);
+            GemmOp r = base;
+            r.type = OP_RESID; r.W = (const bf16_t *)c->wdown[b]; r.N = d; r.K = F; r.act_in = u; r.planes_in = planes_u;
+            r.ss_in = nullptr; r.x = x; r.gain_next = next_gain(c, mask, 2 * b + 1); r.act_out = act_d; r.planes_out = planes_d;
+            r.ss_out = ss;
+            launch(r);
+        }
+    }
+    if (want_head) {
+        GemmOp h = base;
+        h.type = OP_HEAD; h.W = (const bf16_t *)c->lm_head; h.N = g.vocab; h.K = d; h.act_in = act_d; h.planes_in = planes_d;
+        h.ss_in = ss; h.logits = c->wsp<float>(c->L.logits); h.head_part = c->wsp<HeadPartial>(c->L.head_part);
+        launch(h);
+        hipLaunchKernelGGL(head_final_kernel, dim3(KS_MAX_ROWS), dim3(NT), 0, s, c->wsp<HeadPartial>(c->L.head_part), KS_NWG,
+                           ctl, c->wsp<HeadResult>(c->L.head));
+    }
+    HIP_TRY(hipGetLastError());
+    return KNNSSD_OK;
+}
+
 // mr: 1 for a draft step, KS_MAX_ROWS for verification / prefill
-static int32_t run_pass(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, int mr) {
+static int32_t run_pass(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, int mr, bool want_head = true) {
     const bool wb = c->cfg.weight_dtype == KNNSSD_BF16, kb = c->cfg.kv_dtype == KNNSSD_BF16;
+    if (mr == 1 && c->tuned) return run_pass_bf16(c, ctl, mask, true, true);
+    if (mr != 1 && c->tuned_verify) return run_pass_bf16(c, ctl, mask, false, want_head);
     if (mr == 1) {
         if (wb && kb) return run_pass_t<bf16_t, bf16_t, 1>(c, ctl, mask);
         if (wb && !kb) return run_pass_t<bf16_t, float, 1>(c, ctl, mask);
@@ -320,13 +444,20 @@ static int32_t prefill_impl(knnssd_ctx *c, const int32_t *tokens, int32_t n, flo
         int rows = n - s < KS_MAX_ROWS ? n - s : KS_MAX_ROWS;
         bool last = s + rows >= n;
         KS_TRY(set_pass(c, ver, 1, rows, s, last ? rows - 1 : rows, tokens + s));
-        KS_TRY(run_pass(c, ver, nullptr, KS_MAX_ROWS));
+        KS_TRY(run_pass(c, ver, nullptr, KS_MAX_ROWS, last));
         if (last) {
-            const float *xn_last = c->wsp<float>(c->L.xn) + (size_t)(rows - 1) * c->cfg.d_model;
-            HIP_TRY(hipMemcpyAsync(c->wsp<float>(c->L.hidden_last), xn_last, (size_t)c->cfg.d_model * 4,
-                                   hipMemcpyDeviceToDevice, c->stream));
-            if (last_hidden_dev)
-                HIP_TRY(hipMemcpyAsync(last_hidden_dev, xn_last, (size_t)c->cfg.d_model * 4, hipMemcpyDeviceToDevice, c->stream));
+            if (c->tuned_verify) {
+                hipLaunchKernelGGL(hidden_from_planes_kernel, dim3(8), dim3(NT), 0, c->stream, c->wsp<bf16_t>(c->L.planes_d),
+                                   c->wsp<float>(c->L.ss), KS_NWG, c->cfg.d_model, c->cfg.rms_eps, ver,
+                                   c->wsp<float>(c->L.hidden_last), last_hidden_dev);
+                HIP_TRY(hipGetLastError());
+            } else {
+                const float *xn_last = c->wsp<float>(c->L.xn) + (size_t)(rows - 1) * c->cfg.d_model;
+                HIP_TRY(hipMemcpyAsync(c->wsp<float>(c->L.hidden_last), xn_last, (size_t)c->cfg.d_model * 4,
+                                       hipMemcpyDeviceToDevice, c->stream));
+                if (last_hidden_dev)
+                    HIP_TRY(hipMemcpyAsync(last_hidden_dev, xn_last, (size_t)c->cfg.d_model * 4, hipMemcpyDeviceToDevice, c->stream));
+            }
             KS_TRY(read_back(c, &c->wsp<HeadResult>(c->L.head)->tok[rows - 1], 4));
             *first_token = c->h_stage[0];
         }

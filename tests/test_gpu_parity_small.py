@@ -13,8 +13,10 @@ pytestmark = pytest.mark.gpu
 SHAPES = {
     "tiny_fp32": synth.workload("tiny").shape,
     "bf16_mha": synth.small_shape("bf16_mha", max_seq=160),
+    # d_ffn a multiple of 32: verification runs on the matrix-core kernels (688 above falls back to the generic ones)
     "bf16_gqa_hd128": synth.small_shape("bf16_gqa", n_blocks=3, d_model=384, n_heads=6, n_kv_heads=2, head_dim=128,
-                                        d_ffn=1000, vocab=1531, max_seq=160),
+                                        d_ffn=992, vocab=1531, max_seq=160),
+    "bf16_mfma_hd64": synth.small_shape("bf16_mfma", d_ffn=704, vocab=2000, max_seq=160),
     "fp32_gqa": synth.small_shape("fp32_gqa", n_heads=4, n_kv_heads=1, weight_dtype="fp32", kv_dtype="fp32",
                                   d_ffn=344, vocab=777, max_seq=160),
     "bf16_w_fp32_kv": synth.small_shape("mixed", kv_dtype="fp32", max_seq=160),
@@ -65,7 +67,8 @@ def test_prefill_draft_verify_logits(name):
 
 
 @pytest.mark.parametrize("name,max_draft,thr", [("tiny_fp32", 4, 0.0), ("tiny_fp32", 1, 0.0), ("bf16_mha", 4, 0.0),
-                                                ("bf16_gqa_hd128", 8, 0.0), ("fp32_gqa", 3, 0.6)])
+                                                ("bf16_gqa_hd128", 8, 0.0), ("bf16_mfma_hd64", 15, 0.0),
+                                                ("bf16_mfma_hd64", 3, 0.6), ("fp32_gqa", 3, 0.6)])
 def test_generate_tokens_and_counts_match_oracle(name, max_draft, thr):
     shape = SHAPES[name]
     print("case", name, max_draft, thr, flush=True)
