@@ -3,7 +3,7 @@
 #include <stdint.h>
 
 #define KS_MAX_ROWS 16
-#define KS_NWG 512      // workgroups of every tuned kernel: two per compute unit
+#define KS_NWG 256      // workgroups of every tuned kernel: one 1024-thread workgroup per compute unit
 
 // What one forward pass works on. Lives in device memory so that a pass can be
 // enqueued before the host knows its contents (the previous kernels fill it in).

@@ -12,6 +12,8 @@
 // gain (.) x (the next norm's gain applied) plus its share of sum(x^2); the consumer adds the
 // shares up in a fixed order and scales its dot products by rsqrt(mean + eps).
 #pragma once
+#include <type_traits>
+
 #include "kernels_generic.h"
 
 namespace ks {
@@ -19,11 +21,11 @@ namespace ks {
 #ifndef KS_GEMV_DB
 #define KS_GEMV_DB 0
 #endif
-constexpr int NT = 512;        // threads per workgroup
+constexpr int NT = 1024;       // threads per workgroup
 constexpr int NWV = NT / 64;   // wavefronts per workgroup
-constexpr int MAX_LROWS = 320; // most rows of one matrix a workgroup may own
+constexpr int MAX_LROWS = 640; // most rows of one matrix a workgroup may own
 constexpr int KSEG = 512;      // bf16 elements one wavefront load covers (64 lanes x 16 bytes)
-constexpr int ATT_CHUNK = 128; // positions per split-KV work item (fixed: results do not depend on context length)
+constexpr int ATT_CHUNK = NWV * 16;  // positions per split-KV work item (fixed: results do not depend on context length)
 constexpr int ATT_PG = 4;      // (row, head) pairs per attention work item
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
@@ -159,28 +161,28 @@ __device__ __forceinline__ void gemm_epilogue(const GemmOp &op, const PassCtl *c
                                               int row_lo, int n_rows, float *scratch) {
     const int tid = threadIdx.x;
     if (op.type == OP_RESID) {
-        float ssq[KS_MAX_ROWS];
-#pragma unroll
-        for (int m = 0; m < KS_MAX_ROWS; ++m) ssq[m] = 0.f;
-        for (int t = tid; t < R; t += NT) {
-            const int n = rowidx[t];
-            const float g = op.gain_next[n];
-#pragma unroll
-            for (int m = 0; m < KS_MAX_ROWS; ++m) {
-                if (m < n_rows) {
-                    float xn = op.x[(size_t)m * op.N + n] + vals[t * ld + m];
-                    op.x[(size_t)m * op.N + n] = xn;
-                    store_act<PLANES>(op, m, n, op.N, g * xn);
-                    ssq[m] = fmaf(xn, xn, ssq[m]);
-                }
+        // one thread per (row of W, token row): residual add, operands of the next norm, x^2 left in vals
+        float *vw = const_cast<float *>(vals);
+        for (int i = tid; i < R * ld; i += NT) {
+            const int t = i / ld, m = i - t * ld;
+            float sq = 0.f;
+            if (m < n_rows) {
+                const int n = rowidx[t];
+                const float xn = op.x[(size_t)m * op.N + n] + vals[i];
+                op.x[(size_t)m * op.N + n] = xn;
+                store_act<PLANES>(op, m, n, op.N, op.gain_next[n] * xn);
+                sq = xn * xn;
             }
+            vw[i] = sq;
         }
-#pragma unroll
-        for (int m = 0; m < KS_MAX_ROWS; ++m) {
-            if (m < n_rows) {                               // n_rows is uniform: every thread takes the same branches
-                float s = block_sum(ssq[m], scratch);
-                if (tid == 0) op.ss_out[(size_t)wg * KS_MAX_ROWS + m] = s;
-            }
+        __syncthreads();
+        // this workgroup's share of sum(x^2) per token row: one wavefront per row, fixed order
+        const int lane = tid & 63;
+        for (int m = tid >> 6; m < n_rows; m += NWV) {
+            float sacc = 0.f;
+            for (int t = lane; t < R; t += 64) sacc += vals[t * ld + m];
+            sacc = wave_sum(sacc);
+            if (lane == 0) op.ss_out[(size_t)wg * KS_MAX_ROWS + m] = sacc;
         }
     } else if (op.type == OP_SWIGLU) {
         for (int t = tid; t < n_first; t += NT) {
@@ -361,7 +363,7 @@ __host__ __device__ inline size_t gemv_lds_bytes(int K) {
     return (size_t)S * KSEG * 4 + (size_t)MAX_LROWS * NWV * 4 + MAX_LROWS * 4 + (4 * NWV + KS_MAX_ROWS) * 4;
 }
 
-__global__ __launch_bounds__(NT, 4) void gemv_kernel(GemmOp op, const PassCtl *ctl) {
+__global__ __launch_bounds__(NT, 1) void gemv_kernel(GemmOp op, const PassCtl *ctl) {
     extern __shared__ __align__(16) char lds[];
     if (!ctl->active) return;
     gemv_device(op, ctl, blockIdx.x, gridDim.x, lds);
@@ -379,21 +381,24 @@ __global__ __launch_bounds__(NT, 4) void gemv_kernel(GemmOp op, const PassCtl *c
 // ------------------------------------------------------------------------------------------
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
-constexpr int MFMA_TG = 4;   // tiles accumulated together (16 accumulator registers)
+
+constexpr int MFMA_BBUF = 51200;   // bytes of one activation staging buffer in LDS (two of them)
 
 __host__ __device__ inline size_t mfma_lds_bytes() {
-    return (size_t)MAX_LROWS * KS_MAX_ROWS * 4 + (size_t)NWV * MFMA_TG * 256 * 4 + MAX_LROWS * 4 + (4 * NWV + KS_MAX_ROWS) * 4;
+    return (size_t)2 * MFMA_BBUF + (size_t)MAX_LROWS * KS_MAX_ROWS * 4 + (size_t)NWV * 256 * 4 + MAX_LROWS * 4 +
+           (4 * NWV + KS_MAX_ROWS) * 4;
 }
 
 __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl *ctl, int wg, int nwg, char *lds) {
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int K = op.K;
-    float *vals = reinterpret_cast<float *>(lds);                       // [MAX_LROWS][16]
-    float *red = vals + MAX_LROWS * KS_MAX_ROWS;                        // [NWV][MFMA_TG][256]
-    int *rowidx = reinterpret_cast<int *>(red + NWV * MFMA_TG * 256);
+    char *bbuf = lds;                                                   // [2][MFMA_BBUF] activation chunks
+    float *vals = reinterpret_cast<float *>(lds + 2 * MFMA_BBUF);       // [MAX_LROWS][16]
+    float *red = vals + MAX_LROWS * KS_MAX_ROWS;                        // [NWV][256]
+    int *rowidx = reinterpret_cast<int *>(red + NWV * 256);
     float *scratch = reinterpret_cast<float *>(rowidx + MAX_LROWS);
     float *rstd_s = scratch + 4 * NWV;
-    const int n_rows = min(ctl->n_rows, KS_MAX_ROWS);
+    const int n_rows = max(min(ctl->n_rows, KS_MAX_ROWS), 1);
 
     int n_first = 0;
     const int R = build_row_table(op, wg, nwg, rowidx, &n_first);
@@ -403,84 +408,127 @@ __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl
     }
     __syncthreads();
 
+    // Work split inside the workgroup: the R rows form T tiles of equal height (<= 16 rows); `tl` tile lanes
+    // work on different tiles at the same time and the NWV / tl wavefronts of a lane split the columns.
     const int T = (R + 15) >> 4;
-    const int KS = K >> 5;                                              // 32-column steps
-    const int ks0 = (int)((long long)KS * wave / NWV), ks1 = (int)((long long)KS * (wave + 1) / NWV);
+    const int rpt = T ? (R + T - 1) / T : 0;                           // rows per tile
+    const int tl = T >= 4 ? 4 : (T >= 2 ? 2 : 1);
+    const int ksplit = NWV / tl;
+    const int tlane = wave / ksplit, kpart = wave - tlane * ksplit;
     const int r16 = lane & 15, kg = lane >> 4;
     const size_t plane = (size_t)KS_MAX_ROWS * K;
-    const bf16_t *bp = op.planes_in + (size_t)r16 * K + kg * 8;         // this lane's token row / column group
-    const bool b_live = r16 < n_rows;
-    const u32x4 zero = {0u, 0u, 0u, 0u};
 
-    for (int t0 = 0; t0 < T; t0 += MFMA_TG) {
-        const int nt = min(MFMA_TG, T - t0);
-        const bf16_t *ap[MFMA_TG];
-        bool a_live[MFMA_TG];
+    // The token rows (B operand) are staged through LDS in column chunks shared by all wavefronts: only the
+    // live rows are staged, so few rows mean long chunks (2 rows: 4096 columns, 16 rows: 512). A chunk is a
+    // multiple of 512 columns, so every wavefront of a tile lane gets whole 32-column steps of it.
+    int KC = (MFMA_BBUF / (3 * n_rows) - 16) / 2;
+    KC = max(512, KC / 512 * 512);
+    if (KC > K) KC = (K + 511) / 512 * 512;
+    const int NC = (K + KC - 1) / KC;
+    const int bstride = KC * 2 + 16;                                     // bytes per staged row (+16: LDS bank spread)
+    const int brow = min(r16, n_rows - 1);                               // dead token lanes re-read the last live row
+    u32x4 breg[3];
+    auto bchunk_load = [&](int c) {          // global -> registers: 16-byte pieces of chunk c, up to 3 per thread
+        const int cols = min(KC, K - c * KC), p8 = cols >> 3, pieces = 3 * n_rows * p8;
 #pragma unroll
-        for (int t = 0; t < MFMA_TG; ++t) {
-            const int lr = (t0 + t) * 16 + r16;
-            a_live[t] = (t < nt) && (lr < R);
-            ap[t] = op.W + (size_t)(a_live[t] ? rowidx[lr] : 0) * K + kg * 8;
+        for (int q = 0; q < 3; ++q) {
+            const int i = tid + q * NT;
+            if (i < pieces) {
+                const int pr = i / p8, c8 = i - pr * p8, pl = pr / n_rows, row = pr - pl * n_rows;
+                breg[q] = *reinterpret_cast<const u32x4 *>(op.planes_in + pl * plane + (size_t)row * K + (size_t)c * KC + c8 * 8);
+            }
         }
-        f32x4 acc[MFMA_TG];
+    };
+    auto bchunk_store = [&](int c) {         // registers -> LDS buffer c & 1
+        const int cols = min(KC, K - c * KC), p8 = cols >> 3, pieces = 3 * n_rows * p8;
+        char *dst = bbuf + (c & 1) * MFMA_BBUF;
 #pragma unroll
-        for (int t = 0; t < MFMA_TG; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int q = 0; q < 3; ++q) {
+            const int i = tid + q * NT;
+            if (i < pieces) {
+                const int pr = i / p8, c8 = i - pr * p8;
+                *reinterpret_cast<u32x4 *>(dst + (size_t)pr * bstride + c8 * 16) = breg[q];
+            }
+        }
+    };
 
-        // software pipeline over 32-column steps: operands of step s+1 are in flight while step s multiplies
-        u32x4 a_cur[MFMA_TG], b_cur[3], a_nxt[MFMA_TG], b_nxt[3];
-        auto load_step = [&](int s, u32x4 *a, u32x4 *b) {
-            const size_t k = (size_t)s * 32;
-#pragma unroll
-            for (int t = 0; t < MFMA_TG; ++t)
-                a[t] = a_live[t] ? __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(ap[t] + k)) : zero;
-#pragma unroll
-            for (int p = 0; p < 3; ++p)
-                b[p] = b_live ? *reinterpret_cast<const u32x4 *>(bp + p * plane + k) : zero;
+    for (int round = 0; round * tl < T; ++round) {   // T = 0 when this workgroup owns no rows
+        const int t = round * tl + tlane;            // this wavefront's tile (uniform per wavefront)
+        const bool have_tile = t < T;
+        f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+        // weights: lane = (row of the tile, 8-column group); dead rows re-read the tile's last live row
+        const int row_end = min((t + 1) * rpt, R);
+        const bf16_t *apt = op.W + (size_t)rowidx[have_tile ? min(t * rpt + r16, row_end - 1) : 0] * K + kg * 8;
+        constexpr int DA = 8;                        // 1 KB weight loads in flight per wavefront
+        u32x4 a[DA];
+        // steps of chunk c this wavefront owns: [lo, lo + cnt) within the chunk
+        auto chunk_range = [&](int c, int &lo, int &cnt) {
+            const int cs = min(KC, K - c * KC) >> 5;
+            lo = (int)((long long)cs * kpart / ksplit);
+            cnt = have_tile ? (int)((long long)cs * (kpart + 1) / ksplit) - lo : 0;
         };
-        auto mma_step = [&](const u32x4 *a, const u32x4 *b) {
+        int lo = 0, cnt = 0;
+        chunk_range(0, lo, cnt);
+        bchunk_load(0);
 #pragma unroll
-            for (int t = 0; t < MFMA_TG; ++t) {
-                if (t < nt) {
-                    const bf16x8 av = __builtin_bit_cast(bf16x8, a[t]);
+        for (int j = 0; j < DA; ++j)
+            if (j < cnt) a[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(apt + (size_t)(lo + j) * 32));
+        bchunk_store(0);
+        __syncthreads();
+        for (int c = 0; c < NC; ++c) {
+            if (c + 1 < NC) bchunk_load(c + 1);
+            const char *bsrc = bbuf + (c & 1) * MFMA_BBUF + (size_t)brow * bstride + kg * 16;
+            const bf16_t *ac = apt + (size_t)c * KC;
+            for (int i = 0; i < cnt; i += DA) {
 #pragma unroll
-                    for (int p = 0; p < 3; ++p)
-                        acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, b[p]), acc[t], 0, 0, 0);
+                for (int j = 0; j < DA; ++j) {
+                    if (i + j < cnt) {
+                        const int ls = lo + i + j;
+                        const bf16x8 av = __builtin_bit_cast(bf16x8, a[j]);
+#pragma unroll
+                        for (int p = 0; p < 3; ++p) {
+                            const u32x4 bv = *reinterpret_cast<const u32x4 *>(bsrc + (size_t)p * n_rows * bstride + ls * 64);
+                            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bv), acc, 0, 0, 0);
+                        }
+                        if (i + j + DA < cnt)
+                            a[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(ac + (size_t)(ls + DA) * 32));
+                    }
                 }
             }
-        };
-        if (ks0 < ks1) load_step(ks0, a_cur, b_cur);
-        for (int s = ks0; s < ks1; s += 2) {
-            if (s + 1 < ks1) load_step(s + 1, a_nxt, b_nxt);
-            mma_step(a_cur, b_cur);
-            if (s + 2 < ks1) load_step(s + 2, a_cur, b_cur);
-            if (s + 1 < ks1) mma_step(a_nxt, b_nxt);
-        }
-        // partial tiles of this wavefront -> LDS; lane holds D[row 4*kg + q][token r16]
-        __syncthreads();    // previous group's reduction reads are done
+            if (c + 1 < NC) {
+                // next chunk's first weight loads go out before the workgroup meets, so the stream never drains
+                chunk_range(c + 1, lo, cnt);
+                const bf16_t *an = apt + (size_t)(c + 1) * KC;
 #pragma unroll
-        for (int t = 0; t < MFMA_TG; ++t) {
-            if (t < nt) {
-                float *rp = red + ((size_t)wave * MFMA_TG + t) * 256;
-#pragma unroll
-                for (int q = 0; q < 4; ++q) rp[(4 * kg + q) * 16 + r16] = acc[t][q];
+                for (int j = 0; j < DA; ++j)
+                    if (j < cnt) a[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(an + (size_t)(lo + j) * 32));
+                bchunk_store(c + 1);
             }
+            __syncthreads();
+        }
+        // partial tile of this wavefront -> LDS; lane holds D[row 4*kg + q][token r16]
+        {
+            float *rp = red + (size_t)wave * 256;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) rp[(4 * kg + q) * 16 + r16] = acc[q];
         }
         __syncthreads();
-        for (int i = tid; i < nt * 256; i += NT) {
-            const int t = i >> 8, e = i & 255;
-            float s = 0.f;
-#pragma unroll
-            for (int w = 0; w < NWV; ++w) s += red[((size_t)w * MFMA_TG + t) * 256 + e];
-            const int lr = (t0 + t) * 16 + (e >> 4);
-            if (lr < R) vals[lr * KS_MAX_ROWS + (e & 15)] = s;
+        for (int i = tid; i < tl * 256; i += NT) {
+            const int l = i >> 8, e = i & 255, tt = round * tl + l, rit = e >> 4;
+            if (tt < T && rit < rpt && tt * rpt + rit < R) {
+                float sum = 0.f;
+                for (int w = 0; w < ksplit; ++w) sum += red[(size_t)(l * ksplit + w) * 256 + e];
+                vals[(tt * rpt + rit) * KS_MAX_ROWS + (e & 15)] = sum;
+            }
         }
+        __syncthreads();    // red and the staging buffers are reused by the next round
     }
     __syncthreads();
     gemm_epilogue<true>(op, ctl, wg, nwg, R, n_first, rowidx, vals, KS_MAX_ROWS, rstd_s,
                         op.type == OP_HEAD ? ctl->head_from : 0, n_rows, scratch);
 }
 
-__global__ __launch_bounds__(NT, 4) void gemm_mfma_kernel(GemmOp op, const PassCtl *ctl) {
+__global__ __launch_bounds__(NT, 1) void gemm_mfma_kernel(GemmOp op, const PassCtl *ctl) {
     extern __shared__ __align__(16) char lds[];
     if (!ctl->active) return;
     gemm_mfma_device(op, ctl, blockIdx.x, gridDim.x, lds);

@@ -33,6 +33,8 @@ static thread_local char g_hip_err[256] = "no HIP error recorded";
         if (rc_ != KNNSSD_OK) return rc_; \
     } while (0)
 
+static const size_t KS_MAX_DYN_LDS = 160 * 1024;  // dynamic LDS the tuned kernels may ask for (one workgroup per compute unit)
+
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // Workspace layout (byte offsets, all 256-byte aligned).
@@ -195,12 +197,12 @@ extern "C" int32_t knnssd_create(const knnssd_model_cfg *cfg, const knnssd_weigh
     c->prefilled = false; c->cache_len = 0;
     c->tuned = tuned_ok(*cfg);
     if (c->tuned) {
-        hipError_t ea = hipFuncSetAttribute((const void *)gemv_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+        hipError_t ea = hipFuncSetAttribute((const void *)gemv_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, KS_MAX_DYN_LDS);
         if (ea != hipSuccess) c->tuned = false;
     }
     c->tuned_verify = c->tuned && cfg->d_model % 32 == 0 && cfg->d_ffn % 32 == 0 && (cfg->n_heads * cfg->head_dim) % 32 == 0;
     if (c->tuned_verify) {
-        hipError_t ea = hipFuncSetAttribute((const void *)gemm_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+        hipError_t ea = hipFuncSetAttribute((const void *)gemm_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, KS_MAX_DYN_LDS);
         if (ea != hipSuccess) c->tuned_verify = false;
     }
     c->h_stage = nullptr;
@@ -323,7 +325,7 @@ static bool tuned_ok(const knnssd_model_cfg &g) {
     if (per(g.vocab) > MAX_LROWS || 2 * per(g.d_ffn) > MAX_LROWS) return false;
     if (2 * per((long long)(g.n_heads + g.n_kv_heads) * g.head_dim / 2) + per((long long)g.n_kv_heads * g.head_dim) > MAX_LROWS) return false;
     if (per(g.d_model) > MAX_LROWS) return false;
-    if (gemv_lds_bytes(g.d_ffn) > 96 * 1024 || gemv_lds_bytes(g.n_heads * g.head_dim) > 96 * 1024) return false;
+    if (gemv_lds_bytes(g.d_ffn) > KS_MAX_DYN_LDS || gemv_lds_bytes(g.n_heads * g.head_dim) > KS_MAX_DYN_LDS) return false;
     return true;
 }
 
