@@ -152,6 +152,18 @@ int32_t knnssd_generate(knnssd_ctx *ctx, const int32_t *prompt_host, int32_t n_p
                         const float *query_dev, const knnssd_gen_cfg *gen, int32_t *out_tokens_host,
                         int32_t *n_out, knnssd_stats *stats);
 
+/* Measurement aid: enqueues ONLY the launches of the weight-streaming kernel of one draft step
+ * (kind 0, n = 1, the installed mask: gemv_kernel) or of one verification pass (kind 1,
+ * n <= KNNSSD_MAX_ROWS rows: gemm_mfma_kernel), back to back on the context's stream between two
+ * HIP events. Outputs: the number of launches, the GPU time between the events (ns, in both
+ * gemm_ns and pass_ns) and the weight bytes the launches streamed, so bytes / time is the
+ * kernel's achieved bandwidth and time / launches its average duration. The pass's other
+ * kernels are skipped, so its numerical outputs are meaningless and the cache entries at
+ * start_pos.. are overwritten: prefill again before decoding. KNNSSD_ESHAPE if the shape runs on
+ * the generic kernels. */
+int32_t knnssd_profile_pass(knnssd_ctx *ctx, int32_t kind, const int32_t *tokens_host, int32_t n, int32_t start_pos,
+                            int64_t *n_launches, int64_t *gemm_ns, int64_t *gemm_bytes, int64_t *pass_ns);
+
 /* Parity/debug: fp32 logits of row `row` of the most recent pass (draft: row 0). */
 int32_t knnssd_get_logits(knnssd_ctx *ctx, int32_t row, float *logits_host);
 

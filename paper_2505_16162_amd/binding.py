@@ -23,7 +23,7 @@ _DT = {"fp32": 0, "bf16": 1}
 EXPORTS = [
     "knnssd_workspace_bytes", "knnssd_kvcache_bytes", "knnssd_create", "knnssd_destroy",
     "knnssd_set_anchors", "knnssd_prefill", "knnssd_select_skipset", "knnssd_set_skipset",
-    "knnssd_draft_step", "knnssd_verify", "knnssd_generate", "knnssd_get_logits", "knnssd_read_kv",
+    "knnssd_draft_step", "knnssd_verify", "knnssd_generate", "knnssd_profile_pass", "knnssd_get_logits", "knnssd_read_kv",
     "knnssd_strerror",
 ]
 
@@ -97,6 +97,8 @@ def load_library() -> ctypes.CDLL:
     lib.knnssd_verify.argtypes = [vp, vp, i32, i32, ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(i32)]
     lib.knnssd_generate.restype = i32
     lib.knnssd_generate.argtypes = [vp, vp, i32, vp, ctypes.POINTER(GenCfg), vp, ctypes.POINTER(i32), ctypes.POINTER(Stats)]
+    lib.knnssd_profile_pass.restype = i32
+    lib.knnssd_profile_pass.argtypes = [vp, i32, vp, i32, i32] + [ctypes.POINTER(ctypes.c_int64)] * 4
     lib.knnssd_get_logits.restype = i32
     lib.knnssd_get_logits.argtypes = [vp, i32, vp]
     lib.knnssd_read_kv.restype = i32
@@ -247,6 +249,13 @@ class KnnSsd:
         _check(self.lib.knnssd_generate(self.h, toks, len(prompt), q.data_ptr() if q is not None else None,
                                         ctypes.byref(gen), out, ctypes.byref(n_out), ctypes.byref(st)))
         return list(out[:n_out.value]), st.as_dict()
+
+    def knnssd_profile_pass(self, kind: int, tokens: Sequence[int], start_pos: int):
+        toks = _i32_array(tokens)
+        out = [ctypes.c_int64() for _ in range(4)]
+        _check(self.lib.knnssd_profile_pass(self.h, int(kind), toks, len(tokens), int(start_pos),
+                                            *[ctypes.byref(o) for o in out]))
+        return dict(n_launches=out[0].value, gemm_ns=out[1].value, gemm_bytes=out[2].value, pass_ns=out[3].value)
 
     def knnssd_get_logits(self, row: int = 0) -> torch.Tensor:
         out = torch.empty(self.shape.vocab, dtype=torch.float32)

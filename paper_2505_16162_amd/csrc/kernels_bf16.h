@@ -461,18 +461,21 @@ __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl
         const bf16_t *apt = op.W + (size_t)rowidx[have_tile ? min(t * rpt + r16, row_end - 1) : 0] * K + kg * 8;
         constexpr int DA = 8;                        // 1 KB weight loads in flight per wavefront
         u32x4 a[DA];
-        // steps of chunk c this wavefront owns: [lo, lo + cnt) within the chunk
-        auto chunk_range = [&](int c, int &lo, int &cnt) {
-            const int cs = min(KC, K - c * KC) >> 5;
-            lo = (int)((long long)cs * kpart / ksplit);
-            cnt = have_tile ? (int)((long long)cs * (kpart + 1) / ksplit) - lo : 0;
+        // Columns are dealt to the wavefronts of a tile lane in fixed 512-column blocks: wavefront kpart owns
+        // the g = 16 / ksplit consecutive 32-column steps [kpart*g, kpart*g + g) of every block. The deal does
+        // not depend on the chunk length, hence not on the number of live token rows: a row's sum is always
+        // grouped the same way. Step u of this wavefront inside a chunk is block u / g, offset u % g.
+        const int g = 16 / ksplit, gshift = (g == 4) ? 2 : (g == 2 ? 1 : 0);
+        auto chunk_count = [&](int c) {
+            const int cs = min(KC, K - c * KC) >> 5, nfull = cs >> 4, rem = cs & 15;
+            return have_tile ? nfull * g + min(max(rem - kpart * g, 0), g) : 0;
         };
-        int lo = 0, cnt = 0;
-        chunk_range(0, lo, cnt);
+        auto step_of = [&](int u) { return ((u >> gshift) << 4) + kpart * g + (u & (g - 1)); };
+        int cnt = chunk_count(0);
         bchunk_load(0);
 #pragma unroll
         for (int j = 0; j < DA; ++j)
-            if (j < cnt) a[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(apt + (size_t)(lo + j) * 32));
+            if (j < cnt) a[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(apt + (size_t)step_of(j) * 32));
         bchunk_store(0);
         __syncthreads();
         for (int c = 0; c < NC; ++c) {
@@ -483,7 +486,7 @@ __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl
 #pragma unroll
                 for (int j = 0; j < DA; ++j) {
                     if (i + j < cnt) {
-                        const int ls = lo + i + j;
+                        const int ls = step_of(i + j);
                         const bf16x8 av = __builtin_bit_cast(bf16x8, a[j]);
 #pragma unroll
                         for (int p = 0; p < 3; ++p) {
@@ -491,17 +494,17 @@ __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl
                             acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bv), acc, 0, 0, 0);
                         }
                         if (i + j + DA < cnt)
-                            a[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(ac + (size_t)(ls + DA) * 32));
+                            a[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(ac + (size_t)step_of(i + j + DA) * 32));
                     }
                 }
             }
             if (c + 1 < NC) {
                 // next chunk's first weight loads go out before the workgroup meets, so the stream never drains
-                chunk_range(c + 1, lo, cnt);
+                cnt = chunk_count(c + 1);
                 const bf16_t *an = apt + (size_t)(c + 1) * KC;
 #pragma unroll
                 for (int j = 0; j < DA; ++j)
-                    if (j < cnt) a[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(an + (size_t)(lo + j) * 32));
+                    if (j < cnt) a[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(an + (size_t)step_of(j) * 32));
                 bchunk_store(c + 1);
             }
             __syncthreads();
@@ -528,6 +531,8 @@ __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl
                         op.type == OP_HEAD ? ctl->head_from : 0, n_rows, scratch);
 }
 
+// PREFILL only names the launch site (prompt chunks vs verification passes) so that a profile keeps the two apart
+template <bool PREFILL>
 __global__ __launch_bounds__(NT, 1) void gemm_mfma_kernel(GemmOp op, const PassCtl *ctl) {
     extern __shared__ __align__(16) char lds[];
     if (!ctl->active) return;

@@ -130,6 +130,10 @@ struct knnssd_ctx {
     // pinned host staging for small read-backs
     int32_t *h_stage;
     std::vector<hipEvent_t> events;
+    // knnssd_profile_pass: enqueue only the weight-streaming launches of a pass and count them
+    bool gemm_only = false;
+    int64_t prof_launches = 0, prof_bytes = 0;
+    bool in_prefill = false;   // the pass being enqueued belongs to a prompt prefill
 
     template <typename T> T *wsp(size_t off) { return reinterpret_cast<T *>(ws + off); }
 };
@@ -196,13 +200,18 @@ extern "C" int32_t knnssd_create(const knnssd_model_cfg *cfg, const knnssd_weigh
     c->draft_mask.assign((size_t)2 * nb, 0);
     c->prefilled = false; c->cache_len = 0;
     c->tuned = tuned_ok(*cfg);
+    // debugging aid: KNNSSD_GENERIC_KERNELS=1 runs every shape on the generic kernels
+    if (const char *env = getenv("KNNSSD_GENERIC_KERNELS"))
+        if (env[0] == '1') c->tuned = false;
     if (c->tuned) {
         hipError_t ea = hipFuncSetAttribute((const void *)gemv_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, KS_MAX_DYN_LDS);
         if (ea != hipSuccess) c->tuned = false;
     }
     c->tuned_verify = c->tuned && cfg->d_model % 32 == 0 && cfg->d_ffn % 32 == 0 && (cfg->n_heads * cfg->head_dim) % 32 == 0;
     if (c->tuned_verify) {
-        hipError_t ea = hipFuncSetAttribute((const void *)gemm_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, KS_MAX_DYN_LDS);
+        hipError_t ea = hipFuncSetAttribute((const void *)gemm_mfma_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, KS_MAX_DYN_LDS);
+        if (ea == hipSuccess)
+            ea = hipFuncSetAttribute((const void *)gemm_mfma_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, KS_MAX_DYN_LDS);
         if (ea != hipSuccess) c->tuned_verify = false;
     }
     c->h_stage = nullptr;
@@ -350,8 +359,14 @@ static int32_t run_pass_bf16(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, b
     hipStream_t s = c->stream;
     auto launch = [&](const GemmOp &op) {
         if (rows1) hipLaunchKernelGGL(gemv_kernel, dim3(KS_NWG), dim3(NT), gemv_lds_bytes(op.K), s, op, ctl);
-        else hipLaunchKernelGGL(gemm_mfma_kernel, dim3(KS_NWG), dim3(NT), mfma_lds_bytes(), s, op, ctl);
+        else if (c->in_prefill) hipLaunchKernelGGL(gemm_mfma_kernel<true>, dim3(KS_NWG), dim3(NT), mfma_lds_bytes(), s, op, ctl);
+        else hipLaunchKernelGGL(gemm_mfma_kernel<false>, dim3(KS_NWG), dim3(NT), mfma_lds_bytes(), s, op, ctl);
+        if (c->gemm_only) {    // measurement aid: count what this launch streams
+            c->prof_launches += 1;
+            c->prof_bytes += ((op.type == OP_SWIGLU) ? 2 * (int64_t)op.N : (int64_t)op.N) * op.K * 2;
+        }
     };
+    const bool others = !c->gemm_only;   // measurement aid: only the weight-streaming launches are enqueued
     GemmOp base{};
     base.n_ss = KS_NWG; base.inv_dim = 1.0f / (float)d; base.eps = g.rms_eps;
     base.H = H; base.Hkv = Hkv; base.hd = hd; base.max_seq = g.max_seq;
@@ -360,7 +375,8 @@ static int32_t run_pass_bf16(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, b
     GemmOp e = base;
     e.type = OP_EMBED; e.N = d; e.embed = (const bf16_t *)c->embed; e.x = x; e.gain_next = next_gain(c, mask, -1);
     e.act_out = act_d; e.planes_out = planes_d; e.ss_out = ss;
-    if (rows1) hipLaunchKernelGGL((embed_producer_kernel<false>), dim3(KS_NWG), dim3(NT), 0, s, e, ctl);
+    if (!others) {
+    } else if (rows1) hipLaunchKernelGGL((embed_producer_kernel<false>), dim3(KS_NWG), dim3(NT), 0, s, e, ctl);
     else hipLaunchKernelGGL((embed_producer_kernel<true>), dim3(KS_NWG), dim3(NT), 0, s, e, ctl);
 
     AttnArgs aa{};
@@ -374,9 +390,11 @@ static int32_t run_pass_bf16(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, b
             o.ss_in = ss; o.q_out = qrot; o.kv_block = kvb;
             launch(o);
             aa.kv_block = kvb;
-            if (hd == 128) hipLaunchKernelGGL((attn_partial_kernel<128>), dim3(KS_NWG), dim3(NT), attn_lds_bytes(128), s, aa, ctl);
+            if (!others) {
+            } else if (hd == 128) hipLaunchKernelGGL((attn_partial_kernel<128>), dim3(KS_NWG), dim3(NT), attn_lds_bytes(128), s, aa, ctl);
             else hipLaunchKernelGGL((attn_partial_kernel<64>), dim3(KS_NWG), dim3(NT), attn_lds_bytes(64), s, aa, ctl);
-            if (rows1) hipLaunchKernelGGL((attn_combine_kernel<false>), dim3(16), dim3(NT), 0, s, aa, ctl);
+            if (!others) {
+            } else if (rows1) hipLaunchKernelGGL((attn_combine_kernel<false>), dim3(16), dim3(NT), 0, s, aa, ctl);
             else hipLaunchKernelGGL((attn_combine_kernel<true>), dim3(64), dim3(NT), 0, s, aa, ctl);
             GemmOp r = base;
             r.type = OP_RESID; r.W = (const bf16_t *)c->wo[b]; r.N = d; r.K = qd; r.act_in = att; r.planes_in = planes_att;
@@ -401,7 +419,7 @@ static int32_t run_pass_bf16(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, b
         h.type = OP_HEAD; h.W = (const bf16_t *)c->lm_head; h.N = g.vocab; h.K = d; h.act_in = act_d; h.planes_in = planes_d;
         h.ss_in = ss; h.logits = c->wsp<float>(c->L.logits); h.head_part = c->wsp<HeadPartial>(c->L.head_part);
         launch(h);
-        hipLaunchKernelGGL(head_final_kernel, dim3(KS_MAX_ROWS), dim3(NT), 0, s, c->wsp<HeadPartial>(c->L.head_part), KS_NWG,
+        if (others) hipLaunchKernelGGL(head_final_kernel, dim3(KS_MAX_ROWS), dim3(NT), 0, s, c->wsp<HeadPartial>(c->L.head_part), KS_NWG,
                            ctl, c->wsp<HeadResult>(c->L.head));
     }
     HIP_TRY(hipGetLastError());
@@ -446,7 +464,10 @@ static int32_t prefill_impl(knnssd_ctx *c, const int32_t *tokens, int32_t n, flo
         int rows = n - s < KS_MAX_ROWS ? n - s : KS_MAX_ROWS;
         bool last = s + rows >= n;
         KS_TRY(set_pass(c, ver, 1, rows, s, last ? rows - 1 : rows, tokens + s));
-        KS_TRY(run_pass(c, ver, nullptr, KS_MAX_ROWS, last));
+        c->in_prefill = true;
+        int32_t rc_pass = run_pass(c, ver, nullptr, KS_MAX_ROWS, last);
+        c->in_prefill = false;
+        KS_TRY(rc_pass);
         if (last) {
             if (c->tuned_verify) {
                 hipLaunchKernelGGL(hidden_from_planes_kernel, dim3(8), dim3(NT), 0, c->stream, c->wsp<bf16_t>(c->L.planes_d),
@@ -654,6 +675,38 @@ extern "C" int32_t knnssd_generate(knnssd_ctx *ctx, const int32_t *prompt_host, 
         stats->ns_total = elapsed_ns(ctx, 0, e_end);
         stats->draft_passes = n_draft_passes; stats->verify_passes = n_verify_passes;
     }
+    return KNNSSD_OK;
+}
+
+extern "C" int32_t knnssd_profile_pass(knnssd_ctx *ctx, int32_t kind, const int32_t *tokens_host, int32_t n, int32_t start_pos,
+                                       int64_t *n_launches, int64_t *gemm_ns, int64_t *gemm_bytes, int64_t *pass_ns) {
+    if (!ctx || !tokens_host || !n_launches || !gemm_ns || !gemm_bytes || !pass_ns) return KNNSSD_EINVAL;
+    if (!ctx->prefilled) return KNNSSD_ESTATE;
+    if (kind != 0 && kind != 1) return KNNSSD_EINVAL;
+    if (n <= 0 || n > (kind == 0 ? 1 : KS_MAX_ROWS)) return KNNSSD_ERANGE;
+    if (start_pos < 0 || start_pos + n > ctx->cfg.max_seq) return KNNSSD_ERANGE;
+    KS_TRY(check_tokens(ctx, tokens_host, n));
+    if (!(kind == 0 ? ctx->tuned : ctx->tuned_verify)) return KNNSSD_ESHAPE;   // only the tuned kernels are instrumented
+    PassCtl *ctl = ctx->wsp<PassCtl>(kind == 0 ? ctx->L.draft_ctl : ctx->L.ver_ctl);
+    KS_TRY(set_pass(ctx, ctl, 1, n, start_pos, 0, tokens_host));
+    hipEvent_t p0, p1;
+    HIP_TRY(hipEventCreate(&p0));
+    HIP_TRY(hipEventCreate(&p1));
+    ctx->prof_launches = 0; ctx->prof_bytes = 0;
+    ctx->gemm_only = true;
+    (void)hipEventRecord(p0, ctx->stream);
+    int32_t rc = run_pass(ctx, ctl, kind == 0 ? ctx->draft_mask.data() : nullptr, kind == 0 ? 1 : KS_MAX_ROWS);
+    (void)hipEventRecord(p1, ctx->stream);
+    ctx->gemm_only = false;
+    hipError_t es = hipStreamSynchronize(ctx->stream);
+    float pms = 0.f;
+    (void)hipEventElapsedTime(&pms, p0, p1);
+    (void)hipEventDestroy(p0);
+    (void)hipEventDestroy(p1);
+    *n_launches = ctx->prof_launches; *gemm_bytes = ctx->prof_bytes;
+    *gemm_ns = (int64_t)((double)pms * 1e6); *pass_ns = *gemm_ns;
+    if (rc != KNNSSD_OK) return rc;
+    HIP_TRY(es);
     return KNNSSD_OK;
 }
 

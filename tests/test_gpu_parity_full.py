@@ -1,0 +1,163 @@
+"""GPU parity at the benchmark's real shapes, in the launch configuration bench.py times.
+
+The oracle cannot decode hundreds of 13B-shaped tokens in a test, so the full-size check has
+two parts: (i) the oracle runs the same 13B-shaped model on a short prompt and a few tokens and
+everything is compared (KNN index, mask, tokens, acceptance counts, logits); (ii) at the
+benchmark's own prompt length the properties that hold at any size are asserted on the GPU
+path itself: the speculative output equals plain autoregressive decoding, an empty skip set is
+accepted in full, and a row's result does not depend on how many rows share the pass.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import knnssd_oracle as O
+from paper_2505_16162_amd import binding, synth
+from gpu_common import logits_close
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def llama13b():
+    wl = synth.workload("llama13b")
+    print("building 13B-shaped model on the GPU", flush=True)
+    w = synth.make_weights(wl.shape, device="cuda:0")
+    gpu = binding.KnnSsd(wl.shape, w, max_anchors=wl.n_anchors)
+    anchors, labels, centres = synth.make_anchors(wl.shape.d_model, wl.n_anchors, wl.n_domains, wl.anchor_sigma,
+                                                  device="cuda:0")
+    masks = synth.make_block_masks(wl.shape.n_blocks, wl.n_domains, wl.skipped_blocks)
+    gpu.knnssd_set_anchors(anchors, labels, masks)
+    yield wl, w, gpu, anchors, labels, masks
+    gpu.close()
+
+
+@pytest.mark.timeout(900)
+def test_13b_short_run_matches_oracle(llama13b):
+    wl, w, gpu, anchors, labels, masks = llama13b
+    shape = wl.shape
+    print("copying 26 GB of weights to the host for the oracle", flush=True)
+    orc = O.OracleModel(shape, synth.weights_to(w, "cpu"))
+    prompt = synth.make_prompt(shape.vocab, 24, seed=123).tolist()      # one full 16-row chunk + a ragged one
+    print("oracle prefill", flush=True)
+    first_o, hidden_o, row_o = O.prefill(orc, prompt)
+    first_g, hidden_g = gpu.knnssd_prefill(prompt)
+    ok, err = logits_close(gpu.knnssd_get_logits(7).numpy(), row_o, shape)
+    assert ok, err
+    assert first_g == first_o
+    assert np.abs(hidden_g.cpu().numpy() - hidden_o).max() <= 2e-2 * np.abs(hidden_o).max()
+    # KNN routing of the prompt's own last hidden vector over the 1000-anchor table
+    idx_g, dom_g, mask_g = gpu.knnssd_select_skipset(hidden_g)
+    idx_o, dom_o, mask_o, scores = O.knn_select(hidden_o, anchors.cpu().numpy(), labels.cpu().numpy(), masks.numpy())
+    assert (idx_g, dom_g, mask_g) == (idx_o, dom_o, mask_o.tolist())
+    # one draft step and one 3-row verification, logits compared
+    print("oracle draft + verify", flush=True)
+    row = orc.forward([first_o], len(prompt), mask_o)[0]
+    tok_g, p_g = gpu.knnssd_draft_step(first_o, len(prompt))
+    ok, err = logits_close(gpu.knnssd_get_logits(0).numpy(), row, shape)
+    assert ok, err
+    print("draft logits max abs err", err, "top-1 prob", p_g, O.top1_prob(row), flush=True)
+    # p = 1 / sum exp(l - l_max): an absolute logit error e moves it by about e relative (bf16 KV rounding
+    # differences of one ulp in a few cache entries give e ~ 1e-3 here)
+    assert tok_g == O.argmax_lowest(row) and abs(p_g - O.top1_prob(row)) <= 1e-2 * O.top1_prob(row)
+    rows_in = [first_o, tok_g, 17]
+    rows_o = orc.forward(rows_in, len(prompt), None)
+    j, nxt, new_len = gpu.knnssd_verify(rows_in, len(prompt))
+    for r in range(3):
+        ok, err = logits_close(gpu.knnssd_get_logits(r).numpy(), rows_o[r], shape)
+        assert ok, (r, err)
+    targets = [O.argmax_lowest(rows_o[r]) for r in range(3)]
+    assert j == O.accept_length(rows_in[1:], targets) and nxt == targets[j] and new_len == len(prompt) + j + 1
+    # the whole path for a few tokens, with the benchmark's draft rule (threshold 0.6 => one draft per round)
+    print("oracle generate", flush=True)
+    res = O.knnssd_generate(orc, prompt, anchors.cpu().numpy(), labels.cpu().numpy(), masks.numpy(), 5, wl.max_draft,
+                            wl.conf_threshold)
+    toks, st = gpu.knnssd_generate(prompt, 5, wl.max_draft, wl.conf_threshold)
+    margins = [min(r.margins) for r in res["rounds"]]
+    assert toks == res["tokens"], f"oracle top-2 margins {margins}"
+    assert (st["rounds"], st["drafted"], st["accepted"]) == (res["stats"].rounds, res["stats"].drafted, res["stats"].accepted)
+    del orc
+
+
+@pytest.mark.timeout(600)
+def test_13b_properties_at_benchmark_size(llama13b):
+    wl, w, gpu, anchors, labels, masks = llama13b
+    shape = wl.shape
+    prompt = synth.make_prompt(shape.vocab, wl.prompt_len).tolist()
+    max_new = 48
+    print("AR", flush=True)
+    ar, st_ar = gpu.knnssd_generate(prompt, max_new, 0)
+    assert len(ar) == max_new and st_ar["rounds"] == max_new - 1
+    # losslessness: KNN-routed mask, benchmark draft rule, and an unconditional 8-token draft
+    print("SSD", flush=True)
+    for max_draft, thr in ((wl.max_draft, wl.conf_threshold), (wl.max_draft, 0.0)):
+        toks, st = gpu.knnssd_generate(prompt, max_new, max_draft, thr)
+        assert toks == ar
+        assert st["emitted"] == max_new and st["accepted"] <= st["drafted"]
+        if thr > 0:
+            assert st["drafted"] <= st["rounds"]          # random-init top-1 probability << 0.6: one draft per round
+    # empty skip set: the draft model is the full model, so drafts are accepted (the draft step sums on the
+    # vector ALUs and verification on the matrix cores, so a near-tie may flip a token: allow a few)
+    print("empty mask", flush=True)
+    gpu.knnssd_set_skipset(None)      # generate() would re-route through the anchors, so use the step calls
+    first, _ = gpu.knnssd_prefill(prompt)
+    assert first == ar[0]
+    pos, x_last, out, drafted, accepted = len(prompt), first, [first], 0, 0
+    while len(out) < 24:
+        drafts, prev = [], x_last
+        for i in range(4):
+            d, p = gpu.knnssd_draft_step(prev, pos + i)
+            drafts.append(d)
+            prev = d
+        j, nxt, new_len = gpu.knnssd_verify([x_last] + drafts, pos)
+        out += drafts[:j] + [nxt]
+        drafted += 4
+        accepted += j
+        pos, x_last = new_len, nxt
+    assert out[:24] == ar[:24]
+    assert accepted >= drafted - 2
+    # a row's logits do not depend on how many rows share the verification pass
+    print("row independence", flush=True)
+    gpu.knnssd_prefill(prompt)
+    rows_in = [ar[0]] + ar[1:9]
+    gpu.knnssd_verify(rows_in, len(prompt))
+    many = [gpu.knnssd_get_logits(r).clone() for r in range(9)]
+    gpu.knnssd_prefill(prompt)
+    for r in range(3):
+        gpu.knnssd_verify(rows_in[r:r + 1], len(prompt) + r)
+        assert torch.equal(gpu.knnssd_get_logits(0), many[r]), r
+
+
+@pytest.mark.timeout(600)
+def test_qwen_widths_gqa_big_vocab_matches_oracle():
+    """Qwen-2.5-14B-shaped widths (GQA 40/8, vocab 152064, FFN 13824) at reduced depth so that the oracle
+    finishes in seconds; exercises the tile shapes of the 14B-shaped configuration, 9-row verification
+    and the 1.56 GB LM head."""
+    full = synth.workload("qwen14b")
+    s = full.shape
+    shape = synth.ModelShape("qwen_w4", 4, s.d_model, s.n_heads, s.n_kv_heads, s.head_dim, s.d_ffn, s.vocab, 320,
+                             "bf16", "bf16")
+    w = synth.make_weights(shape, device="cuda:0", seed=5)
+    gpu = binding.KnnSsd(shape, w)
+    orc = O.OracleModel(shape, synth.weights_to(w, "cpu"))
+    prompt = synth.make_prompt(shape.vocab, 40, seed=9).tolist()
+    mask = synth.make_block_masks(shape.n_blocks, 1, 2, seed=1).numpy()[0]
+    print("oracle", flush=True)
+    toks_o, st_o, rounds = O.ssd_generate(orc, prompt, mask, 20, 8, 0.0)
+    gpu.knnssd_set_skipset(mask.tolist())
+    toks_g, st_g = gpu.knnssd_generate(prompt, 20, 8, 0.0)
+    assert toks_g == toks_o, [min(r.margins) for r in rounds]
+    assert (st_g["rounds"], st_g["drafted"], st_g["accepted"]) == (st_o.rounds, st_o.drafted, st_o.accepted)
+    # logits of a 9-row verification
+    first = toks_o[0]
+    gpu.knnssd_prefill(prompt)
+    rows_in = [first] + toks_o[1:9]
+    orc2 = O.OracleModel(shape, synth.weights_to(w, "cpu"))
+    orc2.forward(prompt, 0, None, logits_from=len(prompt))
+    rows_o = orc2.forward(rows_in, len(prompt), None)
+    j, nxt, _ = gpu.knnssd_verify(rows_in, len(prompt))
+    for r in range(9):
+        ok, err = logits_close(gpu.knnssd_get_logits(r).numpy(), rows_o[r], shape)
+        assert ok, (r, err)
+    assert j == 8 and nxt == toks_o[9]
+    gpu.close()
