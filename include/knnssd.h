@@ -14,8 +14,10 @@
  *   - The caller owns every device buffer (weights, KV cache, workspace, anchor
  *     table) and the HIP stream; the library allocates no device memory. All
  *     buffers must stay valid until knnssd_destroy.
- *   - Every matrix is row-major [out_features][in_features]; weight_dtype says
- *     whether matrices hold fp32 or bf16 values. RMSNorm gains are always fp32.
+ *   - Every matrix is given row-major [out_features][in_features]; weight_dtype says
+ *     whether matrices hold fp32 or bf16 values. RMSNorm gains are always fp32. For the
+ *     tuned bf16 kernels the caller repacks each matrix once into stream order
+ *     (knnssd_pack_matrix) and sets cfg.weights_packed.
  *   - Skip mask layout: mask[2*b] = 1 skips the attention sublayer of block b,
  *     mask[2*b+1] = 1 skips its MLP sublayer (z_i = 1 means "skip", Sec. 3.1).
  *   - Activations, residual stream, RoPE, softmax and all accumulators are fp32;
@@ -56,6 +58,8 @@ typedef struct knnssd_model_cfg {
     float rms_eps;
     int32_t weight_dtype; /* KNNSSD_FP32 | KNNSSD_BF16 */
     int32_t kv_dtype;     /* KNNSSD_FP32 | KNNSSD_BF16 */
+    int32_t weights_packed; /* 1: wqkv/wo/wgu/wdown/lm_head are in stream order (knnssd_pack_matrix) and the
+                               tuned bf16 kernels run; 0: row-major, generic kernels. embed is always row-major. */
 } knnssd_model_cfg;
 
 /* Device pointers to the model. The four per-block members are HOST arrays of
@@ -93,6 +97,20 @@ typedef struct knnssd_stats {
 } knnssd_stats;
 
 typedef struct knnssd_ctx knnssd_ctx;
+
+/* Stream order. The tuned kernels read each weight matrix once per pass, front to back, in the
+ * order their wavefronts consume it; knnssd_pack_matrix rewrites a row-major bf16 matrix into
+ * that order (same size, out of place, one kernel on hip_stream; src and dst are device
+ * pointers, 16-byte aligned, and must not overlap). knnssd_pack_supported says whether a shape
+ * can use it (bf16 weights and cache, d_model, d_ffn and n_heads*head_dim multiples of 32). */
+#define KNNSSD_W_QKV 0      /* [(n_heads+2*n_kv_heads)*head_dim][d_model] */
+#define KNNSSD_W_O 1        /* [d_model][n_heads*head_dim]                */
+#define KNNSSD_W_GATE_UP 2  /* [2*d_ffn][d_model]                         */
+#define KNNSSD_W_DOWN 3     /* [d_model][d_ffn]                           */
+#define KNNSSD_W_LM_HEAD 4  /* [vocab][d_model]                           */
+int32_t knnssd_pack_supported(const knnssd_model_cfg *cfg);
+int32_t knnssd_pack_matrix(const knnssd_model_cfg *cfg, int32_t which, const void *src_dev, void *dst_dev,
+                           void *hip_stream);
 
 /* Bytes of device workspace / KV cache a context of this shape needs (0 if cfg is invalid). */
 size_t knnssd_workspace_bytes(const knnssd_model_cfg *cfg);

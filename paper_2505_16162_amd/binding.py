@@ -22,6 +22,7 @@ _DT = {"fp32": 0, "bf16": 1}
 
 EXPORTS = [
     "knnssd_workspace_bytes", "knnssd_kvcache_bytes", "knnssd_create", "knnssd_destroy",
+    "knnssd_pack_supported", "knnssd_pack_matrix",
     "knnssd_set_anchors", "knnssd_prefill", "knnssd_select_skipset", "knnssd_set_skipset",
     "knnssd_draft_step", "knnssd_verify", "knnssd_generate", "knnssd_profile_pass", "knnssd_get_logits", "knnssd_read_kv",
     "knnssd_strerror",
@@ -33,7 +34,7 @@ class ModelCfg(ctypes.Structure):
                 ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32), ("d_ffn", ctypes.c_int32),
                 ("vocab", ctypes.c_int32), ("max_seq", ctypes.c_int32), ("max_anchors", ctypes.c_int32),
                 ("rope_base", ctypes.c_float), ("rms_eps", ctypes.c_float),
-                ("weight_dtype", ctypes.c_int32), ("kv_dtype", ctypes.c_int32)]
+                ("weight_dtype", ctypes.c_int32), ("kv_dtype", ctypes.c_int32), ("weights_packed", ctypes.c_int32)]
 
 
 class Weights(ctypes.Structure):
@@ -81,6 +82,10 @@ def load_library() -> ctypes.CDLL:
     lib.knnssd_kvcache_bytes.argtypes = [ctypes.POINTER(ModelCfg)]
     lib.knnssd_create.restype = i32
     lib.knnssd_create.argtypes = [ctypes.POINTER(ModelCfg), ctypes.POINTER(Weights), vp, vp, vp, ctypes.POINTER(vp)]
+    lib.knnssd_pack_supported.restype = i32
+    lib.knnssd_pack_supported.argtypes = [ctypes.POINTER(ModelCfg)]
+    lib.knnssd_pack_matrix.restype = i32
+    lib.knnssd_pack_matrix.argtypes = [ctypes.POINTER(ModelCfg), i32, vp, vp, vp]
     lib.knnssd_destroy.restype = i32
     lib.knnssd_destroy.argtypes = [vp]
     lib.knnssd_set_anchors.restype = i32
@@ -117,7 +122,7 @@ def _check(rc: int):
 def make_cfg(shape, max_anchors: int = 0) -> ModelCfg:
     return ModelCfg(shape.n_blocks, shape.d_model, shape.n_heads, shape.n_kv_heads, shape.head_dim, shape.d_ffn,
                     shape.vocab, shape.max_seq, max_anchors, float(shape.rope_base), float(shape.rms_eps),
-                    _DT[shape.weight_dtype], _DT[shape.kv_dtype])
+                    _DT[shape.weight_dtype], _DT[shape.kv_dtype], 0)
 
 
 def _i32_array(values: Sequence[int]):
@@ -148,18 +153,36 @@ class KnnSsd:
             return t
 
         nb = shape.n_blocks
+        self.stream = stream if stream is not None else torch.cuda.current_stream(dev)
+        # Stream order: shapes the tuned kernels support get every matrix repacked once by the library
+        # (KNNSSD_GENERIC_KERNELS=1 keeps them row-major and runs the generic kernels, for debugging).
+        self.packed = bool(self.lib.knnssd_pack_supported(ctypes.byref(self.cfg))) and \
+            os.environ.get("KNNSSD_GENERIC_KERNELS", "0") != "1"
+        self.cfg.weights_packed = 1 if self.packed else 0
+
+        def matrix(t: torch.Tensor, which: int) -> torch.Tensor:
+            t = t.to(dev).contiguous()
+            if self.packed:
+                dst = torch.empty_like(t)
+                _check(self.lib.knnssd_pack_matrix(ctypes.byref(self.cfg), which, t.data_ptr(), dst.data_ptr(),
+                                                   ctypes.c_void_p(self.stream.cuda_stream)))
+                torch.cuda.synchronize(dev)     # the row-major copy may be freed once the pack kernel is done
+                t = dst
+            self._keep.append(t)
+            return t
+
         # fused row-major matrices the ABI asks for: [q;k;v] and [gate;up] stacked along rows
         blocks = weights["blocks"]
         wqkv, wo, wgu, wdown, an, mn = [], [], [], [], [], []
         for b in blocks:
-            wqkv.append(on_dev(torch.cat([b["wq"].to(dev), b["wk"].to(dev), b["wv"].to(dev)], 0)))
-            wo.append(on_dev(b["wo"]))
-            wgu.append(on_dev(torch.cat([b["wg"].to(dev), b["wu"].to(dev)], 0)))
-            wdown.append(on_dev(b["wd"]))
+            wqkv.append(matrix(torch.cat([b["wq"].to(dev), b["wk"].to(dev), b["wv"].to(dev)], 0), 0))
+            wo.append(matrix(b["wo"], 1))
+            wgu.append(matrix(torch.cat([b["wg"].to(dev), b["wu"].to(dev)], 0), 2))
+            wdown.append(matrix(b["wd"], 3))
             an.append(on_dev(b["attn_norm"].float()))
             mn.append(on_dev(b["mlp_norm"].float()))
         self.embed = on_dev(weights["embed"])
-        self.lm_head = on_dev(weights["lm_head"])
+        self.lm_head = matrix(weights["lm_head"], 4)
         self.final_norm = on_dev(weights["final_norm"].float())
 
         def ptr_array(ts):
@@ -171,7 +194,6 @@ class KnnSsd:
                          ptr_array(an), ptr_array(wqkv), ptr_array(wo), ptr_array(mn), ptr_array(wgu), ptr_array(wdown))
         self.kv = torch.zeros(kv_bytes, dtype=torch.uint8, device=dev)
         self.ws = torch.zeros(ws_bytes, dtype=torch.uint8, device=dev)
-        self.stream = stream if stream is not None else torch.cuda.current_stream(dev)
         h = ctypes.c_void_p()
         torch.cuda.synchronize(dev)
         _check(self.lib.knnssd_create(ctypes.byref(self.cfg), ctypes.byref(self.w), self.kv.data_ptr(),

@@ -2,11 +2,11 @@
 //
 // Everything here is bound by HBM bandwidth: a pass streams every retained weight matrix once.
 // The kernels therefore share one structure: a fixed grid of workgroups, each owning a balanced
-// share of every matrix's rows; inside a workgroup the wavefronts split that share into
-// contiguous 1 KB units (draft: flat row segments; verify: 16-row x 32-column MFMA operand
-// tiles with K split over the wavefronts), keep several 16-byte loads per lane in flight, and
-// meet once in LDS for the reduction and the fused epilogue (RoPE + KV-cache write, residual
-// add + next RMSNorm's operands, SwiGLU, LM-head arg-max partials).
+// share of every matrix's rows; the weights are stored in the order the wavefronts stream them
+// (units of <= 16 rows x 32 columns, the MFMA A operand), so every wavefront reads one contiguous
+// region with several 16-byte loads per lane in flight; the wavefronts meet once in LDS for the
+// reduction and the fused epilogue (RoPE + KV-cache write, residual add + next RMSNorm's
+// operands, SwiGLU, LM-head arg-max partials).
 //
 // RMSNorm is folded in without a pass of its own: the producer of a residual row writes
 // gain (.) x (the next norm's gain applied) plus its share of sum(x^2); the consumer adds the
@@ -24,7 +24,6 @@ namespace ks {
 constexpr int NT = 1024;       // threads per workgroup
 constexpr int NWV = NT / 64;   // wavefronts per workgroup
 constexpr int MAX_LROWS = 640; // most rows of one matrix a workgroup may own
-constexpr int KSEG = 512;      // bf16 elements one wavefront load covers (64 lanes x 16 bytes)
 constexpr int ATT_CHUNK = NWV * 16;  // positions per split-KV work item (fixed: results do not depend on context length)
 constexpr int ATT_PG = 4;      // (row, head) pairs per attention work item
 
@@ -260,107 +259,176 @@ __device__ __forceinline__ void gemm_epilogue(const GemmOp &op, const PassCtl *c
 }
 
 // ------------------------------------------------------------------------------------------
-// Draft step (one row): y = W x on flat 1 KB units. Each wavefront streams a contiguous range of
-// (row, 512-column segment) units of the workgroup's rows, 8 loads in flight twice over.
+// Stream order. The weight matrices are not read in row-major order: knnssd_pack_matrix rewrites
+// each of them once into the exact order the kernels stream it, so that every wavefront reads one
+// contiguous region of HBM with fully coalesced loads (row-major operand tiles, 16 rows x 64
+// bytes per load, measure about 30 % slower on MI355X). The order is:
+//
+//   workgroup (256 of them, balanced row shares, rows in build_row_table order)
+//     tile (T = ceil(R/16) tiles of rpt = ceil(R/T) <= 16 rows; the last one may be shorter)
+//       wavefront of the tile's lane: tl = 4, 2 or 1 tile lanes work on different tiles at once,
+//       the ksplit = 16 / tl wavefronts of a lane deal the columns among themselves in fixed
+//       512-column blocks (wavefront kpart owns the g = 16 / ksplit 32-column steps
+//       [kpart*g, kpart*g+g) of every block)
+//         unit = one 32-column step of the tile: rows_t x 64 bytes, stored as 4 column groups of
+//         rows_t 16-byte pieces (piece (kg, r) = 8 columns at 8*kg of row r), which is the A operand
+//         of v_mfma_f32_16x16x32_bf16 with lane = 16*kg + r.
+//
+// The draft GEMV and the verification GEMM read the same units; they differ only in the
+// arithmetic applied to a unit. The packed matrix has the size of the original.
 // ------------------------------------------------------------------------------------------
-struct UnitCursor { int lr, ks; };
+struct WgSplit {
+    int R, n_first;   // rows of this workgroup, rows of the first kind (rotary pairs / gate rows)
+    int T, rpt, tl, ksplit, g, gshift;
+    int KS, nfull, rem;   // 32-column steps in K, full 16-step blocks, steps of the last partial block
+    size_t wg_base;       // element offset of the workgroup's region in the packed matrix
+};
 
+__device__ __forceinline__ WgSplit make_split(const GemmOp &op, int wg, int nwg, int *rowidx) {
+    WgSplit s;
+    s.R = build_row_table(op, wg, nwg, rowidx, &s.n_first);
+    size_t rows_before;
+    if (op.type == OP_QKV) {
+        const int half = op.hd >> 1;
+        const long long P = (long long)(op.H + op.Hkv) * half, VR = (long long)op.Hkv * op.hd;
+        rows_before = (size_t)(2 * (P * wg / nwg) + VR * wg / nwg);
+    } else if (op.type == OP_SWIGLU) {
+        rows_before = (size_t)(2 * ((long long)op.N * wg / nwg));
+    } else {
+        rows_before = (size_t)((long long)op.N * wg / nwg);
+    }
+    s.wg_base = rows_before * op.K;
+    s.T = (s.R + 15) >> 4;
+    s.rpt = s.T ? (s.R + s.T - 1) / s.T : 0;
+    s.tl = s.T >= 4 ? 4 : (s.T >= 2 ? 2 : 1);
+    s.ksplit = NWV / s.tl;
+    s.g = 16 / s.ksplit;
+    s.gshift = (s.g == 4) ? 2 : (s.g == 2 ? 1 : 0);
+    s.KS = op.K >> 5;
+    s.nfull = s.KS >> 4;
+    s.rem = s.KS & 15;
+    return s;
+}
+
+// One wavefront's share of one tile.
+struct WaveTile {
+    bool have;          // this wavefront has a tile in this round
+    int t, rows_t;      // tile index, its row count
+    int cnt;            // 32-column steps this wavefront owns (over all of K)
+    int unit;           // elements per unit = rows_t * 32
+    size_t base;        // element offset of the wavefront's first unit in the packed matrix
+};
+
+__device__ __forceinline__ WaveTile wave_tile(const WgSplit &s, int K, int round, int tlane, int kpart) {
+    WaveTile w;
+    w.t = round * s.tl + tlane;
+    w.have = w.t < s.T;
+    w.rows_t = w.have ? min(s.rpt, s.R - w.t * s.rpt) : 1;
+    w.unit = w.rows_t * 32;
+    w.cnt = w.have ? s.nfull * s.g + min(max(s.rem - kpart * s.g, 0), s.g) : 0;
+    const int steps_before = s.nfull * s.g * kpart + min(s.rem, kpart * s.g);
+    w.base = s.wg_base + (size_t)(w.t * s.rpt) * K + (size_t)steps_before * w.unit;
+    return w;
+}
+
+// 32-column step (index within K) of a wavefront's u-th unit
+__device__ __forceinline__ int step_of_unit(const WgSplit &s, int kpart, int u) {
+    return ((u >> s.gshift) << 4) + kpart * s.g + (u & (s.g - 1));
+}
+
+// Rewrites a row-major matrix into stream order (run once per matrix when the model is loaded).
+__global__ __launch_bounds__(NT, 1) void pack_matrix_kernel(GemmOp op, const bf16_t *__restrict__ src, bf16_t *__restrict__ dst) {
+    __shared__ int rowidx[MAX_LROWS];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const WgSplit s = make_split(op, blockIdx.x, gridDim.x, rowidx);
+    __syncthreads();
+    const int tlane = wave / s.ksplit, kpart = wave - tlane * s.ksplit;
+    const int r16 = lane & 15, kg = lane >> 4;
+    for (int round = 0; round * s.tl < s.T; ++round) {
+        const WaveTile w = wave_tile(s, op.K, round, tlane, kpart);
+        if (!w.have || r16 >= w.rows_t) continue;
+        const bf16_t *srow = src + (size_t)rowidx[w.t * s.rpt + r16] * op.K + kg * 8;
+        bf16_t *d = dst + w.base + (size_t)(kg * w.rows_t + r16) * 8;
+        for (int u = 0; u < w.cnt; ++u) {
+            const u32x4 v = *reinterpret_cast<const u32x4 *>(srow + (size_t)step_of_unit(s, kpart, u) * 32);
+            *reinterpret_cast<u32x4 *>(d + (size_t)u * w.unit) = v;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Draft step (one row): y = W x on the vector ALUs. Each wavefront streams its units (eight 16-byte
+// loads per lane in flight), lane (kg, r) multiplies its 8 weights with x[32*step + 8*kg ..] from
+// LDS and keeps a private sum for row r; a tile ends with a 4-lane reduction over kg.
+// ------------------------------------------------------------------------------------------
 __device__ __forceinline__ void gemv_device(const GemmOp &op, const PassCtl *ctl, int wg, int nwg, char *lds) {
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int K = op.K;
-    const int S = (K + KSEG - 1) / KSEG;
-    float *xs = reinterpret_cast<float *>(lds);                 // [S*512]
-    float *part = xs + (size_t)S * KSEG;                        // [MAX_LROWS][NWV]
+    float *xs = reinterpret_cast<float *>(lds);                 // [K]
+    float *part = xs + K;                                       // [MAX_LROWS][NWV]
     int *rowidx = reinterpret_cast<int *>(part + MAX_LROWS * NWV);
-    float *scratch = reinterpret_cast<float *>(rowidx + MAX_LROWS);  // [4*NWV + KS_MAX_ROWS]
+    float *vals = reinterpret_cast<float *>(rowidx + MAX_LROWS);     // [MAX_LROWS]
+    float *scratch = vals + MAX_LROWS;                               // [4*NWV + KS_MAX_ROWS]
     float *rstd_s = scratch + 4 * NWV;
 
-    int n_first = 0;
-    const int R = build_row_table(op, wg, nwg, rowidx, &n_first);
-    for (int i = tid; i < R * NWV; i += NT) part[i] = 0.f;
-    __syncthreads();
+    const WgSplit s = make_split(op, wg, nwg, rowidx);
+    const int R = s.R;
+    const int tlane = wave / s.ksplit, kpart = wave - tlane * s.ksplit;
+    const int r16 = lane & 15, kg = lane >> 4;
 
-    const int total = R * S;
-    const int u0 = (int)((long long)total * wave / NWV), u1 = (int)((long long)total * (wave + 1) / NWV);
-    UnitCursor cl, cc;
-    cl.lr = u0 / S; cl.ks = u0 - cl.lr * S; cc = cl;
-    int left_l = u1 - u0, left_c = u1 - u0;
-
-    u32x4 wa[8], wb[8];
-    auto load_batch = [&](u32x4 *w) {
+    // first tile's first loads go out before the input vector is staged
+    WaveTile w = wave_tile(s, K, 0, tlane, kpart);
+    u32x4 wa[8];
+    auto load_batch = [&](const bf16_t *p, int u0, int cnt, int unit) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            if (left_l > 0) {
-                const int k = cl.ks * KSEG + lane * 8;
-                const bf16_t *p = op.W + (size_t)rowidx[cl.lr] * K + k;
-                u32x4 z = {0u, 0u, 0u, 0u};
-                w[i] = (k < K) ? __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p)) : z;
-                if (++cl.ks == S) { cl.ks = 0; ++cl.lr; }
-                --left_l;
-            }
-        }
+        for (int i = 0; i < 8; ++i)
+            if (u0 + i < cnt) wa[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p + (size_t)(u0 + i) * unit));
     };
-    float acc = 0.f;
-    auto compute_batch = [&](const u32x4 *w) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            if (left_c > 0) {
-                const float *xp = xs + cc.ks * KSEG + lane * 8;
-                float4 x0 = *reinterpret_cast<const float4 *>(xp), x1 = *reinterpret_cast<const float4 *>(xp + 4);
-                acc = dot8(w[i], x0, x1, acc);
-                if (cc.ks == S - 1 || left_c == 1) {
-                    float s = wave_sum(acc);
-                    if (lane == 0) part[cc.lr * NWV + wave] = s;
-                    acc = 0.f;
-                }
-                if (++cc.ks == S) { cc.ks = 0; ++cc.lr; }
-                --left_c;
-            }
-        }
-    };
+    const bf16_t *wp = op.W + w.base + (size_t)(kg * w.rows_t + min(r16, w.rows_t - 1)) * 8;
+    if (s.T > 0) load_batch(wp, 0, w.cnt, w.unit);
 
-    load_batch(wa);                       // weights are in flight while the input vector is staged
-    for (int i = tid * 4; i < S * KSEG; i += NT * 4) {
-        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (i < K) v = *reinterpret_cast<const float4 *>(op.act_in + i);
-        *reinterpret_cast<float4 *>(xs + i) = v;
-    }
+    for (int i = tid * 4; i < K; i += NT * 4) *reinterpret_cast<float4 *>(xs + i) = *reinterpret_cast<const float4 *>(op.act_in + i);
     if (wave == 0) {
         float r = op.ss_in ? rstd_from_shares(op, 0, lane) : 1.0f;
         if (lane == 0) rstd_s[0] = r;
     }
     __syncthreads();
-#if KS_GEMV_DB
-    while (left_c > 0) {
-        load_batch(wb);
-        compute_batch(wa);
-        load_batch(wa);
-        compute_batch(wb);
-    }
-#else
-    // one batch of eight 1 KB loads per wavefront at a time: with 16 wavefronts per compute unit that is
-    // 128 KB in flight per compute unit, which measures fastest on MI355X (more in flight is slower)
-    while (left_c > 0) {
-        compute_batch(wa);
-        load_batch(wa);
-    }
-#endif
-    __syncthreads();
-    // finished dot products: vals[lr] = sum over wavefronts, fixed order
-    float *vals = xs;   // the staged input is no longer needed
-    for (int t = tid; t < R; t += NT) {
-        float s = 0.f;
+
+    for (int round = 0; round * s.tl < s.T; ++round) {
+        if (round > 0) {
+            w = wave_tile(s, K, round, tlane, kpart);
+            wp = op.W + w.base + (size_t)(kg * w.rows_t + min(r16, w.rows_t - 1)) * 8;
+            load_batch(wp, 0, w.cnt, w.unit);
+        }
+        float acc = 0.f;
+        for (int u0 = 0; u0 < w.cnt; u0 += 8) {
 #pragma unroll
-        for (int w = 0; w < NWV; ++w) s += part[t * NWV + w];
-        vals[t] = s;
+            for (int i = 0; i < 8; ++i) {
+                if (u0 + i < w.cnt) {
+                    const float *xp = xs + step_of_unit(s, kpart, u0 + i) * 32 + kg * 8;
+                    const float4 x0 = *reinterpret_cast<const float4 *>(xp), x1 = *reinterpret_cast<const float4 *>(xp + 4);
+                    acc = dot8(wa[i], x0, x1, acc);
+                }
+            }
+            load_batch(wp, u0 + 8, w.cnt, w.unit);
+        }
+        acc += __shfl_xor(acc, 16, 64);
+        acc += __shfl_xor(acc, 32, 64);
+        if (w.have && kg == 0 && r16 < w.rows_t) part[(w.t * s.rpt + r16) * NWV + kpart] = acc;
     }
     __syncthreads();
-    gemm_epilogue<false>(op, ctl, wg, nwg, R, n_first, rowidx, vals, 1, rstd_s, ctl->head_from, 1, scratch);
+    // finished dot products: fixed-order sum over the wavefronts that shared the tile's columns
+    for (int t = tid; t < R; t += NT) {
+        float sum = 0.f;
+        for (int k = 0; k < s.ksplit; ++k) sum += part[t * NWV + k];
+        vals[t] = sum;
+    }
+    __syncthreads();
+    gemm_epilogue<false>(op, ctl, wg, nwg, R, s.n_first, rowidx, vals, 1, rstd_s, ctl->head_from, 1, scratch);
 }
 
 __host__ __device__ inline size_t gemv_lds_bytes(int K) {
-    const int S = (K + KSEG - 1) / KSEG;
-    return (size_t)S * KSEG * 4 + (size_t)MAX_LROWS * NWV * 4 + MAX_LROWS * 4 + (4 * NWV + KS_MAX_ROWS) * 4;
+    return (size_t)K * 4 + (size_t)MAX_LROWS * NWV * 4 + MAX_LROWS * 4 + MAX_LROWS * 4 + (4 * NWV + KS_MAX_ROWS) * 4;
 }
 
 __global__ __launch_bounds__(NT, 1) void gemv_kernel(GemmOp op, const PassCtl *ctl) {
@@ -370,14 +438,12 @@ __global__ __launch_bounds__(NT, 1) void gemv_kernel(GemmOp op, const PassCtl *c
 }
 
 // ------------------------------------------------------------------------------------------
-// Verification (up to 16 rows): Y = W X on the matrix cores. The weights are the A operand of
-// v_mfma_f32_16x16x32_bf16 (lane = (row l%16, 8 columns at 8*(l/16)): one 16-byte load per lane
-// and 16-row x 32-column tile), the token rows the B operand. Activations stay fp32-exact: each
-// value is the sum of three bf16 planes (hi + mid + lo), so a tile takes three MFMAs whose
-// bf16 x bf16 products are exact in the fp32 accumulator. The path is HBM-bound (<= 16 flop per
-// weight byte against a ridge of ~300), so the two extra MFMAs cost nothing.
-// K is split over the workgroup's wavefronts; a token column's result never depends on how
-// many other columns are live.
+// Verification (up to 16 rows): Y = W X on the matrix cores. A unit is the A operand of
+// v_mfma_f32_16x16x32_bf16 as stored (lane = 16*kg + r), the token rows are the B operand.
+// Activations stay fp32-exact: each value is the sum of three bf16 planes (hi + mid + lo), so a
+// unit takes three MFMAs whose bf16 x bf16 products are exact in the fp32 accumulator. The path is
+// HBM-bound (<= 16 flop per weight byte against a ridge of ~300), so the two extra MFMAs cost
+// nothing. A token row's result never depends on how many other rows are live.
 // ------------------------------------------------------------------------------------------
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -400,27 +466,22 @@ __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl
     float *rstd_s = scratch + 4 * NWV;
     const int n_rows = max(min(ctl->n_rows, KS_MAX_ROWS), 1);
 
-    int n_first = 0;
-    const int R = build_row_table(op, wg, nwg, rowidx, &n_first);
+    const WgSplit s = make_split(op, wg, nwg, rowidx);
+    const int R = s.R;
     for (int m = wave; m < KS_MAX_ROWS; m += NWV) {
         float r = (op.ss_in && m < n_rows) ? rstd_from_shares(op, m, lane) : 1.0f;
         if (lane == 0) rstd_s[m] = r;
     }
     __syncthreads();
 
-    // Work split inside the workgroup: the R rows form T tiles of equal height (<= 16 rows); `tl` tile lanes
-    // work on different tiles at the same time and the NWV / tl wavefronts of a lane split the columns.
-    const int T = (R + 15) >> 4;
-    const int rpt = T ? (R + T - 1) / T : 0;                           // rows per tile
-    const int tl = T >= 4 ? 4 : (T >= 2 ? 2 : 1);
-    const int ksplit = NWV / tl;
-    const int tlane = wave / ksplit, kpart = wave - tlane * ksplit;
+    const int tlane = wave / s.ksplit, kpart = wave - tlane * s.ksplit;
     const int r16 = lane & 15, kg = lane >> 4;
     const size_t plane = (size_t)KS_MAX_ROWS * K;
 
     // The token rows (B operand) are staged through LDS in column chunks shared by all wavefronts: only the
     // live rows are staged, so few rows mean long chunks (2 rows: 4096 columns, 16 rows: 512). A chunk is a
-    // multiple of 512 columns, so every wavefront of a tile lane gets whole 32-column steps of it.
+    // multiple of 512 columns, i.e. whole blocks of the column deal; the deal itself does not depend on the
+    // chunk length, so a row's sum is grouped the same way however many rows are live.
     int KC = (MFMA_BBUF / (3 * n_rows) - 16) / 2;
     KC = max(512, KC / 512 * 512);
     if (KC > K) KC = (K + 511) / 512 * 512;
@@ -451,42 +512,35 @@ __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl
             }
         }
     };
+    // units of chunk c this wavefront owns (they are consecutive in its stream)
+    auto chunk_count = [&](int c, bool have) {
+        const int cs = min(KC, K - c * KC) >> 5, nfull = cs >> 4, rem = cs & 15;
+        return have ? nfull * s.g + min(max(rem - kpart * s.g, 0), s.g) : 0;
+    };
 
-    for (int round = 0; round * tl < T; ++round) {   // T = 0 when this workgroup owns no rows
-        const int t = round * tl + tlane;            // this wavefront's tile (uniform per wavefront)
-        const bool have_tile = t < T;
+    for (int round = 0; round * s.tl < s.T; ++round) {   // T = 0 when this workgroup owns no rows
+        const WaveTile w = wave_tile(s, K, round, tlane, kpart);
         f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
-        // weights: lane = (row of the tile, 8-column group); dead rows re-read the tile's last live row
-        const int row_end = min((t + 1) * rpt, R);
-        const bf16_t *apt = op.W + (size_t)rowidx[have_tile ? min(t * rpt + r16, row_end - 1) : 0] * K + kg * 8;
-        constexpr int DA = 8;                        // 1 KB weight loads in flight per wavefront
+        // lane = (row of the tile, 8-column group); dead rows re-read the tile's last live row: their products land
+        // in accumulator rows that are never stored
+        const bf16_t *ap = op.W + w.base + (size_t)(kg * w.rows_t + min(r16, w.rows_t - 1)) * 8;
+        constexpr int DA = 8;                        // weight loads in flight per wavefront
         u32x4 a[DA];
-        // Columns are dealt to the wavefronts of a tile lane in fixed 512-column blocks: wavefront kpart owns
-        // the g = 16 / ksplit consecutive 32-column steps [kpart*g, kpart*g + g) of every block. The deal does
-        // not depend on the chunk length, hence not on the number of live token rows: a row's sum is always
-        // grouped the same way. Step u of this wavefront inside a chunk is block u / g, offset u % g.
-        const int g = 16 / ksplit, gshift = (g == 4) ? 2 : (g == 2 ? 1 : 0);
-        auto chunk_count = [&](int c) {
-            const int cs = min(KC, K - c * KC) >> 5, nfull = cs >> 4, rem = cs & 15;
-            return have_tile ? nfull * g + min(max(rem - kpart * g, 0), g) : 0;
-        };
-        auto step_of = [&](int u) { return ((u >> gshift) << 4) + kpart * g + (u & (g - 1)); };
-        int cnt = chunk_count(0);
+        int cnt = chunk_count(0, w.have);
         bchunk_load(0);
 #pragma unroll
         for (int j = 0; j < DA; ++j)
-            if (j < cnt) a[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(apt + (size_t)step_of(j) * 32));
+            if (j < cnt) a[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(ap + (size_t)j * w.unit));
         bchunk_store(0);
         __syncthreads();
         for (int c = 0; c < NC; ++c) {
             if (c + 1 < NC) bchunk_load(c + 1);
             const char *bsrc = bbuf + (c & 1) * MFMA_BBUF + (size_t)brow * bstride + kg * 16;
-            const bf16_t *ac = apt + (size_t)c * KC;
             for (int i = 0; i < cnt; i += DA) {
 #pragma unroll
                 for (int j = 0; j < DA; ++j) {
                     if (i + j < cnt) {
-                        const int ls = step_of(i + j);
+                        const int ls = step_of_unit(s, kpart, i + j);     // step within the chunk
                         const bf16x8 av = __builtin_bit_cast(bf16x8, a[j]);
 #pragma unroll
                         for (int p = 0; p < 3; ++p) {
@@ -494,17 +548,17 @@ __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl
                             acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bv), acc, 0, 0, 0);
                         }
                         if (i + j + DA < cnt)
-                            a[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(ac + (size_t)step_of(i + j + DA) * 32));
+                            a[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(ap + (size_t)(i + j + DA) * w.unit));
                     }
                 }
             }
+            ap += (size_t)cnt * w.unit;
             if (c + 1 < NC) {
                 // next chunk's first weight loads go out before the workgroup meets, so the stream never drains
-                cnt = chunk_count(c + 1);
-                const bf16_t *an = apt + (size_t)(c + 1) * KC;
+                cnt = chunk_count(c + 1, w.have);
 #pragma unroll
                 for (int j = 0; j < DA; ++j)
-                    if (j < cnt) a[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(an + (size_t)step_of(j) * 32));
+                    if (j < cnt) a[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(ap + (size_t)j * w.unit));
                 bchunk_store(c + 1);
             }
             __syncthreads();
@@ -516,18 +570,18 @@ __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl
             for (int q = 0; q < 4; ++q) rp[(4 * kg + q) * 16 + r16] = acc[q];
         }
         __syncthreads();
-        for (int i = tid; i < tl * 256; i += NT) {
-            const int l = i >> 8, e = i & 255, tt = round * tl + l, rit = e >> 4;
-            if (tt < T && rit < rpt && tt * rpt + rit < R) {
+        for (int i = tid; i < s.tl * 256; i += NT) {
+            const int l = i >> 8, e = i & 255, tt = round * s.tl + l, rit = e >> 4;
+            if (tt < s.T && rit < s.rpt && tt * s.rpt + rit < R) {
                 float sum = 0.f;
-                for (int w = 0; w < ksplit; ++w) sum += red[(size_t)(l * ksplit + w) * 256 + e];
-                vals[(tt * rpt + rit) * KS_MAX_ROWS + (e & 15)] = sum;
+                for (int k = 0; k < s.ksplit; ++k) sum += red[(size_t)(l * s.ksplit + k) * 256 + e];
+                vals[(tt * s.rpt + rit) * KS_MAX_ROWS + (e & 15)] = sum;
             }
         }
         __syncthreads();    // red and the staging buffers are reused by the next round
     }
     __syncthreads();
-    gemm_epilogue<true>(op, ctl, wg, nwg, R, n_first, rowidx, vals, KS_MAX_ROWS, rstd_s,
+    gemm_epilogue<true>(op, ctl, wg, nwg, R, s.n_first, rowidx, vals, KS_MAX_ROWS, rstd_s,
                         op.type == OP_HEAD ? ctl->head_from : 0, n_rows, scratch);
 }
 

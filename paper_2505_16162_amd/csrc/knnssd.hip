@@ -169,6 +169,7 @@ extern "C" int32_t knnssd_create(const knnssd_model_cfg *cfg, const knnssd_weigh
     *out = nullptr;
     if (!cfg_valid(cfg) || !w || !kv_dev || !ws_dev) return KNNSSD_EINVAL;
     if (!cfg_supported(cfg)) return KNNSSD_ESHAPE;
+    if (cfg->weights_packed && !tuned_ok(*cfg)) return KNNSSD_ESHAPE;
     if (((uintptr_t)kv_dev & 255) || ((uintptr_t)ws_dev & 255)) return KNNSSD_EINVAL;
     if (!w->embed || !w->lm_head || !w->final_norm) return KNNSSD_EINVAL;
     const int nb = cfg->n_blocks;
@@ -199,20 +200,19 @@ extern "C" int32_t knnssd_create(const knnssd_model_cfg *cfg, const knnssd_weigh
     c->anchors = nullptr; c->labels = nullptr; c->n_anchors = 0; c->n_domains = 0;
     c->draft_mask.assign((size_t)2 * nb, 0);
     c->prefilled = false; c->cache_len = 0;
-    c->tuned = tuned_ok(*cfg);
-    // debugging aid: KNNSSD_GENERIC_KERNELS=1 runs every shape on the generic kernels
-    if (const char *env = getenv("KNNSSD_GENERIC_KERNELS"))
-        if (env[0] == '1') c->tuned = false;
+    c->tuned = cfg->weights_packed != 0;     // stream-order weights <=> tuned kernels (checked above)
+    c->tuned_verify = c->tuned;
     if (c->tuned) {
         hipError_t ea = hipFuncSetAttribute((const void *)gemv_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, KS_MAX_DYN_LDS);
-        if (ea != hipSuccess) c->tuned = false;
-    }
-    c->tuned_verify = c->tuned && cfg->d_model % 32 == 0 && cfg->d_ffn % 32 == 0 && (cfg->n_heads * cfg->head_dim) % 32 == 0;
-    if (c->tuned_verify) {
-        hipError_t ea = hipFuncSetAttribute((const void *)gemm_mfma_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, KS_MAX_DYN_LDS);
+        if (ea == hipSuccess)
+            ea = hipFuncSetAttribute((const void *)gemm_mfma_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, KS_MAX_DYN_LDS);
         if (ea == hipSuccess)
             ea = hipFuncSetAttribute((const void *)gemm_mfma_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, KS_MAX_DYN_LDS);
-        if (ea != hipSuccess) c->tuned_verify = false;
+        if (ea != hipSuccess) {
+            snprintf(g_hip_err, sizeof(g_hip_err), "%s (hipFuncSetAttribute)", hipGetErrorString(ea));
+            delete c;
+            return KNNSSD_EHIP;
+        }
     }
     c->h_stage = nullptr;
     hipError_t e = hipHostMalloc((void **)&c->h_stage, 4096, hipHostMallocDefault);
@@ -234,6 +234,33 @@ extern "C" int32_t knnssd_create(const knnssd_model_cfg *cfg, const knnssd_weigh
         return KNNSSD_EHIP;
     }
     *out = c;
+    return KNNSSD_OK;
+}
+
+extern "C" int32_t knnssd_pack_supported(const knnssd_model_cfg *cfg) {
+    return (cfg_valid(cfg) && cfg_supported(cfg) && tuned_ok(*cfg)) ? 1 : 0;
+}
+
+extern "C" int32_t knnssd_pack_matrix(const knnssd_model_cfg *cfg, int32_t which, const void *src_dev, void *dst_dev,
+                                      void *hip_stream) {
+    if (!cfg || !src_dev || !dst_dev || src_dev == dst_dev) return KNNSSD_EINVAL;
+    if (!cfg_valid(cfg)) return KNNSSD_EINVAL;
+    if (!cfg_supported(cfg) || !tuned_ok(*cfg)) return KNNSSD_ESHAPE;
+    if (((uintptr_t)src_dev | (uintptr_t)dst_dev) & 15) return KNNSSD_EINVAL;
+    const int d = cfg->d_model, qd = cfg->n_heads * cfg->head_dim;
+    GemmOp op{};
+    op.H = cfg->n_heads; op.Hkv = cfg->n_kv_heads; op.hd = cfg->head_dim;
+    switch (which) {
+        case KNNSSD_W_QKV: op.type = OP_QKV; op.N = (cfg->n_heads + 2 * cfg->n_kv_heads) * cfg->head_dim; op.K = d; break;
+        case KNNSSD_W_O: op.type = OP_RESID; op.N = d; op.K = qd; break;
+        case KNNSSD_W_GATE_UP: op.type = OP_SWIGLU; op.N = cfg->d_ffn; op.K = d; break;
+        case KNNSSD_W_DOWN: op.type = OP_RESID; op.N = d; op.K = cfg->d_ffn; break;
+        case KNNSSD_W_LM_HEAD: op.type = OP_HEAD; op.N = cfg->vocab; op.K = d; break;
+        default: return KNNSSD_EINVAL;
+    }
+    hipLaunchKernelGGL(pack_matrix_kernel, dim3(KS_NWG), dim3(NT), 0, (hipStream_t)hip_stream, op, (const bf16_t *)src_dev,
+                       (bf16_t *)dst_dev);
+    HIP_TRY(hipGetLastError());
     return KNNSSD_OK;
 }
 
@@ -334,7 +361,11 @@ static bool tuned_ok(const knnssd_model_cfg &g) {
     if (per(g.vocab) > MAX_LROWS || 2 * per(g.d_ffn) > MAX_LROWS) return false;
     if (2 * per((long long)(g.n_heads + g.n_kv_heads) * g.head_dim / 2) + per((long long)g.n_kv_heads * g.head_dim) > MAX_LROWS) return false;
     if (per(g.d_model) > MAX_LROWS) return false;
-    if (gemv_lds_bytes(g.d_ffn) > KS_MAX_DYN_LDS || gemv_lds_bytes(g.n_heads * g.head_dim) > KS_MAX_DYN_LDS) return false;
+    // every reduction length is a whole number of 32-column MFMA steps
+    if (g.d_model % 32 || g.d_ffn % 32 || (g.n_heads * g.head_dim) % 32) return false;
+    if (gemv_lds_bytes(g.d_ffn) > KS_MAX_DYN_LDS || gemv_lds_bytes(g.n_heads * g.head_dim) > KS_MAX_DYN_LDS ||
+        gemv_lds_bytes(g.d_model) > KS_MAX_DYN_LDS)
+        return false;
     return true;
 }
 
