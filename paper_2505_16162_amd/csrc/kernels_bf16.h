@@ -59,6 +59,8 @@ struct GemmOp {
     HeadPartial *head_part;   // [KS_MAX_ROWS][gridDim]
     // OP_EMBED
     const bf16_t *embed;
+    // verification GEMM: LDS plan (dynamic LDS bytes of the launch, most rows any workgroup owns of this matrix)
+    int lds_bytes, max_rows;
 };
 
 __device__ __forceinline__ float bf_lo(unsigned int u) { return __uint_as_float(u << 16); }
@@ -448,51 +450,53 @@ __global__ __launch_bounds__(NT, 1) void gemv_kernel(GemmOp op, const PassCtl *c
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int MFMA_BBUF = 51200;   // bytes of one activation staging buffer in LDS (two of them)
+constexpr int MFMA_BQ = 5;          // 16-byte pieces of an activation chunk a thread may carry (chunk <= 80 KB)
 
-__host__ __device__ inline size_t mfma_lds_bytes() {
-    return (size_t)2 * MFMA_BBUF + (size_t)MAX_LROWS * KS_MAX_ROWS * 4 + (size_t)NWV * 256 * 4 + MAX_LROWS * 4 +
-           (4 * NWV + KS_MAX_ROWS) * 4;
+// LDS plan of the verification GEMM: [vals: max_rows x 16 floats][red: NWV x 256 floats][row table][scratch]
+// and two activation staging buffers sharing what is left of the dynamic LDS the launch asked for.
+__host__ __device__ inline size_t mfma_fixed_lds(int max_rows) {
+    return ((size_t)max_rows * KS_MAX_ROWS * 4 + (size_t)NWV * 256 * 4 + (size_t)max_rows * 4 + (4 * NWV + KS_MAX_ROWS) * 4 + 255) / 256 * 256;
+}
+__host__ __device__ inline int mfma_bbuf_bytes(size_t lds_total, int max_rows) {
+    long long b = ((long long)lds_total - (long long)mfma_fixed_lds(max_rows)) / 2 / 256 * 256;
+    const long long cap = (long long)MFMA_BQ * NT * 16;
+    return (int)(b > cap ? cap : b);
 }
 
 __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl *ctl, int wg, int nwg, char *lds) {
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int K = op.K;
-    char *bbuf = lds;                                                   // [2][MFMA_BBUF] activation chunks
-    float *vals = reinterpret_cast<float *>(lds + 2 * MFMA_BBUF);       // [MAX_LROWS][16]
-    float *red = vals + MAX_LROWS * KS_MAX_ROWS;                        // [NWV][256]
+    float *vals = reinterpret_cast<float *>(lds);                       // [max_rows][16]
+    float *red = vals + (size_t)op.max_rows * KS_MAX_ROWS;              // [NWV][256]
     int *rowidx = reinterpret_cast<int *>(red + NWV * 256);
-    float *scratch = reinterpret_cast<float *>(rowidx + MAX_LROWS);
+    float *scratch = reinterpret_cast<float *>(rowidx + op.max_rows);
     float *rstd_s = scratch + 4 * NWV;
+    const int BBUF = mfma_bbuf_bytes(op.lds_bytes, op.max_rows);
+    char *bbuf = lds + mfma_fixed_lds(op.max_rows);                     // [2][BBUF] activation chunks
     const int n_rows = max(min(ctl->n_rows, KS_MAX_ROWS), 1);
 
     const WgSplit s = make_split(op, wg, nwg, rowidx);
     const int R = s.R;
-    for (int m = wave; m < KS_MAX_ROWS; m += NWV) {
-        float r = (op.ss_in && m < n_rows) ? rstd_from_shares(op, m, lane) : 1.0f;
-        if (lane == 0) rstd_s[m] = r;
-    }
-    __syncthreads();
 
     const int tlane = wave / s.ksplit, kpart = wave - tlane * s.ksplit;
     const int r16 = lane & 15, kg = lane >> 4;
     const size_t plane = (size_t)KS_MAX_ROWS * K;
 
     // The token rows (B operand) are staged through LDS in column chunks shared by all wavefronts: only the
-    // live rows are staged, so few rows mean long chunks (2 rows: 4096 columns, 16 rows: 512). A chunk is a
-    // multiple of 512 columns, i.e. whole blocks of the column deal; the deal itself does not depend on the
-    // chunk length, so a row's sum is grouped the same way however many rows are live.
-    int KC = (MFMA_BBUF / (3 * n_rows) - 16) / 2;
+    // live rows are staged, so few rows mean long chunks (often the whole of K). A chunk is a multiple of 512
+    // columns, i.e. whole blocks of the column deal; the deal itself does not depend on the chunk length, so a
+    // row's sum is grouped the same way however many rows are live.
+    int KC = (BBUF / (3 * n_rows) - 16) / 2;
     KC = max(512, KC / 512 * 512);
     if (KC > K) KC = (K + 511) / 512 * 512;
     const int NC = (K + KC - 1) / KC;
     const int bstride = KC * 2 + 16;                                     // bytes per staged row (+16: LDS bank spread)
     const int brow = min(r16, n_rows - 1);                               // dead token lanes re-read the last live row
-    u32x4 breg[3];
-    auto bchunk_load = [&](int c) {          // global -> registers: 16-byte pieces of chunk c, up to 3 per thread
+    u32x4 breg[MFMA_BQ];
+    auto bchunk_load = [&](int c) {          // global -> registers: 16-byte pieces of chunk c
         const int cols = min(KC, K - c * KC), p8 = cols >> 3, pieces = 3 * n_rows * p8;
 #pragma unroll
-        for (int q = 0; q < 3; ++q) {
+        for (int q = 0; q < MFMA_BQ; ++q) {
             const int i = tid + q * NT;
             if (i < pieces) {
                 const int pr = i / p8, c8 = i - pr * p8, pl = pr / n_rows, row = pr - pl * n_rows;
@@ -502,9 +506,9 @@ __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl
     };
     auto bchunk_store = [&](int c) {         // registers -> LDS buffer c & 1
         const int cols = min(KC, K - c * KC), p8 = cols >> 3, pieces = 3 * n_rows * p8;
-        char *dst = bbuf + (c & 1) * MFMA_BBUF;
+        char *dst = bbuf + (c & 1) * BBUF;
 #pragma unroll
-        for (int q = 0; q < 3; ++q) {
+        for (int q = 0; q < MFMA_BQ; ++q) {
             const int i = tid + q * NT;
             if (i < pieces) {
                 const int pr = i / p8, c8 = i - pr * p8;
@@ -531,11 +535,18 @@ __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl
 #pragma unroll
         for (int j = 0; j < DA; ++j)
             if (j < cnt) a[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(ap + (size_t)j * w.unit));
+        if (round == 0) {
+            // per-row rsqrt(mean(x^2) + eps) while the first operands are in flight
+            for (int m = wave; m < KS_MAX_ROWS; m += NWV) {
+                float r = (op.ss_in && m < n_rows) ? rstd_from_shares(op, m, lane) : 1.0f;
+                if (lane == 0) rstd_s[m] = r;
+            }
+        }
         bchunk_store(0);
         __syncthreads();
         for (int c = 0; c < NC; ++c) {
             if (c + 1 < NC) bchunk_load(c + 1);
-            const char *bsrc = bbuf + (c & 1) * MFMA_BBUF + (size_t)brow * bstride + kg * 16;
+            const char *bsrc = bbuf + (c & 1) * BBUF + (size_t)brow * bstride + kg * 16;
             for (int i = 0; i < cnt; i += DA) {
 #pragma unroll
                 for (int j = 0; j < DA; ++j) {

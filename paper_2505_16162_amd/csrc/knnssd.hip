@@ -390,8 +390,16 @@ static int32_t run_pass_bf16(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, b
     hipStream_t s = c->stream;
     auto launch = [&](const GemmOp &op) {
         if (rows1) hipLaunchKernelGGL(gemv_kernel, dim3(KS_NWG), dim3(NT), gemv_lds_bytes(op.K), s, op, ctl);
-        else if (c->in_prefill) hipLaunchKernelGGL(gemm_mfma_kernel<true>, dim3(KS_NWG), dim3(NT), mfma_lds_bytes(), s, op, ctl);
-        else hipLaunchKernelGGL(gemm_mfma_kernel<false>, dim3(KS_NWG), dim3(NT), mfma_lds_bytes(), s, op, ctl);
+        else {
+            GemmOp v = op;
+            auto per = [&](long long n) { return (int)((n + KS_NWG - 1) / KS_NWG); };
+            if (v.type == OP_QKV) v.max_rows = 2 * per((long long)(H + Hkv) * hd / 2) + per((long long)Hkv * hd);
+            else if (v.type == OP_SWIGLU) v.max_rows = 2 * per(v.N);
+            else v.max_rows = per(v.N);
+            v.lds_bytes = (int)KS_MAX_DYN_LDS;
+            if (c->in_prefill) hipLaunchKernelGGL(gemm_mfma_kernel<true>, dim3(KS_NWG), dim3(NT), KS_MAX_DYN_LDS, s, v, ctl);
+            else hipLaunchKernelGGL(gemm_mfma_kernel<false>, dim3(KS_NWG), dim3(NT), KS_MAX_DYN_LDS, s, v, ctl);
+        }
         if (c->gemm_only) {    // measurement aid: count what this launch streams
             c->prof_launches += 1;
             c->prof_bytes += ((op.type == OP_SWIGLU) ? 2 * (int64_t)op.N : (int64_t)op.N) * op.K * 2;
