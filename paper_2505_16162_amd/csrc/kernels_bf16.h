@@ -61,6 +61,7 @@ struct GemmOp {
     const bf16_t *embed;
     // verification GEMM: LDS plan (dynamic LDS bytes of the launch, most rows any workgroup owns of this matrix)
     int lds_bytes, max_rows;
+    int n_rows;               // token rows of the pass as the host counts them (the same number the control block holds)
 };
 
 __device__ __forceinline__ float bf_lo(unsigned int u) { return __uint_as_float(u << 16); }
@@ -113,14 +114,6 @@ __device__ __forceinline__ int build_row_table(const GemmOp &op, int wg, int nwg
     return R;
 }
 
-// rsqrt(mean(x^2) + eps) of row m from the producers' shares, summed in a fixed order by one wavefront
-__device__ __forceinline__ float rstd_from_shares(const GemmOp &op, int m, int lane) {
-    float s = 0.f;
-    for (int i = lane; i < op.n_ss; i += 64) s += op.ss_in[(size_t)i * KS_MAX_ROWS + m];
-    s = wave_sum(s);
-    return 1.0f / sqrtf(s * op.inv_dim + op.eps);
-}
-
 // workgroup sum of one float per thread (NT threads); scratch: NWV floats of LDS
 __device__ __forceinline__ float block_sum(float v, float *scratch) {
     v = wave_sum(v);
@@ -159,7 +152,9 @@ __device__ __forceinline__ void store_act(const GemmOp &op, int m, int n, int ld
 template <bool PLANES>
 __device__ __forceinline__ void gemm_epilogue(const GemmOp &op, const PassCtl *ctl, int wg, int nwg, int R, int n_first,
                                               const int *rowidx, const float *vals, int ld, const float *rstd,
-                                              int row_lo, int n_rows, float *scratch) {
+                                              int row_lo, int n_rows, float *scratch, float xpre, float gpre) {
+    // xpre / gpre: OP_RESID only, the residual value and the next norm's gain of element i = tid (fetched early by
+    // the caller so that the tail of the kernel does not wait on memory)
     const int tid = threadIdx.x;
     if (op.type == OP_RESID) {
         // one thread per (row of W, token row): residual add, operands of the next norm, x^2 left in vals
@@ -169,9 +164,10 @@ __device__ __forceinline__ void gemm_epilogue(const GemmOp &op, const PassCtl *c
             float sq = 0.f;
             if (m < n_rows) {
                 const int n = rowidx[t];
-                const float xn = op.x[(size_t)m * op.N + n] + vals[i];
+                const bool pre = i == tid;
+                const float xn = (pre ? xpre : op.x[(size_t)m * op.N + n]) + vals[i];
                 op.x[(size_t)m * op.N + n] = xn;
-                store_act<PLANES>(op, m, n, op.N, op.gain_next[n] * xn);
+                store_act<PLANES>(op, m, n, op.N, (pre ? gpre : op.gain_next[n]) * xn);
                 sq = xn * xn;
             }
             vw[i] = sq;
@@ -378,7 +374,28 @@ __device__ __forceinline__ void gemv_device(const GemmOp &op, const PassCtl *ctl
     const int tlane = wave / s.ksplit, kpart = wave - tlane * s.ksplit;
     const int r16 = lane & 15, kg = lane >> 4;
 
-    // first tile's first loads go out before the input vector is staged
+    // Order of the first loads: the input vector and the norm's shares (small, cache hits) go out first and the
+    // first weight batch right behind them, before the pass control block has even been read; the vector is in
+    // LDS and the workgroup has met long before the weights arrive, so no wavefront sits on a full batch.
+    // Every load of this prologue is unconditional (addresses are clamped instead): only then does the compiler
+    // count the loads in flight exactly and wait for the small ones alone.
+    constexpr int XQ = 4;
+    u32x4 xr[XQ];
+#pragma unroll
+    for (int q = 0; q < XQ; ++q) xr[q] = *reinterpret_cast<const u32x4 *>(op.act_in + min((tid + q * NT) * 4, K - 4));
+    float sh[4];
+    {
+        const float *sp = op.ss_in ? op.ss_in : op.act_in;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) sh[j] = sp[op.ss_in ? (size_t)min(lane + 64 * j, op.n_ss - 1) * KS_MAX_ROWS : 0];
+    }
+    float xpre, gpre;
+    {
+        const bool resid = op.type == OP_RESID;
+        const int n = resid ? min((int)((long long)op.N * wg / nwg) + tid, op.N - 1) : 0;
+        xpre = (resid ? op.x : op.act_in)[n];
+        gpre = (resid ? op.gain_next : op.act_in)[n];
+    }
     WaveTile w = wave_tile(s, K, 0, tlane, kpart);
     u32x4 wa[8];
     auto load_batch = [&](const bf16_t *p, int u0, int cnt, int unit) {
@@ -387,11 +404,27 @@ __device__ __forceinline__ void gemv_device(const GemmOp &op, const PassCtl *ctl
             if (u0 + i < cnt) wa[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p + (size_t)(u0 + i) * unit));
     };
     const bf16_t *wp = op.W + w.base + (size_t)(kg * w.rows_t + min(r16, w.rows_t - 1)) * 8;
-    if (s.T > 0) load_batch(wp, 0, w.cnt, w.unit);
+    {
+        const bf16_t *p0 = w.cnt > 0 ? wp : op.W;      // a wavefront without units reads the matrix's first bytes
+        const int last = max(w.cnt - 1, 0);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) wa[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p0 + (size_t)min(i, last) * w.unit));
+    }
+    __builtin_amdgcn_sched_barrier(0);     // nothing that waits on a load may move up between the loads
+    if (!ctl->active) return;      // uniform; loads still in flight are dropped with the wavefront
 
-    for (int i = tid * 4; i < K; i += NT * 4) *reinterpret_cast<float4 *>(xs + i) = *reinterpret_cast<const float4 *>(op.act_in + i);
+    // (stores clamped like the loads: a duplicate writes the same value to the same place; a conditional store
+    // would pull its load down next to it)
+#pragma unroll
+    for (int q = 0; q < XQ; ++q) *reinterpret_cast<u32x4 *>(xs + min((tid + q * NT) * 4, K - 4)) = xr[q];
+    for (int i = (tid + XQ * NT) * 4; i < K; i += NT * 4) *reinterpret_cast<float4 *>(xs + i) = *reinterpret_cast<const float4 *>(op.act_in + i);
     if (wave == 0) {
-        float r = op.ss_in ? rstd_from_shares(op, 0, lane) : 1.0f;
+        float share = 0.f;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) share += (lane + 64 * j < op.n_ss) ? sh[j] : 0.f;
+        if (op.ss_in)
+            for (int i = lane + 256; i < op.n_ss; i += 64) share += op.ss_in[(size_t)i * KS_MAX_ROWS];
+        const float r = op.ss_in ? 1.0f / sqrtf(wave_sum(share) * op.inv_dim + op.eps) : 1.0f;
         if (lane == 0) rstd_s[0] = r;
     }
     __syncthreads();
@@ -426,7 +459,7 @@ __device__ __forceinline__ void gemv_device(const GemmOp &op, const PassCtl *ctl
         vals[t] = sum;
     }
     __syncthreads();
-    gemm_epilogue<false>(op, ctl, wg, nwg, R, s.n_first, rowidx, vals, 1, rstd_s, ctl->head_from, 1, scratch);
+    gemm_epilogue<false>(op, ctl, wg, nwg, R, s.n_first, rowidx, vals, 1, rstd_s, ctl->head_from, 1, scratch, xpre, gpre);
 }
 
 __host__ __device__ inline size_t gemv_lds_bytes(int K) {
@@ -435,7 +468,6 @@ __host__ __device__ inline size_t gemv_lds_bytes(int K) {
 
 __global__ __launch_bounds__(NT, 1) void gemv_kernel(GemmOp op, const PassCtl *ctl) {
     extern __shared__ __align__(16) char lds[];
-    if (!ctl->active) return;
     gemv_device(op, ctl, blockIdx.x, gridDim.x, lds);
 }
 
@@ -452,10 +484,10 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int MFMA_BQ = 5;          // 16-byte pieces of an activation chunk a thread may carry (chunk <= 80 KB)
 
-// LDS plan of the verification GEMM: [vals: max_rows x 16 floats][red: NWV x 256 floats][row table][scratch]
+// LDS plan of the verification GEMM: [vals: max_rows x 16 floats][red: 2 x NWV x 256 floats][row table][scratch]
 // and two activation staging buffers sharing what is left of the dynamic LDS the launch asked for.
 __host__ __device__ inline size_t mfma_fixed_lds(int max_rows) {
-    return ((size_t)max_rows * KS_MAX_ROWS * 4 + (size_t)NWV * 256 * 4 + (size_t)max_rows * 4 + (4 * NWV + KS_MAX_ROWS) * 4 + 255) / 256 * 256;
+    return ((size_t)max_rows * KS_MAX_ROWS * 4 + (size_t)2 * NWV * 256 * 4 + (size_t)max_rows * 4 + (4 * NWV + KS_MAX_ROWS) * 4 + 255) / 256 * 256;
 }
 __host__ __device__ inline int mfma_bbuf_bytes(size_t lds_total, int max_rows) {
     long long b = ((long long)lds_total - (long long)mfma_fixed_lds(max_rows)) / 2 / 256 * 256;
@@ -467,13 +499,13 @@ __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int K = op.K;
     float *vals = reinterpret_cast<float *>(lds);                       // [max_rows][16]
-    float *red = vals + (size_t)op.max_rows * KS_MAX_ROWS;              // [NWV][256]
-    int *rowidx = reinterpret_cast<int *>(red + NWV * 256);
+    float *red = vals + (size_t)op.max_rows * KS_MAX_ROWS;              // [2][NWV][256]
+    int *rowidx = reinterpret_cast<int *>(red + 2 * NWV * 256);
     float *scratch = reinterpret_cast<float *>(rowidx + op.max_rows);
     float *rstd_s = scratch + 4 * NWV;
     const int BBUF = mfma_bbuf_bytes(op.lds_bytes, op.max_rows);
     char *bbuf = lds + mfma_fixed_lds(op.max_rows);                     // [2][BBUF] activation chunks
-    const int n_rows = max(min(ctl->n_rows, KS_MAX_ROWS), 1);
+    const int n_rows = op.n_rows;                                       // the host's count; equals ctl->n_rows
 
     const WgSplit s = make_split(op, wg, nwg, rowidx);
     const int R = s.R;
@@ -496,24 +528,20 @@ __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl
     auto bchunk_load = [&](int c) {          // global -> registers: 16-byte pieces of chunk c
         const int cols = min(KC, K - c * KC), p8 = cols >> 3, pieces = 3 * n_rows * p8;
 #pragma unroll
-        for (int q = 0; q < MFMA_BQ; ++q) {
-            const int i = tid + q * NT;
-            if (i < pieces) {
-                const int pr = i / p8, c8 = i - pr * p8, pl = pr / n_rows, row = pr - pl * n_rows;
-                breg[q] = *reinterpret_cast<const u32x4 *>(op.planes_in + pl * plane + (size_t)row * K + (size_t)c * KC + c8 * 8);
-            }
+        for (int q = 0; q < MFMA_BQ; ++q) {      // unconditional loads (clamped), so that none of them is waited for on the spot
+            const int i = min(tid + q * NT, pieces - 1);
+            const int pr = i / p8, c8 = i - pr * p8, pl = pr / n_rows, row = pr - pl * n_rows;
+            breg[q] = *reinterpret_cast<const u32x4 *>(op.planes_in + pl * plane + (size_t)row * K + (size_t)c * KC + c8 * 8);
         }
     };
     auto bchunk_store = [&](int c) {         // registers -> LDS buffer c & 1
         const int cols = min(KC, K - c * KC), p8 = cols >> 3, pieces = 3 * n_rows * p8;
         char *dst = bbuf + (c & 1) * BBUF;
 #pragma unroll
-        for (int q = 0; q < MFMA_BQ; ++q) {
-            const int i = tid + q * NT;
-            if (i < pieces) {
-                const int pr = i / p8, c8 = i - pr * p8;
-                *reinterpret_cast<u32x4 *>(dst + (size_t)pr * bstride + c8 * 16) = breg[q];
-            }
+        for (int q = 0; q < MFMA_BQ; ++q) {      // clamped like the loads: a duplicate writes the same value to the same place
+            const int i = min(tid + q * NT, pieces - 1);
+            const int pr = i / p8, c8 = i - pr * p8;
+            *reinterpret_cast<u32x4 *>(dst + (size_t)pr * bstride + c8 * 16) = breg[q];
         }
     };
     // units of chunk c this wavefront owns (they are consecutive in its stream)
@@ -522,28 +550,61 @@ __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl
         return have ? nfull * s.g + min(max(rem - kpart * s.g, 0), s.g) : 0;
     };
 
+    // Order of the first loads: activations, norm shares and residual values (small, cache hits) go out first and
+    // the first weight batch right behind them, before the pass control block has been read. The activations
+    // are in LDS and the workgroup has met long before the weights arrive.
+    // Every load of this prologue is unconditional (addresses are clamped instead): only then does the compiler
+    // count the loads in flight exactly and wait for the small ones alone.
+    bchunk_load(0);
+    float sh[4];
+    {
+        const float *sp = op.ss_in ? op.ss_in : reinterpret_cast<const float *>(op.planes_in);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            sh[j] = sp[op.ss_in ? (size_t)min(lane + 64 * j, op.n_ss - 1) * KS_MAX_ROWS + min(wave, n_rows - 1) : 0];
+    }
+    float xpre, gpre;
+    {
+        const bool resid = op.type == OP_RESID;
+        const int n = resid ? min((int)((long long)op.N * wg / nwg) + (tid >> 4), op.N - 1) : 0;
+        const float *fallback = reinterpret_cast<const float *>(op.planes_in);
+        xpre = (resid ? op.x : fallback)[resid ? (size_t)min(tid & 15, n_rows - 1) * op.N + n : 0];
+        gpre = (resid ? op.gain_next : fallback)[n];
+    }
+
+    constexpr int DA = 8;                        // weight loads in flight per wavefront
+    u32x4 a[DA];
     for (int round = 0; round * s.tl < s.T; ++round) {   // T = 0 when this workgroup owns no rows
         const WaveTile w = wave_tile(s, K, round, tlane, kpart);
         f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
         // lane = (row of the tile, 8-column group); dead rows re-read the tile's last live row: their products land
         // in accumulator rows that are never stored
         const bf16_t *ap = op.W + w.base + (size_t)(kg * w.rows_t + min(r16, w.rows_t - 1)) * 8;
-        constexpr int DA = 8;                        // weight loads in flight per wavefront
-        u32x4 a[DA];
         int cnt = chunk_count(0, w.have);
-        bchunk_load(0);
+        const bool stage = round == 0 || NC > 1;     // a single chunk stays in LDS for every round
+        if (stage && round > 0) bchunk_load(0);
+        {
+            const bf16_t *p0 = cnt > 0 ? ap : op.W;        // a wavefront without units reads the matrix's first bytes
+            const int last = max(cnt - 1, 0);
 #pragma unroll
-        for (int j = 0; j < DA; ++j)
-            if (j < cnt) a[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(ap + (size_t)j * w.unit));
+            for (int j = 0; j < DA; ++j) a[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p0 + (size_t)min(j, last) * w.unit));
+        }
         if (round == 0) {
-            // per-row rsqrt(mean(x^2) + eps) while the first operands are in flight
-            for (int m = wave; m < KS_MAX_ROWS; m += NWV) {
-                float r = (op.ss_in && m < n_rows) ? rstd_from_shares(op, m, lane) : 1.0f;
-                if (lane == 0) rstd_s[m] = r;
+            if (!ctl->active) return;            // uniform; loads still in flight are dropped with the wavefront
+            if (wave < KS_MAX_ROWS) {
+                float share = 0.f;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) share += (lane + 64 * j < op.n_ss) ? sh[j] : 0.f;
+                if (op.ss_in && wave < n_rows)
+                    for (int i = lane + 256; i < op.n_ss; i += 64) share += op.ss_in[(size_t)i * KS_MAX_ROWS + wave];
+                const float r = (op.ss_in && wave < n_rows) ? 1.0f / sqrtf(wave_sum(share) * op.inv_dim + op.eps) : 1.0f;
+                if (lane == 0) rstd_s[wave] = r;
             }
         }
-        bchunk_store(0);
-        __syncthreads();
+        if (stage) {
+            bchunk_store(0);
+            __syncthreads();
+        }
         for (int c = 0; c < NC; ++c) {
             if (c + 1 < NC) bchunk_load(c + 1);
             const char *bsrc = bbuf + (c & 1) * BBUF + (size_t)brow * bstride + kg * 16;
@@ -567,40 +628,45 @@ __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl
             if (c + 1 < NC) {
                 // next chunk's first weight loads go out before the workgroup meets, so the stream never drains
                 cnt = chunk_count(c + 1, w.have);
+                {
+                    const bf16_t *p0 = cnt > 0 ? ap : op.W;        // a wavefront without units reads the matrix's first bytes
+                    const int last = max(cnt - 1, 0);
 #pragma unroll
-                for (int j = 0; j < DA; ++j)
-                    if (j < cnt) a[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(ap + (size_t)j * w.unit));
+                    for (int j = 0; j < DA; ++j) a[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p0 + (size_t)min(j, last) * w.unit));
+                }
                 bchunk_store(c + 1);
+                __syncthreads();
             }
-            __syncthreads();
         }
-        // partial tile of this wavefront -> LDS; lane holds D[row 4*kg + q][token r16]
+        // partial tile of this wavefront -> LDS; lane holds D[row 4*kg + q][token r16]. The partials of
+        // consecutive rounds alternate between two buffers, so one meeting per round is enough: a buffer is
+        // written again only after every wavefront has passed the next round's meeting, i.e. finished summing it.
+        float *redr = red + (size_t)(round & 1) * NWV * 256;
         {
-            float *rp = red + (size_t)wave * 256;
+            float *rp = redr + (size_t)wave * 256;
 #pragma unroll
             for (int q = 0; q < 4; ++q) rp[(4 * kg + q) * 16 + r16] = acc[q];
         }
-        __syncthreads();
+        __syncthreads();    // also: every wavefront is done with the staging buffers of this round
         for (int i = tid; i < s.tl * 256; i += NT) {
             const int l = i >> 8, e = i & 255, tt = round * s.tl + l, rit = e >> 4;
             if (tt < s.T && rit < s.rpt && tt * s.rpt + rit < R) {
                 float sum = 0.f;
-                for (int k = 0; k < s.ksplit; ++k) sum += red[(size_t)(l * s.ksplit + k) * 256 + e];
+                for (int k = 0; k < s.ksplit; ++k) sum += redr[(size_t)(l * s.ksplit + k) * 256 + e];
                 vals[(tt * s.rpt + rit) * KS_MAX_ROWS + (e & 15)] = sum;
             }
         }
-        __syncthreads();    // red and the staging buffers are reused by the next round
     }
+    if (s.T == 0 && !ctl->active) return;
     __syncthreads();
     gemm_epilogue<true>(op, ctl, wg, nwg, R, s.n_first, rowidx, vals, KS_MAX_ROWS, rstd_s,
-                        op.type == OP_HEAD ? ctl->head_from : 0, n_rows, scratch);
+                        op.type == OP_HEAD ? ctl->head_from : 0, n_rows, scratch, xpre, gpre);
 }
 
 // PREFILL only names the launch site (prompt chunks vs verification passes) so that a profile keeps the two apart
 template <bool PREFILL>
 __global__ __launch_bounds__(NT, 1) void gemm_mfma_kernel(GemmOp op, const PassCtl *ctl) {
     extern __shared__ __align__(16) char lds[];
-    if (!ctl->active) return;
     gemm_mfma_device(op, ctl, blockIdx.x, gridDim.x, lds);
 }
 

@@ -379,7 +379,7 @@ static const float *next_gain(const knnssd_ctx *c, const uint8_t *mask, int afte
 // One pass with the tuned bf16 kernels. rows1 = true: a draft step (one row, vector-ALU GEMV, fp32
 // activations); false: verification / prefill (up to 16 rows on the matrix cores, activations as
 // three bf16 planes). want_head = false skips the LM head (prefill chunks before the last).
-static int32_t run_pass_bf16(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, bool rows1, bool want_head) {
+static int32_t run_pass_bf16(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, bool rows1, bool want_head, int n_rows) {
     const knnssd_model_cfg &g = c->cfg;
     const int d = g.d_model, H = g.n_heads, Hkv = g.n_kv_heads, hd = g.head_dim, F = g.d_ffn;
     const int qd = H * hd, qkvd = (H + 2 * Hkv) * hd;
@@ -397,6 +397,7 @@ static int32_t run_pass_bf16(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, b
             else if (v.type == OP_SWIGLU) v.max_rows = 2 * per(v.N);
             else v.max_rows = per(v.N);
             v.lds_bytes = (int)KS_MAX_DYN_LDS;
+            v.n_rows = n_rows;
             if (c->in_prefill) hipLaunchKernelGGL(gemm_mfma_kernel<true>, dim3(KS_NWG), dim3(NT), KS_MAX_DYN_LDS, s, v, ctl);
             else hipLaunchKernelGGL(gemm_mfma_kernel<false>, dim3(KS_NWG), dim3(NT), KS_MAX_DYN_LDS, s, v, ctl);
         }
@@ -465,11 +466,13 @@ static int32_t run_pass_bf16(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, b
     return KNNSSD_OK;
 }
 
-// mr: 1 for a draft step, KS_MAX_ROWS for verification / prefill
-static int32_t run_pass(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, int mr, bool want_head = true) {
+// mr: 1 for a draft step, KS_MAX_ROWS for verification / prefill; n_rows: the rows the control block will hold when
+// the pass runs (the host always knows the count, the device fills in the contents)
+static int32_t run_pass(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, int mr, int n_rows, bool want_head = true) {
     const bool wb = c->cfg.weight_dtype == KNNSSD_BF16, kb = c->cfg.kv_dtype == KNNSSD_BF16;
-    if (mr == 1 && c->tuned) return run_pass_bf16(c, ctl, mask, true, true);
-    if (mr != 1 && c->tuned_verify) return run_pass_bf16(c, ctl, mask, false, want_head);
+    if (n_rows < 1 || n_rows > mr) return KNNSSD_ERANGE;
+    if (mr == 1 && c->tuned) return run_pass_bf16(c, ctl, mask, true, true, 1);
+    if (mr != 1 && c->tuned_verify) return run_pass_bf16(c, ctl, mask, false, want_head, n_rows);
     if (mr == 1) {
         if (wb && kb) return run_pass_t<bf16_t, bf16_t, 1>(c, ctl, mask);
         if (wb && !kb) return run_pass_t<bf16_t, float, 1>(c, ctl, mask);
@@ -504,7 +507,7 @@ static int32_t prefill_impl(knnssd_ctx *c, const int32_t *tokens, int32_t n, flo
         bool last = s + rows >= n;
         KS_TRY(set_pass(c, ver, 1, rows, s, last ? rows - 1 : rows, tokens + s));
         c->in_prefill = true;
-        int32_t rc_pass = run_pass(c, ver, nullptr, KS_MAX_ROWS, last);
+        int32_t rc_pass = run_pass(c, ver, nullptr, KS_MAX_ROWS, rows, last);
         c->in_prefill = false;
         KS_TRY(rc_pass);
         if (last) {
@@ -585,7 +588,7 @@ extern "C" int32_t knnssd_draft_step(knnssd_ctx *ctx, int32_t token_in, int32_t 
     if (token_in < 0 || token_in >= ctx->cfg.vocab) return KNNSSD_ERANGE;
     PassCtl *dr = ctx->wsp<PassCtl>(ctx->L.draft_ctl);
     KS_TRY(set_pass(ctx, dr, 1, 1, pos, 0, &token_in));
-    KS_TRY(run_pass(ctx, dr, ctx->draft_mask.data(), 1));
+    KS_TRY(run_pass(ctx, dr, ctx->draft_mask.data(), 1, 1));
     KS_TRY(read_back(ctx, ctx->wsp<HeadResult>(ctx->L.head), sizeof(HeadResult)));
     HeadResult hr;
     memcpy(&hr, ctx->h_stage, sizeof(hr));
@@ -603,7 +606,7 @@ extern "C" int32_t knnssd_verify(knnssd_ctx *ctx, const int32_t *tokens_host, in
     KS_TRY(check_tokens(ctx, tokens_host, n));
     PassCtl *ver = ctx->wsp<PassCtl>(ctx->L.ver_ctl);
     KS_TRY(set_pass(ctx, ver, 1, n, start_pos, 0, tokens_host));
-    KS_TRY(run_pass(ctx, ver, nullptr, KS_MAX_ROWS));
+    KS_TRY(run_pass(ctx, ver, nullptr, KS_MAX_ROWS, n));
     int32_t *out3 = ctx->wsp<int32_t>(ctx->L.out3);
     hipLaunchKernelGGL(verify_accept_kernel, dim3(1), dim3(1), 0, ctx->stream, ver, ctx->wsp<HeadResult>(ctx->L.head), out3);
     HIP_TRY(hipGetLastError());
@@ -668,14 +671,18 @@ extern "C" int32_t knnssd_generate(knnssd_ctx *ctx, const int32_t *prompt_host, 
     int64_t n_draft_passes = 0, n_verify_passes = 0;
     std::vector<size_t> round_ev;  // triples of event indices
     bool done = gen->max_new <= 1;
+    int32_t emitted_host = 1;     // the host mirrors the round control far enough to know each pass's row count
     while (!done) {
         hipLaunchKernelGGL(round_begin_kernel, dim3(1), dim3(1), 0, s, st, dr);
         size_t ea = ev++;
         KS_TRY(mark(ctx, ea));
-        for (int i = 0; i < gen->max_draft; ++i) {
-            KS_TRY(run_pass(ctx, dr, ctx->draft_mask.data(), 1));
+        int kmax = gen->max_new - emitted_host - 1;
+        if (kmax > gen->max_draft) kmax = gen->max_draft;
+        int k_host = 0;
+        for (int i = 0; i < kmax; ++i) {
+            KS_TRY(run_pass(ctx, dr, ctx->draft_mask.data(), 1, 1));
             hipLaunchKernelGGL(draft_end_kernel, dim3(1), dim3(1), 0, s, st, dr, head);
-            ++n_draft_passes;
+            ++n_draft_passes; ++k_host;
             // the host decides whether to enqueue another draft pass
             KS_TRY(read_back(ctx, &dr->active, 4));
             if (!ctx->h_stage[0]) break;
@@ -683,14 +690,15 @@ extern "C" int32_t knnssd_generate(knnssd_ctx *ctx, const int32_t *prompt_host, 
         size_t eb = ev++;
         KS_TRY(mark(ctx, eb));
         hipLaunchKernelGGL(verify_begin_kernel, dim3(1), dim3(1), 0, s, st, ver);
-        KS_TRY(run_pass(ctx, ver, nullptr, KS_MAX_ROWS));
+        KS_TRY(run_pass(ctx, ver, nullptr, KS_MAX_ROWS, k_host + 1));
         hipLaunchKernelGGL(accept_kernel, dim3(1), dim3(1), 0, s, st, head, out_dev);
         ++n_verify_passes;
         size_t ec = ev++;
         KS_TRY(mark(ctx, ec));
         round_ev.push_back(ea); round_ev.push_back(eb); round_ev.push_back(ec);
-        KS_TRY(read_back(ctx, &st->done, 4));
-        done = ctx->h_stage[0] != 0;
+        KS_TRY(read_back(ctx, &st->emitted, 4));
+        emitted_host = ctx->h_stage[0];
+        done = emitted_host >= gen->max_new;
     }
     size_t e_end = ev++;
     KS_TRY(mark(ctx, e_end));
@@ -734,7 +742,7 @@ extern "C" int32_t knnssd_profile_pass(knnssd_ctx *ctx, int32_t kind, const int3
     ctx->prof_launches = 0; ctx->prof_bytes = 0;
     ctx->gemm_only = true;
     (void)hipEventRecord(p0, ctx->stream);
-    int32_t rc = run_pass(ctx, ctl, kind == 0 ? ctx->draft_mask.data() : nullptr, kind == 0 ? 1 : KS_MAX_ROWS);
+    int32_t rc = run_pass(ctx, ctl, kind == 0 ? ctx->draft_mask.data() : nullptr, kind == 0 ? 1 : KS_MAX_ROWS, n);
     (void)hipEventRecord(p1, ctx->stream);
     ctx->gemm_only = false;
     hipError_t es = hipStreamSynchronize(ctx->stream);
