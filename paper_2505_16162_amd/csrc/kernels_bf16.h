@@ -758,25 +758,23 @@ __device__ __forceinline__ void attn_partial_device(const AttnArgs &a, const Pas
         const int p_base = pg * ATT_PG;
         const int n_p = min(ATT_PG, P - p_base);
         __syncthreads();   // previous item's LDS reads are done
-        for (int i = tid; i < n_p * HD; i += NT) {
-            const int pl = i / HD, dim = i - pl * HD, p = p_base + pl;
-            const int m = p / group, h = kvh * group + (p - m * group);
-            qs[pl * HD + dim] = a.q[(size_t)m * a.H * HD + h * HD + dim];
-        }
-        // this wavefront's 16 positions of K and V
+        // this wavefront's 16 positions of K and V (issued before the queries are staged)
         const int pos0 = chunk * ATT_CHUNK + wave * 16;
         const bf16_t *kc = a.kv_block + (size_t)kvh * kv_head_stride;
         const bf16_t *vc = a.kv_block + ((size_t)a.Hkv + kvh) * kv_head_stride;
         u32x4 kf[STEPS], vf[STEPS];
 #pragma unroll
         for (int s = 0; s < STEPS; ++s) {
-            const int pos = pos0 + s * PPS + ps;
-            u32x4 z = {0u, 0u, 0u, 0u};
-            kf[s] = z; vf[s] = z;
-            if (pos < start + n_rows) {
-                kf[s] = *reinterpret_cast<const u32x4 *>(kc + (size_t)pos * HD + dg * 8);
-                vf[s] = *reinterpret_cast<const u32x4 *>(vc + (size_t)pos * HD + dg * 8);
-            }
+            // unconditional loads (a position past the end re-reads the last live one; its score is masked below):
+            // a load under a divergent branch would be waited for on the spot, one round trip after the other
+            const int pos = min(pos0 + s * PPS + ps, start + n_rows - 1);
+            kf[s] = *reinterpret_cast<const u32x4 *>(kc + (size_t)pos * HD + dg * 8);
+            vf[s] = *reinterpret_cast<const u32x4 *>(vc + (size_t)pos * HD + dg * 8);
+        }
+        for (int i = tid; i < n_p * HD; i += NT) {
+            const int pl = i / HD, dim = i - pl * HD, p = p_base + pl;
+            const int m = p / group, h = kvh * group + (p - m * group);
+            qs[pl * HD + dim] = a.q[(size_t)m * a.H * HD + h * HD + dim];
         }
         __syncthreads();
         for (int pl = 0; pl < n_p; ++pl) {
