@@ -27,6 +27,53 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+COPY_BYTES = 1 << 30          # size of the calibration copy of --traffic-probe
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "gemm_mfma_kernel_llama13b_hbm_traffic.md")
+
+
+def traffic_parse(fetch_csv, write_csv):
+    """Per-launch HBM traffic of the verification GEMM from two `rocprofv3 --pmc` runs of
+    `bench.py --traffic-probe` (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch). Each counter is scaled by
+    what it reads for the plain copy of COPY_BYTES in the same run."""
+    import csv
+
+    def per_kernel(path, counter):
+        rows = [r for r in csv.DictReader(open(path)) if r["Counter_Name"] == counter]
+        rows.sort(key=lambda r: int(r["Dispatch_Id"]))
+        copy, gemm = None, []
+        for r in rows:
+            name = r["Kernel_Name"]
+            if "gemm_mfma_kernel<false>" in name:
+                gemm.append(float(r["Counter_Value"]))
+            elif "MulFunctor" in name and not gemm:
+                copy = float(r["Counter_Value"])           # the last multiply before the passes is the calibration copy
+        return copy, gemm
+
+    out = {}
+    for tag, path, counter in (("read", fetch_csv, "FETCH_SIZE"), ("write", write_csv, "WRITE_SIZE")):
+        copy, gemm = per_kernel(path, counter)
+        copy_v = copy
+        scale = COPY_BYTES / (copy_v * 1024.0)             # true bytes per counted byte
+        out[tag] = {"copy_counter_KiB": copy_v, "scale": scale, "launches": len(gemm),
+                    "gemm_avg_KiB": sum(gemm) / len(gemm), "bytes_per_launch": scale * 1024.0 * sum(gemm) / len(gemm)}
+    total = out["read"]["bytes_per_launch"] + out["write"]["bytes_per_launch"]
+    for tag in ("read", "write"):
+        o = out[tag]
+        print(f"{tag}: copy of {COPY_BYTES} B counted as {o['copy_counter_KiB']:.0f} KiB -> scale {o['scale']:.4f}; "
+              f"gemm_mfma_kernel<false>: {o['launches']} launches, avg counter {o['gemm_avg_KiB']:.0f} KiB "
+              f"-> {o['bytes_per_launch']:.0f} B per launch")
+    print(f"traffic_bytes_per_launch: {total:.0f}")
+
+
+def recorded_traffic():
+    """HBM bytes per launch of the verification GEMM as last measured with the counters (None if never)."""
+    try:
+        for line in open(TRAFFIC_FILE):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
 
 
 def pass_bytes(shape, mask, ctx, rows):
@@ -58,7 +105,15 @@ def main():
     ap.add_argument("--cpu-tokens", type=int, default=6, help="tokens the CPU oracle decodes for its baseline")
     ap.add_argument("--max-new", type=int, default=0, help="override the workload's generation length")
     ap.add_argument("--prompt-len", type=int, default=0, help="override the workload's prompt length")
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="run under `rocprofv3 --pmc FETCH_SIZE` (or WRITE_SIZE): one plain 1 GiB copy for calibration, "
+                         "then verification passes with only the weight-streaming launches; prints nothing else")
+    ap.add_argument("--traffic-parse", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"),
+                    help="summarise the two counter_collection.csv files written by the --traffic-probe runs")
     args = ap.parse_args()
+    if args.traffic_parse:
+        traffic_parse(*args.traffic_parse)
+        return
     if args.gpus != 1:
         print("bench.py: this build is a single-GPU path; run with --gpus 1 "
               "(independent samples would shard round-robin over GPUs with no communication)", file=sys.stderr)
@@ -87,6 +142,19 @@ def main():
     prompt = synth.make_prompt(shape.vocab, prompt_len).tolist()
     torch.cuda.synchronize()
     t_setup = time.time() - t0
+
+    if args.traffic_probe:
+        src = torch.empty(COPY_BYTES // 4, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        torch.mul(src, 1.0, out=dst)         # the calibration kernel: a plain elementwise copy, reads and writes COPY_BYTES
+        torch.cuda.synchronize()
+        gpu.knnssd_prefill(prompt)
+        for _ in range(3):
+            gpu.knnssd_profile_pass(1, prompt[:2], prompt_len)
+        torch.cuda.synchronize()
+        gpu.close()
+        return
 
     def one_step():
         return gpu.knnssd_generate(prompt, max_new, wl.max_draft, wl.conf_threshold)
@@ -143,7 +211,8 @@ def main():
         roof = {"bound": "hbm", "kernel": "gemm_mfma_kernel<false> (verification GEMM: the 161 launches of one pass, "
                                           "back to back between two HIP events)",
                 "achieved": round(gemm_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(gemm_gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                "frac": round(gemm_gbs / HBM_PEAK_GBS, 4),
+                "traffic": recorded_traffic() if args.workload == "llama13b" else None,
                 "launches_per_pass": acc["n_launches"] // reps,
                 "avg_launch_us": round(acc["gemm_ns"] * 1e-3 / acc["n_launches"], 2),
                 "avg_bytes_per_launch": acc["gemm_bytes"] // acc["n_launches"],
@@ -172,6 +241,12 @@ def main():
         "mean_generated_length_M": round((agg["emitted"] - args.steps) / max(agg["rounds"], 1), 4),
         "acceptance_rate_alpha": round(agg["accepted"] / max(agg["drafted"], 1), 4),
         "drafts_per_round": round(agg["drafted"] / max(agg["rounds"], 1), 3),
+        # App. C.2 accounting with the measured pass times: a round costs k draft steps + one verification and
+        # emits M tokens, plain decoding costs one verification-sized pass per token
+        "ssd_over_ar_from_pass_times": round(
+            ((agg["emitted"] - args.steps) / max(agg["rounds"], 1)) * (1e3 / ar_tps)
+            / ((agg["drafted"] / max(agg["rounds"], 1)) * draft_ms + verify_ms), 4),
+        "cost_ratio_draft_over_verify": round(draft_ms / verify_ms, 4) if verify_ms else None,
         "verify_pass": {"ms": round(verify_ms, 4), "GB": round(vb / 1e9, 3), "GBps": round(verify_gbs, 1),
                         "frac_of_peak": round(verify_gbs / HBM_PEAK_GBS, 4)},
         "draft_pass": {"ms": round(draft_ms, 4), "GB": round(db / 1e9, 3), "GBps": round(draft_gbs, 1),

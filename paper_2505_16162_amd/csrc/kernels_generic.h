@@ -405,14 +405,17 @@ __global__ void round_begin_kernel(GenState *st, PassCtl *draft) {
     draft->tok[0] = st->x_last;
 }
 
-__global__ void draft_end_kernel(GenState *st, PassCtl *draft, const HeadResult *res) {
-    if (!draft->active) return;
+// host_flag (may be null): pinned host word that receives the pass's new `active` value, so the host can decide on
+// the next draft step after a plain stream synchronisation, without a copy
+__global__ void draft_end_kernel(GenState *st, PassCtl *draft, const HeadResult *res, int32_t *host_flag) {
+    if (!draft->active) { if (host_flag) *host_flag = 0; return; }
     int k = st->k;
     int d = res->tok[0]; float p = res->prob[0];
     st->drafts[k] = d; st->draft_p[k] = p;
     k += 1; st->k = k; st->draft_passes += 1;
     bool stop = (k >= st->kmax) || (st->conf_thr > 0.f && p < st->conf_thr);
     draft->active = stop ? 0 : 1;
+    if (host_flag) *host_flag = stop ? 0 : 1;
     draft->tok[0] = d;
     draft->start = st->cache_len + k;
 }
@@ -426,8 +429,9 @@ __global__ void verify_begin_kernel(const GenState *st, PassCtl *ver) {
 
 // Greedy acceptance and rollback: keep the leading drafts that equal the full model's own
 // token, emit the model's next token after them, move the cache length behind the last kept row.
-__global__ void accept_kernel(GenState *st, const HeadResult *res, int32_t *out_tokens) {
-    if (st->done) return;
+// host_emitted (may be null): pinned host word that receives the new count of emitted tokens
+__global__ void accept_kernel(GenState *st, const HeadResult *res, int32_t *out_tokens, int32_t *host_emitted) {
+    if (st->done) { if (host_emitted) *host_emitted = st->emitted; return; }
     int k = st->k, j = 0;
     while (j < k && st->drafts[j] == res->tok[j]) ++j;
     int e = st->emitted;
@@ -439,6 +443,7 @@ __global__ void accept_kernel(GenState *st, const HeadResult *res, int32_t *out_
     st->n_accepted = j;
     st->rounds += 1; st->drafted += k; st->accepted += j;
     if (st->emitted >= st->max_new) st->done = 1;
+    if (host_emitted) *host_emitted = st->emitted;
 }
 
 // Acceptance for a stand-alone verification call: rows tok[0..n-1] = [x_last, d_1..d_k].

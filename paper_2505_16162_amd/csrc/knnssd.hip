@@ -129,6 +129,7 @@ struct knnssd_ctx {
     int32_t cache_len;
     // pinned host staging for small read-backs
     int32_t *h_stage;
+    int32_t *d_flags;   // device view of h_stage + 512: words the round-control kernels write for the host
     std::vector<hipEvent_t> events;
     // knnssd_profile_pass: enqueue only the weight-streaming launches of a pass and count them
     bool gemm_only = false;
@@ -218,6 +219,14 @@ extern "C" int32_t knnssd_create(const knnssd_model_cfg *cfg, const knnssd_weigh
     hipError_t e = hipHostMalloc((void **)&c->h_stage, 4096, hipHostMallocDefault);
     if (e != hipSuccess) {
         snprintf(g_hip_err, sizeof(g_hip_err), "%s (hipHostMalloc)", hipGetErrorString(e));
+        delete c;
+        return KNNSSD_EHIP;
+    }
+    c->d_flags = nullptr;
+    e = hipHostGetDevicePointer((void **)&c->d_flags, c->h_stage + 512, 0);
+    if (e != hipSuccess) {
+        snprintf(g_hip_err, sizeof(g_hip_err), "%s (hipHostGetDevicePointer)", hipGetErrorString(e));
+        hipHostFree(c->h_stage);
         delete c;
         return KNNSSD_EHIP;
     }
@@ -681,23 +690,23 @@ extern "C" int32_t knnssd_generate(knnssd_ctx *ctx, const int32_t *prompt_host, 
         int k_host = 0;
         for (int i = 0; i < kmax; ++i) {
             KS_TRY(run_pass(ctx, dr, ctx->draft_mask.data(), 1, 1));
-            hipLaunchKernelGGL(draft_end_kernel, dim3(1), dim3(1), 0, s, st, dr, head);
+            hipLaunchKernelGGL(draft_end_kernel, dim3(1), dim3(1), 0, s, st, dr, head, ctx->d_flags);
             ++n_draft_passes; ++k_host;
             // the host decides whether to enqueue another draft pass
-            KS_TRY(read_back(ctx, &dr->active, 4));
-            if (!ctx->h_stage[0]) break;
+            HIP_TRY(hipStreamSynchronize(s));
+            if (!((volatile int32_t *)ctx->h_stage)[512]) break;
         }
         size_t eb = ev++;
         KS_TRY(mark(ctx, eb));
         hipLaunchKernelGGL(verify_begin_kernel, dim3(1), dim3(1), 0, s, st, ver);
         KS_TRY(run_pass(ctx, ver, nullptr, KS_MAX_ROWS, k_host + 1));
-        hipLaunchKernelGGL(accept_kernel, dim3(1), dim3(1), 0, s, st, head, out_dev);
+        hipLaunchKernelGGL(accept_kernel, dim3(1), dim3(1), 0, s, st, head, out_dev, ctx->d_flags + 1);
         ++n_verify_passes;
         size_t ec = ev++;
         KS_TRY(mark(ctx, ec));
         round_ev.push_back(ea); round_ev.push_back(eb); round_ev.push_back(ec);
-        KS_TRY(read_back(ctx, &st->emitted, 4));
-        emitted_host = ctx->h_stage[0];
+        HIP_TRY(hipStreamSynchronize(s));
+        emitted_host = ((volatile int32_t *)ctx->h_stage)[513];
         done = emitted_host >= gen->max_new;
     }
     size_t e_end = ev++;
