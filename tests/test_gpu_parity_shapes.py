@@ -1,0 +1,113 @@
+"""GPU parity on further shapes and on the edges of the path: 7B-shaped widths, a context of several
+thousand positions (many split-KV chunks, the domain-shift stream's prompt length), and the degenerate
+cases of the round loop (one-token prompt, one or two tokens to generate, 16-row verification)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import knnssd_oracle as O
+from paper_2505_16162_amd import binding, synth
+from gpu_common import logits_close, make_pair
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.timeout(600)
+def test_llama7b_widths_match_oracle():
+    """7B-shaped widths (d 4096, 32 heads, FFN 11008: 43 FFN rows per workgroup, K = 11008 = 21.5 column blocks)
+    at reduced depth; draft with a block mask, verification of 5 rows, a short generation."""
+    s = synth.workload("llama7b").shape
+    shape = synth.ModelShape("llama7b_w3", 3, s.d_model, s.n_heads, s.n_kv_heads, s.head_dim, s.d_ffn, s.vocab, 200,
+                             "bf16", "bf16")
+    w = synth.make_weights(shape, device="cuda:0", seed=3)
+    gpu = binding.KnnSsd(shape, w)
+    orc = O.OracleModel(shape, synth.weights_to(w, "cpu"))
+    prompt = synth.make_prompt(shape.vocab, 45, seed=2).tolist()
+    mask = synth.make_block_masks(shape.n_blocks, 1, 1, seed=4).numpy()[0]
+    print("oracle generate", flush=True)
+    toks_o, st_o, rounds = O.ssd_generate(orc, prompt, mask, 12, 4, 0.0)
+    gpu.knnssd_set_skipset(mask.tolist())
+    print("gpu generate", flush=True)
+    toks_g, st_g = gpu.knnssd_generate(prompt, 12, 4, 0.0)
+    assert toks_g == toks_o, [min(r.margins) for r in rounds]
+    assert (st_g["rounds"], st_g["drafted"], st_g["accepted"]) == (st_o.rounds, st_o.drafted, st_o.accepted)
+    # logits: one draft step and a 5-row verification behind a fresh prefill
+    orc2 = O.OracleModel(shape, synth.weights_to(w, "cpu"))
+    first_o, _, _ = O.prefill(orc2, prompt)
+    first_g, _ = gpu.knnssd_prefill(prompt)
+    assert first_g == first_o
+    gpu.knnssd_draft_step(first_o, len(prompt))
+    row = orc2.forward([first_o], len(prompt), mask)[0]
+    ok, err = logits_close(gpu.knnssd_get_logits(0).numpy(), row, shape)
+    assert ok, err
+    rows_in = [first_o] + toks_o[1:5]
+    rows_o = orc2.forward(rows_in, len(prompt), None)
+    gpu.knnssd_verify(rows_in, len(prompt))
+    for r in range(5):
+        ok, err = logits_close(gpu.knnssd_get_logits(r).numpy(), rows_o[r], shape)
+        assert ok, (r, err)
+    gpu.close()
+
+
+@pytest.mark.timeout(900)
+def test_long_context_many_kv_chunks():
+    """Context of 4100+ positions (17 split-KV chunks of 256, the stream configuration's prompt length) on a
+    narrow model, so that the oracle's prefill stays in seconds: draft and verification logits, cached keys
+    at both ends, tokens of a short generation."""
+    shape = synth.small_shape("long_ctx", n_blocks=2, d_model=256, n_heads=4, n_kv_heads=2, head_dim=64, d_ffn=704,
+                              vocab=1200, max_seq=4200)
+    w, orc, gpu = make_pair(shape, seed=8, std=0.05)
+    P = 4101                                             # 256 full 16-row chunks + 5 rows; 17th KV chunk holds 5 positions
+    prompt = synth.make_prompt(shape.vocab, P, seed=6).tolist()
+    print("oracle prefill", flush=True)
+    first_o, hidden_o, row_o = O.prefill(orc, prompt)
+    print("gpu prefill", flush=True)
+    first_g, hidden_g = gpu.knnssd_prefill(prompt)
+    assert first_g == first_o
+    ok, err = logits_close(gpu.knnssd_get_logits((P - 1) % 16).numpy(), row_o, shape)
+    assert ok, err
+    for pos in (0, 255, 256, 4095, 4096, 4100):
+        kg, vg = gpu.knnssd_read_kv(1, pos)
+        ko, vo = orc.read_kv(1, pos)
+        assert np.abs(kg.numpy() - ko).max() <= 2e-2 * max(1.0, np.abs(ko).max())
+        assert np.abs(vg.numpy() - vo).max() <= 2e-2 * max(1.0, np.abs(vo).max())
+    mask = [0, 1, 0, 0]                                  # skip the MLP of block 0
+    gpu.knnssd_set_skipset(mask)
+    tok_g, _ = gpu.knnssd_draft_step(first_o, P)
+    row = orc.forward([first_o], P, np.array(mask, dtype=np.uint8))[0]
+    ok, err = logits_close(gpu.knnssd_get_logits(0).numpy(), row, shape)
+    assert ok, err
+    assert tok_g == O.argmax_lowest(row)
+    rows_in = [first_o, 5, 17, 1199, 0, 3, 3]
+    rows_o = orc.forward(rows_in, P, None)
+    gpu.knnssd_verify(rows_in, P)
+    for r in range(len(rows_in)):
+        ok, err = logits_close(gpu.knnssd_get_logits(r).numpy(), rows_o[r], shape)
+        assert ok, (r, err)
+    gpu.close()
+
+
+def test_round_loop_edges():
+    """One-token prompt; max_new of 1 (nothing after the prefill's token), 2 (one verification of one row) and 3;
+    16-row verification (15 drafts); a generation that ends exactly at max_seq."""
+    shape = synth.small_shape("edges", d_ffn=704, vocab=900, max_seq=64)
+    w, orc, gpu = make_pair(shape, seed=13, std=0.05)
+    mask = synth.make_block_masks(shape.n_blocks, 1, 1, seed=2).numpy()[0]
+    gpu.knnssd_set_skipset(mask.tolist())
+    for prompt_len, max_new, max_draft in ((1, 1, 4), (1, 2, 4), (1, 3, 4), (5, 20, 15), (7, 17, 1), (16, 33, 15)):
+        prompt = synth.make_prompt(shape.vocab, prompt_len, seed=prompt_len).tolist()
+        print("case", prompt_len, max_new, max_draft, flush=True)
+        o = O.OracleModel(shape, w)
+        toks_o, st_o, rounds = O.ssd_generate(o, prompt, mask, max_new, max_draft, 0.0)
+        toks_g, st_g = gpu.knnssd_generate(prompt, max_new, max_draft, 0.0)
+        assert toks_g == toks_o, (prompt_len, max_new, max_draft, [min(r.margins) for r in rounds if r.margins])
+        assert len(toks_g) == max_new
+        assert (st_g["rounds"], st_g["drafted"], st_g["accepted"]) == (st_o.rounds, st_o.drafted, st_o.accepted)
+    # the generation may use the cache up to its last position but not beyond: prompt + max_new + max_draft <= max_seq
+    prompt = synth.make_prompt(shape.vocab, 40, seed=1).tolist()
+    toks_g, _ = gpu.knnssd_generate(prompt, 20, 4, 0.0)          # 40 + 20 + 4 = 64 = max_seq
+    toks_o, _, _ = O.ssd_generate(O.OracleModel(shape, w), prompt, mask, 20, 4, 0.0)
+    assert toks_g == toks_o
+    with pytest.raises(binding.KnnSsdError):
+        gpu.knnssd_generate(prompt, 21, 4, 0.0)
+    gpu.close()
