@@ -105,6 +105,16 @@ def main():
     ap.add_argument("--cpu-tokens", type=int, default=6, help="tokens the CPU oracle decodes for its baseline")
     ap.add_argument("--max-new", type=int, default=0, help="override the workload's generation length")
     ap.add_argument("--prompt-len", type=int, default=0, help="override the workload's prompt length")
+    ap.add_argument("--stream", type=int, default=0, metavar="N",
+                    help="run N samples of the workload's domain-shift stream (Eq. 8) through the stream driver and "
+                         "print per-domain figures instead of the benchmark line (use with --workload llama13b_stream)")
+    ap.add_argument("--mix-ratio", type=float, default=0.7, help="r of Eq. 8 for --stream")
+    ap.add_argument("--no-reselect", action="store_true", help="--stream: keep the first sample's mask (fixed Self-SD)")
+    ap.add_argument("--beta-probe", action="store_true",
+                    help="measure the attention:MLP sublayer latency ratio (beta of Eq. 11) of the draft step and the "
+                         "cost coefficient of a sublayer-granular mask with skip ratios --s-attn / --s-mlp")
+    ap.add_argument("--s-attn", type=float, default=0.48)
+    ap.add_argument("--s-mlp", type=float, default=0.42)
     ap.add_argument("--traffic-probe", action="store_true",
                     help="run under `rocprofv3 --pmc FETCH_SIZE` (or WRITE_SIZE): one plain 1 GiB copy for calibration, "
                          "then verification passes with only the weight-streaming launches; prints nothing else")
@@ -143,6 +153,14 @@ def main():
     torch.cuda.synchronize()
     t_setup = time.time() - t0
 
+    if args.stream:
+        print(json.dumps(stream_mode(args, gpu, wl, shape, centres, prompt_len, max_new, dev)))
+        gpu.close()
+        return
+    if args.beta_probe:
+        print(json.dumps(beta_probe(args, gpu, shape, prompt, prompt_len)))
+        gpu.close()
+        return
     if args.traffic_probe:
         src = torch.empty(COPY_BYTES // 4, dtype=torch.float32, device=dev).normal_()
         dst = torch.empty_like(src)
@@ -259,6 +277,71 @@ def main():
         out["cpu_baseline"] = cpu_baseline(shape, w, wl, mask, args.cpu_tokens)
     print(json.dumps(out))
     gpu.close()
+
+
+def stream_mode(args, gpu, wl, shape, centres, prompt_len, max_new, dev):
+    """N samples of the domain-shift stream: fresh prompt and a query near the sample's domain centre per
+    sample, mask re-selected per sample by the 1-NN routing (or kept from the first sample)."""
+    from paper_2505_16162_amd import stream, synth
+    domains = stream.domain_sequence(wl.n_domains, args.stream, args.mix_ratio, seed=synth.BASE_SEED + 7)
+    res = stream.run_stream(
+        gpu, wl.n_domains, domains,
+        prompt_of=lambda i: synth.make_prompt(shape.vocab, prompt_len, seed=synth.BASE_SEED + 100 + i).tolist(),
+        query_of=lambda i, d: synth.make_domain_query(centres, d, wl.anchor_sigma, seed=synth.BASE_SEED + 1000 + i),
+        max_new=max_new, max_draft=wl.max_draft, conf_threshold=wl.conf_threshold, reselect=not args.no_reselect)
+
+    def fig(t):
+        return {"samples": t.samples, "routed_right": t.routed_right, "M": round(t.mean_generated_length, 4),
+                "alpha": round(t.acceptance_rate, 4), "tokens_per_s": round(t.tokens_per_s, 2),
+                "prefill_ms_per_sample": round(t.prefill_ns * 1e-6 / max(t.samples, 1), 2)}
+    return {"mode": "stream", "workload": shape.name, "samples": args.stream, "mix_ratio": args.mix_ratio,
+            "reselect": not args.no_reselect, "prompt_len": prompt_len, "max_new": max_new,
+            "domains": domains, "routed": res.routed, "total": fig(res.total),
+            "per_domain": {str(d): fig(t) for d, t in sorted(res.per_domain.items())}}
+
+
+def beta_probe(args, gpu, shape, prompt, prompt_len):
+    """Latency of the draft step with nothing / only attention / only MLP / everything retained gives the
+    per-sublayer costs and beta = attention : MLP latency (App. C.2); the cost coefficient of a
+    sublayer-granular mask is then compared with Eq. 11 evaluated at that beta."""
+    import torch
+    from paper_2505_16162_amd import synth
+    nb = shape.n_blocks
+    gpu.knnssd_prefill(prompt)
+    tok = prompt[0]
+
+    def draft_ms(mask, reps=12):
+        gpu.knnssd_set_skipset(mask)
+        gpu.knnssd_draft_step(tok, prompt_len)
+        torch.cuda.synchronize()
+        t0 = time.time()
+        for _ in range(reps):
+            gpu.knnssd_draft_step(tok, prompt_len)
+        torch.cuda.synchronize()
+        return (time.time() - t0) * 1e3 / reps
+
+    t_none = draft_ms([1] * (2 * nb))                       # embedding + LM head only
+    t_attn = draft_ms([0, 1] * nb)                          # every attention sublayer, no MLP
+    t_mlp = draft_ms([1, 0] * nb)                           # every MLP sublayer, no attention
+    t_full = draft_ms([0] * (2 * nb))
+    per_attn = (t_attn - t_none) / nb
+    per_mlp = (t_mlp - t_none) / nb
+    beta = per_attn / per_mlp
+    m = synth.make_sublayer_masks(nb, 1, args.s_attn, args.s_mlp, seed=synth.BASE_SEED + 9).numpy()[0]
+    s_attn = float(m[0::2].mean())
+    s_mlp = float(m[1::2].mean())
+    t_mask = draft_ms(m.tolist())
+    c_eq11 = ((1 - s_mlp) + (1 - s_attn) * beta) / (1 + beta)          # Eq. 11
+    c_uniform = 1 - (s_attn + s_mlp) / 2                               # c = 1 - s (Eq. 9's cost model)
+    return {"mode": "beta-probe", "workload": shape.name, "context": prompt_len,
+            "draft_ms": {"head_only": round(t_none, 4), "attention_only": round(t_attn, 4), "mlp_only": round(t_mlp, 4),
+                         "full": round(t_full, 4), "masked": round(t_mask, 4)},
+            "attention_sublayer_us": round(per_attn * 1e3, 2), "mlp_sublayer_us": round(per_mlp * 1e3, 2),
+            "beta": round(beta, 4), "mask_skip_ratio_attn": round(s_attn, 4), "mask_skip_ratio_mlp": round(s_mlp, 4),
+            "c_measured_sublayers_only": round((t_mask - t_none) / (t_full - t_none), 4),
+            "c_measured_whole_step": round(t_mask / t_full, 4),
+            "c_eq11_at_measured_beta": round(c_eq11, 4), "c_one_minus_s": round(c_uniform, 4),
+            "note": "times include one host round trip per draft step (the call returns the token)"}
 
 
 def cpu_baseline(shape, w_dev, wl, mask, n_tokens):

@@ -85,6 +85,8 @@ typedef struct knnssd_gen_cfg {
     int32_t max_draft;     /* K: draft tokens per round, 0 = plain autoregressive decoding, <= 15 */
     float conf_threshold;  /* > 0: stop drafting after the first draft whose top-1 probability is
                               below it (that token is still verified); <= 0 disables the rule    */
+    int32_t keep_mask;     /* 1: do not route this sample, draft with the mask already installed (the
+                              fixed-configuration Self-SD baseline of Sec. 5.1 on a task stream); 0: route */
 } knnssd_gen_cfg;
 
 /* Counters of one knnssd_generate call. Mean generated length M = (emitted-1)/rounds and
@@ -145,6 +147,11 @@ int32_t knnssd_select_skipset(knnssd_ctx *ctx, const float *query_dev, int32_t *
 
 /* Install a draft mask directly (2*n_blocks bytes on the host; NULL = skip nothing). */
 int32_t knnssd_set_skipset(knnssd_ctx *ctx, const uint8_t *mask_host);
+
+/* Anchor index n* and domain (Eq. 4-5) of the most recent routing on this context, whether it was made by
+ * knnssd_select_skipset or inside knnssd_generate; both are -1 before the first routing. Either output
+ * pointer may be NULL. Host-only, no device work. */
+int32_t knnssd_last_selection(const knnssd_ctx *ctx, int32_t *anchor_idx_out, int32_t *domain_out);
 
 /* One draft step (Eq. 7): token_in at position pos through M(z) with the installed mask; only
  * retained attention sublayers read and write the KV cache. Returns the arg-max token (lowest

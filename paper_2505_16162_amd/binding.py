@@ -23,7 +23,7 @@ _DT = {"fp32": 0, "bf16": 1}
 EXPORTS = [
     "knnssd_workspace_bytes", "knnssd_kvcache_bytes", "knnssd_create", "knnssd_destroy",
     "knnssd_pack_supported", "knnssd_pack_matrix",
-    "knnssd_set_anchors", "knnssd_prefill", "knnssd_select_skipset", "knnssd_set_skipset",
+    "knnssd_set_anchors", "knnssd_prefill", "knnssd_select_skipset", "knnssd_set_skipset", "knnssd_last_selection",
     "knnssd_draft_step", "knnssd_verify", "knnssd_generate", "knnssd_profile_pass", "knnssd_get_logits", "knnssd_read_kv",
     "knnssd_strerror",
 ]
@@ -44,7 +44,8 @@ class Weights(ctypes.Structure):
 
 
 class GenCfg(ctypes.Structure):
-    _fields_ = [("max_new", ctypes.c_int32), ("max_draft", ctypes.c_int32), ("conf_threshold", ctypes.c_float)]
+    _fields_ = [("max_new", ctypes.c_int32), ("max_draft", ctypes.c_int32), ("conf_threshold", ctypes.c_float),
+                ("keep_mask", ctypes.c_int32)]
 
 
 class Stats(ctypes.Structure):
@@ -96,6 +97,8 @@ def load_library() -> ctypes.CDLL:
     lib.knnssd_select_skipset.argtypes = [vp, vp, ctypes.POINTER(i32), ctypes.POINTER(i32), vp]
     lib.knnssd_set_skipset.restype = i32
     lib.knnssd_set_skipset.argtypes = [vp, vp]
+    lib.knnssd_last_selection.restype = i32
+    lib.knnssd_last_selection.argtypes = [vp, ctypes.POINTER(i32), ctypes.POINTER(i32)]
     lib.knnssd_draft_step.restype = i32
     lib.knnssd_draft_step.argtypes = [vp, i32, i32, ctypes.POINTER(i32), ctypes.POINTER(f32)]
     lib.knnssd_verify.restype = i32
@@ -258,10 +261,18 @@ class KnnSsd:
                                       ctypes.byref(new_len)))
         return int(j.value), int(nxt.value), int(new_len.value)
 
+    def knnssd_last_selection(self):
+        idx, dom = ctypes.c_int32(), ctypes.c_int32()
+        _check(self.lib.knnssd_last_selection(self.h, ctypes.byref(idx), ctypes.byref(dom)))
+        return int(idx.value), int(dom.value)
+
+    def last_domain(self) -> int:
+        return self.knnssd_last_selection()[1]
+
     def knnssd_generate(self, prompt: Sequence[int], max_new: int, max_draft: int, conf_threshold: float = 0.0,
-                        query: Optional[torch.Tensor] = None):
+                        query: Optional[torch.Tensor] = None, route: bool = True):
         toks = _i32_array(prompt)
-        gen = GenCfg(int(max_new), int(max_draft), float(conf_threshold))
+        gen = GenCfg(int(max_new), int(max_draft), float(conf_threshold), 0 if route else 1)
         out = (ctypes.c_int32 * max(int(max_new), 1))()
         n_out = ctypes.c_int32()
         st = Stats()

@@ -127,6 +127,7 @@ struct knnssd_ctx {
     bool tuned;         // shape fits the tuned bf16 draft kernels
     bool tuned_verify;  // ... and the matrix-core verification kernels (every K a multiple of 32)
     int32_t cache_len;
+    int32_t last_anchor = -1, last_domain = -1;   // most recent routing
     // pinned host staging for small read-backs
     int32_t *h_stage;
     int32_t *d_flags;   // device view of h_stage + 512: words the round-control kernels write for the host
@@ -573,6 +574,14 @@ static int32_t select_impl(knnssd_ctx *c, const float *query_dev, int32_t *idx_o
     c->draft_mask.assign(c->masks.begin() + ml * r.label, c->masks.begin() + ml * (r.label + 1));
     *idx_out = r.idx;
     *dom_out = r.label;
+    c->last_anchor = r.idx; c->last_domain = r.label;
+    return KNNSSD_OK;
+}
+
+extern "C" int32_t knnssd_last_selection(const knnssd_ctx *ctx, int32_t *anchor_idx_out, int32_t *domain_out) {
+    if (!ctx) return KNNSSD_EINVAL;
+    if (anchor_idx_out) *anchor_idx_out = ctx->last_anchor;
+    if (domain_out) *domain_out = ctx->last_domain;
     return KNNSSD_OK;
 }
 
@@ -664,7 +673,7 @@ extern "C" int32_t knnssd_generate(knnssd_ctx *ctx, const int32_t *prompt_host, 
     int32_t first = 0;
     KS_TRY(prefill_impl(ctx, prompt_host, n_prompt, nullptr, &first));
     KS_TRY(mark(ctx, ev++));  // 1
-    if (ctx->anchors && gen->max_draft > 0) {
+    if (ctx->anchors && gen->max_draft > 0 && !gen->keep_mask) {
         int32_t idx, dom;
         KS_TRY(select_impl(ctx, query_dev ? query_dev : ctx->wsp<float>(ctx->L.hidden_last), &idx, &dom));
     }
