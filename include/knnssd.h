@@ -119,10 +119,12 @@ size_t knnssd_workspace_bytes(const knnssd_model_cfg *cfg);
 size_t knnssd_kvcache_bytes(const knnssd_model_cfg *cfg);
 
 /* Create a context over caller-owned device memory. kv_dev and ws_dev must be 256-byte
- * aligned and at least as large as the two size queries say. hip_stream is a hipStream_t
- * (NULL = the null stream). Launches one set-up kernel (RoPE table) on the stream. */
-int32_t knnssd_create(const knnssd_model_cfg *cfg, const knnssd_weights *w, void *kv_dev, void *ws_dev,
-                      void *hip_stream, knnssd_ctx **out);
+ * aligned; kv_bytes and ws_bytes are the sizes of the two buffers, and the call fails with
+ * KNNSSD_EINVAL when either is smaller than the size queries above say for THIS cfg (the queries
+ * depend on every field, weights_packed included). hip_stream is a hipStream_t (NULL = the null
+ * stream). Launches one set-up kernel (RoPE table) on the stream. */
+int32_t knnssd_create(const knnssd_model_cfg *cfg, const knnssd_weights *w, void *kv_dev, size_t kv_bytes,
+                      void *ws_dev, size_t ws_bytes, void *hip_stream, knnssd_ctx **out);
 int32_t knnssd_destroy(knnssd_ctx *ctx);
 
 /* Anchor table for the KNN routing step (Sec. 4.1: anchors a_ij with their domain label i and

@@ -82,7 +82,8 @@ def load_library() -> ctypes.CDLL:
     lib.knnssd_kvcache_bytes.restype = ctypes.c_size_t
     lib.knnssd_kvcache_bytes.argtypes = [ctypes.POINTER(ModelCfg)]
     lib.knnssd_create.restype = i32
-    lib.knnssd_create.argtypes = [ctypes.POINTER(ModelCfg), ctypes.POINTER(Weights), vp, vp, vp, ctypes.POINTER(vp)]
+    lib.knnssd_create.argtypes = [ctypes.POINTER(ModelCfg), ctypes.POINTER(Weights), vp, ctypes.c_size_t, vp, ctypes.c_size_t, vp,
+                                  ctypes.POINTER(vp)]
     lib.knnssd_pack_supported.restype = i32
     lib.knnssd_pack_supported.argtypes = [ctypes.POINTER(ModelCfg)]
     lib.knnssd_pack_matrix.restype = i32
@@ -143,9 +144,7 @@ class KnnSsd:
         if self.device.type != "cuda":
             raise ValueError("the decode path runs on the GPU only")
         self.cfg = make_cfg(shape, max_anchors)
-        ws_bytes = self.lib.knnssd_workspace_bytes(ctypes.byref(self.cfg))
-        kv_bytes = self.lib.knnssd_kvcache_bytes(ctypes.byref(self.cfg))
-        if ws_bytes == 0 or kv_bytes == 0:
+        if self.lib.knnssd_workspace_bytes(ctypes.byref(self.cfg)) == 0:
             raise KnnSsdError(-2, "shape not supported")
         self._keep: List = []
         dev = self.device
@@ -162,6 +161,11 @@ class KnnSsd:
         self.packed = bool(self.lib.knnssd_pack_supported(ctypes.byref(self.cfg))) and \
             os.environ.get("KNNSSD_GENERIC_KERNELS", "0") != "1"
         self.cfg.weights_packed = 1 if self.packed else 0
+        # sizes of the caller-owned buffers, asked for with the final cfg (they depend on weights_packed)
+        ws_bytes = self.lib.knnssd_workspace_bytes(ctypes.byref(self.cfg))
+        kv_bytes = self.lib.knnssd_kvcache_bytes(ctypes.byref(self.cfg))
+        if ws_bytes == 0 or kv_bytes == 0:
+            raise KnnSsdError(-2, "shape not supported")
 
         def matrix(t: torch.Tensor, which: int) -> torch.Tensor:
             t = t.to(dev).contiguous()
@@ -199,8 +203,8 @@ class KnnSsd:
         self.ws = torch.zeros(ws_bytes, dtype=torch.uint8, device=dev)
         h = ctypes.c_void_p()
         torch.cuda.synchronize(dev)
-        _check(self.lib.knnssd_create(ctypes.byref(self.cfg), ctypes.byref(self.w), self.kv.data_ptr(),
-                                      self.ws.data_ptr(), ctypes.c_void_p(self.stream.cuda_stream), ctypes.byref(h)))
+        _check(self.lib.knnssd_create(ctypes.byref(self.cfg), ctypes.byref(self.w), self.kv.data_ptr(), kv_bytes,
+                                      self.ws.data_ptr(), ws_bytes, ctypes.c_void_p(self.stream.cuda_stream), ctypes.byref(h)))
         self.h = h
         self.weight_bytes = sum(t.numel() * t.element_size() for t in wqkv + wo + wgu + wdown) + \
             self.lm_head.numel() * self.lm_head.element_size()

@@ -13,6 +13,7 @@
 #include "device_types.h"
 #include "kernels_generic.h"
 #include "kernels_bf16.h"
+#include "kernels_prefill.h"
 
 using namespace ks;
 
@@ -43,6 +44,9 @@ struct WsLayout {
     size_t x, xn, qkv, att, u, logits, hidden_last, rope_cos, rope_sin, knn_scores, out_tokens;
     // tuned bf16 path
     size_t act_d, planes_d, qrot, planes_att, planes_u, ss, head_part, attn_part;
+    // tuned prompt prefill (stream-order weights only): all prompt rows at once
+    size_t pf_tokens, pf_x, pf_q, pf_frag_d, pf_frag_att, pf_frag_u, pf_ss, pf_rstd;
+    int pf_tt;          // token tiles the fragment buffers are laid out for
     size_t total;
 };
 
@@ -99,12 +103,25 @@ static WsLayout ws_layout(const knnssd_model_cfg *c) {
         L.ss = take((size_t)KS_NWG * R * 4);
         L.head_part = take(R * (size_t)KS_NWG * sizeof(HeadPartial));
         L.attn_part = take(R * c->n_heads * max_chunks * (c->head_dim + 2) * 4);
+        if (c->weights_packed) {
+            const size_t tt = (((size_t)c->max_seq + 15) / 16 + 15) / 16 * 16, rows = tt * 16;
+            L.pf_tt = (int)tt;
+            L.pf_tokens = take(rows * 4);
+            L.pf_x = take(rows * c->d_model * 4);
+            L.pf_q = take(rows * qd * 4);
+            L.pf_frag_d = take(3 * rows * (size_t)c->d_model * 2);
+            L.pf_frag_att = take(3 * rows * qd * 2);
+            L.pf_frag_u = take(3 * rows * (size_t)c->d_ffn * 2);
+            L.pf_ss = take((size_t)KS_NWG * rows * 4);
+            L.pf_rstd = take(rows * 4);
+        }
     }
     L.total = off;
     return L;
 }
 
 static bool tuned_ok(const knnssd_model_cfg &g);
+static bool prefill_tuned_ok(const knnssd_model_cfg &g);
 
 struct knnssd_ctx {
     knnssd_model_cfg cfg;
@@ -126,6 +143,7 @@ struct knnssd_ctx {
     bool prefilled;
     bool tuned;         // shape fits the tuned bf16 draft kernels
     bool tuned_verify;  // ... and the matrix-core verification kernels (every K a multiple of 32)
+    bool tuned_prefill; // ... and the many-row prefill kernels (a row group fits 16 tile slots)
     int32_t cache_len;
     int32_t last_anchor = -1, last_domain = -1;   // most recent routing
     // pinned host staging for small read-backs
@@ -165,12 +183,14 @@ extern "C" const char *knnssd_strerror(int32_t code) {
     }
 }
 
-extern "C" int32_t knnssd_create(const knnssd_model_cfg *cfg, const knnssd_weights *w, void *kv_dev, void *ws_dev,
-                                 void *hip_stream, knnssd_ctx **out) {
+extern "C" int32_t knnssd_create(const knnssd_model_cfg *cfg, const knnssd_weights *w, void *kv_dev, size_t kv_bytes,
+                                 void *ws_dev, size_t ws_bytes, void *hip_stream, knnssd_ctx **out) {
     if (!out) return KNNSSD_EINVAL;
     *out = nullptr;
     if (!cfg_valid(cfg) || !w || !kv_dev || !ws_dev) return KNNSSD_EINVAL;
     if (!cfg_supported(cfg)) return KNNSSD_ESHAPE;
+    // the kernels index these buffers by the layout of THIS cfg: a buffer sized for another one must not get through
+    if (ws_bytes < ws_layout(cfg).total || kv_bytes < knnssd_kvcache_bytes(cfg)) return KNNSSD_EINVAL;
     if (cfg->weights_packed && !tuned_ok(*cfg)) return KNNSSD_ESHAPE;
     if (((uintptr_t)kv_dev & 255) || ((uintptr_t)ws_dev & 255)) return KNNSSD_EINVAL;
     if (!w->embed || !w->lm_head || !w->final_norm) return KNNSSD_EINVAL;
@@ -204,12 +224,17 @@ extern "C" int32_t knnssd_create(const knnssd_model_cfg *cfg, const knnssd_weigh
     c->prefilled = false; c->cache_len = 0;
     c->tuned = cfg->weights_packed != 0;     // stream-order weights <=> tuned kernels (checked above)
     c->tuned_verify = c->tuned;
+    c->tuned_prefill = c->tuned && prefill_tuned_ok(*cfg) && !getenv("KNNSSD_CHUNKED_PREFILL");
     if (c->tuned) {
         hipError_t ea = hipFuncSetAttribute((const void *)gemv_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, KS_MAX_DYN_LDS);
         if (ea == hipSuccess)
             ea = hipFuncSetAttribute((const void *)gemm_mfma_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, KS_MAX_DYN_LDS);
         if (ea == hipSuccess)
             ea = hipFuncSetAttribute((const void *)gemm_mfma_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, KS_MAX_DYN_LDS);
+        if (ea == hipSuccess)
+            ea = hipFuncSetAttribute((const void *)prefill_gemm_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pf_gemm_lds_bytes(4));
+        if (ea == hipSuccess)
+            ea = hipFuncSetAttribute((const void *)prefill_gemm_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pf_gemm_lds_bytes(2));
         if (ea != hipSuccess) {
             snprintf(g_hip_err, sizeof(g_hip_err), "%s (hipFuncSetAttribute)", hipGetErrorString(ea));
             delete c;
@@ -510,9 +535,94 @@ static int32_t read_back(knnssd_ctx *c, const void *dev, size_t bytes) {
     return KNNSSD_OK;
 }
 
+// Tile slots a row group of each matrix needs in the prefill GEMM (<= 0: the shape does not fit its 16 slots)
+static int pf_slots(const knnssd_model_cfg &g, int type) {
+    auto per = [&](long long n) { return (int)((n + KS_NWG - 1) / KS_NWG); };
+    int rows;
+    if (type == OP_QKV) rows = 2 * per((long long)(g.n_heads + g.n_kv_heads) * g.head_dim / 2) + per((long long)g.n_kv_heads * g.head_dim);
+    else if (type == OP_SWIGLU) rows = 2 * per(g.d_ffn);
+    else rows = per(g.d_model);
+    const int t = (rows + 15) / 16;
+    return t <= PF_SLOTS ? t : 0;
+}
+
+static bool prefill_tuned_ok(const knnssd_model_cfg &g) {
+    return pf_slots(g, OP_QKV) > 0 && pf_slots(g, OP_SWIGLU) > 0 && pf_slots(g, OP_RESID) > 0;
+}
+
+// The full model over the first n_tok prompt rows (a multiple of 16) with the matrix-core prefill kernels: fills the
+// KV cache at positions 0..n_tok-1. The last rows of the prompt go through an ordinary 16-row pass afterwards,
+// which also produces the first token and the routing query.
+static int32_t prefill_tuned(knnssd_ctx *c, const int32_t *tokens_host, int n_tok) {
+    const knnssd_model_cfg &g = c->cfg;
+    const int d = g.d_model, H = g.n_heads, Hkv = g.n_kv_heads, hd = g.head_dim, F = g.d_ffn;
+    const int qd = H * hd, qkvd = (H + 2 * Hkv) * hd, TT = c->L.pf_tt, TTL = n_tok / 16;
+    hipStream_t s = c->stream;
+    int32_t *toks = c->wsp<int32_t>(c->L.pf_tokens);
+    float *x = c->wsp<float>(c->L.pf_x), *q = c->wsp<float>(c->L.pf_q), *ss = c->wsp<float>(c->L.pf_ss);
+    float *rstd = c->wsp<float>(c->L.pf_rstd);
+    bf16_t *frag_d = c->wsp<bf16_t>(c->L.pf_frag_d), *frag_att = c->wsp<bf16_t>(c->L.pf_frag_att);
+    bf16_t *frag_u = c->wsp<bf16_t>(c->L.pf_frag_u);
+    HIP_TRY(hipMemcpyAsync(toks, tokens_host, (size_t)n_tok * 4, hipMemcpyHostToDevice, s));
+    hipLaunchKernelGGL(prefill_embed_kernel, dim3(n_tok), dim3(PF_NT), 0, s, toks, (const bf16_t *)c->embed,
+                       next_gain(c, nullptr, -1), d, g.rms_eps, TT, x, frag_d, rstd);
+
+    GemmOp base{};
+    base.H = H; base.Hkv = Hkv; base.hd = hd; base.max_seq = g.max_seq;
+    base.cos_t = c->wsp<float>(c->L.rope_cos); base.sin_t = c->wsp<float>(c->L.rope_sin);
+    auto gemm = [&](const GemmOp &op, const bf16_t *fin, bf16_t *fout, const float *rs, float *ss_out, int *n_shares) {
+        PfArgs a{};
+        a.op = op; a.frag_in = fin; a.frag_out = fout; a.rstd = rs; a.ss_out = ss_out; a.TT = TT; a.n_tok = n_tok;
+        a.T = pf_slots(g, op.type); a.G = PF_SLOTS / a.T;
+        const int gx = (KS_NWG + a.G - 1) / a.G;
+        // enough workgroups to fill the chip with 16 token tiles each? otherwise 8 per workgroup
+        const bool wide = (long long)gx * ((TTL + 15) / 16) >= 200;
+        if (n_shares) *n_shares = gx;
+        if (wide) hipLaunchKernelGGL(prefill_gemm_kernel<4>, dim3(gx, (TTL + 15) / 16), dim3(PF_NT), pf_gemm_lds_bytes(4), s, a);
+        else hipLaunchKernelGGL(prefill_gemm_kernel<2>, dim3(gx, (TTL + 7) / 8), dim3(PF_NT), pf_gemm_lds_bytes(2), s, a);
+    };
+    auto norm = [&](int n_shares) {
+        hipLaunchKernelGGL(prefill_rstd_kernel, dim3((n_tok + 255) / 256), dim3(256), 0, s, ss, n_shares, TT * 16, n_tok,
+                           1.0f / (float)d, g.rms_eps, rstd);
+    };
+    for (int b = 0; b < g.n_blocks; ++b) {
+        bf16_t *kvb = (bf16_t *)(c->kv + (size_t)b * c->kv_block_bytes);
+        int shares = 0;
+        GemmOp o = base;
+        o.type = OP_QKV; o.W = (const bf16_t *)c->wqkv[b]; o.N = qkvd; o.K = d; o.q_out = q; o.kv_block = kvb;
+        gemm(o, frag_d, nullptr, rstd, nullptr, nullptr);
+        PfAttn at{};
+        at.q = q; at.kv_block = kvb; at.frag_out = frag_att; at.H = H; at.Hkv = Hkv; at.max_seq = g.max_seq; at.TT = TT; at.n_tok = n_tok;
+        if (hd == 128) hipLaunchKernelGGL(prefill_attn_kernel<128>, dim3(TTL * H), dim3(NT), 0, s, at);
+        else hipLaunchKernelGGL(prefill_attn_kernel<64>, dim3(TTL * H), dim3(NT), 0, s, at);
+        GemmOp r = base;
+        r.type = OP_RESID; r.W = (const bf16_t *)c->wo[b]; r.N = d; r.K = qd; r.x = x; r.gain_next = next_gain(c, nullptr, 2 * b);
+        gemm(r, frag_att, frag_d, nullptr, ss, &shares);
+        norm(shares);
+        GemmOp u = base;
+        u.type = OP_SWIGLU; u.W = (const bf16_t *)c->wgu[b]; u.N = F; u.K = d;
+        gemm(u, frag_d, frag_u, rstd, nullptr, nullptr);
+        GemmOp dn = base;
+        dn.type = OP_RESID; dn.W = (const bf16_t *)c->wdown[b]; dn.N = d; dn.K = F; dn.x = x; dn.gain_next = next_gain(c, nullptr, 2 * b + 1);
+        gemm(dn, frag_u, frag_d, nullptr, ss, &shares);
+        norm(shares);
+    }
+    HIP_TRY(hipGetLastError());
+    return KNNSSD_OK;
+}
+
 static int32_t prefill_impl(knnssd_ctx *c, const int32_t *tokens, int32_t n, float *last_hidden_dev, int32_t *first_token) {
     PassCtl *ver = c->wsp<PassCtl>(c->L.ver_ctl);
-    for (int s = 0; s < n; s += KS_MAX_ROWS) {
+    int s0 = 0;
+    if (c->tuned_prefill) {
+        // every complete 16-row tile before the prompt's last rows goes through the matrix-core prefill
+        const int n_main = (n - 1) / KS_MAX_ROWS * KS_MAX_ROWS;
+        if (n_main >= 2 * KS_MAX_ROWS) {
+            KS_TRY(prefill_tuned(c, tokens, n_main));
+            s0 = n_main;
+        }
+    }
+    for (int s = s0; s < n; s += KS_MAX_ROWS) {
         int rows = n - s < KS_MAX_ROWS ? n - s : KS_MAX_ROWS;
         bool last = s + rows >= n;
         KS_TRY(set_pass(c, ver, 1, rows, s, last ? rows - 1 : rows, tokens + s));

@@ -45,8 +45,8 @@ def test_null_arguments_are_rejected_without_a_device(lib):
     h = ctypes.c_void_p()
     cfg = binding.make_cfg(synth.workload("tiny").shape, 8)
     w = binding.Weights()
-    assert lib.knnssd_create(ctypes.byref(cfg), ctypes.byref(w), None, None, None, ctypes.byref(h)) == -1
-    assert lib.knnssd_create(None, None, None, None, None, ctypes.byref(h)) == -1
+    assert lib.knnssd_create(ctypes.byref(cfg), ctypes.byref(w), None, 0, None, 0, None, ctypes.byref(h)) == -1
+    assert lib.knnssd_create(None, None, None, 0, None, 0, None, ctypes.byref(h)) == -1
     assert lib.knnssd_destroy(None) == -1
     assert lib.knnssd_set_skipset(None, None) == -1
     assert lib.knnssd_draft_step(None, 0, 0, None, None) == -1
@@ -54,3 +54,22 @@ def test_null_arguments_are_rejected_without_a_device(lib):
     assert lib.knnssd_generate(None, None, 0, None, None, None, None, None) == -1
     assert lib.knnssd_strerror(-3).decode().startswith("position")
     assert lib.knnssd_strerror(0).decode() == "ok"
+
+
+def test_create_rejects_buffers_smaller_than_the_size_queries(lib):
+    """The kernels index the caller's buffers by the layout of the cfg given to knnssd_create; a buffer sized
+    for a different cfg (e.g. before weights_packed was set) must be refused before anything touches the device."""
+    shape = synth.small_shape("sz", d_ffn=704, max_seq=160)
+    cfg = binding.make_cfg(shape, 0)
+    plain = lib.knnssd_workspace_bytes(ctypes.byref(cfg))
+    assert lib.knnssd_pack_supported(ctypes.byref(cfg)) == 1
+    cfg.weights_packed = 1
+    packed = lib.knnssd_workspace_bytes(ctypes.byref(cfg))
+    kv = lib.knnssd_kvcache_bytes(ctypes.byref(cfg))
+    assert packed > plain > 0          # the stream-order path keeps all prompt rows of a prefill in its workspace
+    h = ctypes.c_void_p()
+    w = binding.Weights()
+    fake = ctypes.c_void_p(0x100000)   # never dereferenced: the size check comes first
+    assert lib.knnssd_create(ctypes.byref(cfg), ctypes.byref(w), fake, kv, fake, plain, None, ctypes.byref(h)) == -1
+    assert lib.knnssd_create(ctypes.byref(cfg), ctypes.byref(w), fake, kv - 1, fake, packed, None, ctypes.byref(h)) == -1
+    assert not h.value
