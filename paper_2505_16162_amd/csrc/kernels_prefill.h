@@ -304,10 +304,12 @@ __global__ void prefill_rstd_kernel(const float *ss, int n_shares, int stride, i
 }
 
 // ------------------------------------------------------------------------------------------
-// Causal attention of the prompt rows over the bf16 cache. Work item = (query head, tile of 16 rows);
-// wavefront w owns row w of the tile. Keys and values go through LDS in chunks of 64 positions shared
-// by the 16 rows; lane = (position of the step, 8-dim slice) as in the decode kernel; running
-// (max, sum, weighted V) per row, rescaled once per chunk.
+// Causal attention of the prompt rows over the bf16 cache, on the matrix cores. A workgroup = one query
+// head x four consecutive 16-row tiles (one wavefront each); keys and values go through LDS in chunks
+// of 64 positions shared by the four wavefronts (values transposed on the way in, so that both are
+// MFMA B operands as stored). Per chunk a wavefront computes S = Q K^T (Q exact as three bf16 planes),
+// the running softmax in fp32 on the vector ALUs, and O += P V with P exact as three bf16 planes;
+// P changes from accumulator layout to operand layout through a wavefront-private LDS tile.
 // ------------------------------------------------------------------------------------------
 struct PfAttn {
     const float *q;          // [n_tok][H*hd] rotated queries
@@ -316,33 +318,66 @@ struct PfAttn {
     int H, Hkv, max_seq, TT, n_tok;
 };
 
+// eight fp32 values -> the three bf16 planes of an MFMA operand fragment (exact: hi + mid + lo = value)
+__device__ __forceinline__ void split_planes8(const float *v, bf16x8 *out3) {
+    unsigned int w[3][4];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const unsigned int u = __float_as_uint(v[e]);
+        const float hi = __uint_as_float(u & 0xffff0000u);
+        const float r1 = v[e] - hi;
+        const unsigned int um = __float_as_uint(r1);
+        const float mid = __uint_as_float(um & 0xffff0000u);
+        const unsigned int ul = __float_as_uint(r1 - mid);
+        const unsigned int h16 = u >> 16, m16 = um >> 16, l16 = ul >> 16;
+        if (e & 1) { w[0][e >> 1] |= h16 << 16; w[1][e >> 1] |= m16 << 16; w[2][e >> 1] |= l16 << 16; }
+        else { w[0][e >> 1] = h16; w[1][e >> 1] = m16; w[2][e >> 1] = l16; }
+    }
+#pragma unroll
+    for (int p = 0; p < 3; ++p) out3[p] = __builtin_bit_cast(bf16x8, u32x4{w[p][0], w[p][1], w[p][2], w[p][3]});
+}
+
 template <int HD>
-__global__ __launch_bounds__(NT) void prefill_attn_kernel(PfAttn a) {
-    constexpr int LPP = HD / 8, PPS = 64 / LPP, CH = 64, STEPS = CH / PPS;
-    constexpr int PIECES = CH * HD / 8;                 // 16-byte pieces of one chunk of K (and of V)
-    constexpr int PQ = (PIECES + NT - 1) / NT;
-    __shared__ __align__(16) bf16_t kc[CH * HD];
-    __shared__ __align__(16) bf16_t vc[CH * HD];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int ps = lane / LPP, dg = lane % LPP;
-    const int n_rt = a.n_tok >> 4;
-    const int rt = n_rt - 1 - (int)(blockIdx.x / a.H);   // long rows first
+__global__ __launch_bounds__(256) void prefill_attn_kernel(PfAttn a) {
+    constexpr int CH = 64, LPP = HD / 8, QS = HD / 32, DT = HD / 16;
+    constexpr int KSTR = HD * 2 + 16;      // bytes per staged key row (+16: the 16 rows of an operand read spread over the banks)
+    constexpr int VSTR = CH * 2 + 16;      // bytes per staged (transposed) value row
+    constexpr int PSTR = CH + 4;           // floats per row of the P tile
+    constexpr int PIECES = CH * LPP, PQ = PIECES / 256;
+    __shared__ __align__(16) char kl[CH * KSTR];
+    __shared__ __align__(16) char vl[HD * VSTR];
+    __shared__ __align__(16) float pb[4][16 * PSTR];
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int kg = lane >> 4, r16 = lane & 15;
+    const int n_rt = a.n_tok >> 4, n_b = (n_rt + 3) >> 2;
+    const int b = n_b - 1 - (int)(blockIdx.x / a.H);          // long blocks first
     const int h = blockIdx.x % a.H, kvh = h / (a.H / a.Hkv);
-    const int tok = rt * 16 + wave;
-    const int qd = a.H * HD;
+    const int rt = min(b * 4 + wave, n_rt - 1);               // a wavefront past the last tile repeats it and stores nothing
+    const bool live = b * 4 + wave < n_rt;
+    const int n_chunks = b + 1;                               // positions 0 .. 64b+63 cover every row of the block
+    const int last_pos = a.n_tok - 1, qd = a.H * HD;
     const float scale = 1.0f / sqrtf((float)HD);
     const bf16_t *kg_ = a.kv_block + (size_t)kvh * a.max_seq * HD;
     const bf16_t *vg_ = a.kv_block + ((size_t)a.Hkv + kvh) * a.max_seq * HD;
-    const float *qp = a.q + (size_t)tok * qd + h * HD + dg * 8;
-    const float4 q0 = *reinterpret_cast<const float4 *>(qp), q1 = *reinterpret_cast<const float4 *>(qp + 4);
-    const int last_pos = rt * 16 + 15;
-    const int n_chunks = last_pos / CH + 1;
+
+    // the wavefront's 16 query rows as operand fragments: lane (kg, i) holds row i, dims 32*ks + 8*kg .. +7
+    bf16x8 qa[QS][3];
+    {
+        const float *qp = a.q + (size_t)(rt * 16 + r16) * qd + h * HD + kg * 8;
+#pragma unroll
+        for (int ks = 0; ks < QS; ++ks) {
+            float v[8];
+            const float4 v0 = *reinterpret_cast<const float4 *>(qp + ks * 32), v1 = *reinterpret_cast<const float4 *>(qp + ks * 32 + 4);
+            v[0] = v0.x; v[1] = v0.y; v[2] = v0.z; v[3] = v0.w; v[4] = v1.x; v[5] = v1.y; v[6] = v1.z; v[7] = v1.w;
+            split_planes8(v, qa[ks]);
+        }
+    }
 
     u32x4 kr[PQ], vr[PQ];
     auto chunk_load = [&](int c) {
 #pragma unroll
         for (int q = 0; q < PQ; ++q) {
-            const int i = min(tid + q * NT, PIECES - 1);
+            const int i = tid + q * 256;
             const int pos = min(c * CH + i / LPP, last_pos);
             kr[q] = *reinterpret_cast<const u32x4 *>(kg_ + (size_t)pos * HD + (i % LPP) * 8);
             vr[q] = *reinterpret_cast<const u32x4 *>(vg_ + (size_t)pos * HD + (i % LPP) * 8);
@@ -351,65 +386,99 @@ __global__ __launch_bounds__(NT) void prefill_attn_kernel(PfAttn a) {
     auto chunk_store = [&]() {
 #pragma unroll
         for (int q = 0; q < PQ; ++q) {
-            const int i = min(tid + q * NT, PIECES - 1);
-            *reinterpret_cast<u32x4 *>(kc + (size_t)i * 8) = kr[q];
-            *reinterpret_cast<u32x4 *>(vc + (size_t)i * 8) = vr[q];
+            const int i = tid + q * 256, pos = i / LPP, d0 = (i % LPP) * 8;
+            *reinterpret_cast<u32x4 *>(kl + pos * KSTR + d0 * 2) = kr[q];
+            const unsigned int w[4] = {vr[q].x, vr[q].y, vr[q].z, vr[q].w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e)        // transpose: value of dim d0+e at position pos
+                *reinterpret_cast<bf16_t *>(vl + (d0 + e) * VSTR + pos * 2) = (bf16_t)((e & 1) ? (w[e >> 1] >> 16) : (w[e >> 1] & 0xffffu));
         }
     };
 
-    float mrun = -INFINITY, l = 0.f, o[8];
+    float mrun[4], lsum[4];
+    f32x4 o[DT];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) o[j] = 0.f;
+    for (int q = 0; q < 4; ++q) { mrun[q] = -INFINITY; lsum[q] = 0.f; }
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float *pw = pb[wave];
+    const int row_tok = rt * 16 + 4 * kg;                     // position of accumulator row q of this lane: row_tok + q
+
     chunk_load(0);
     for (int c = 0; c < n_chunks; ++c) {
-        __syncthreads();                                  // the previous chunk has been consumed
+        __syncthreads();                                      // the previous chunk has been consumed by every wavefront
         chunk_store();
         __syncthreads();
         chunk_load(min(c + 1, n_chunks - 1));
-        if (c * CH > tok) continue;                       // nothing of this chunk is visible to this row (uniform per wavefront)
-        float sc[STEPS];
-        float cm = -INFINITY;
+        // S = Q K^T for the chunk's four position tiles: lane (kg, j) holds rows 4*kg..4*kg+3 at position 16*pt + j
+        float sc[4][4];
 #pragma unroll
-        for (int s = 0; s < STEPS; ++s) {
-            const u32x4 kf = *reinterpret_cast<const u32x4 *>(kc + (size_t)(s * PPS + ps) * HD + dg * 8);
-            float d = dot8(kf, q0, q1, 0.f);
+        for (int pt = 0; pt < 4; ++pt) {
+            f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int off = 1; off < LPP; off <<= 1) d += __shfl_xor(d, off, 64);
-            const int pos = c * CH + s * PPS + ps;
-            sc[s] = (pos <= tok) ? d * scale : -INFINITY;
-            cm = fmaxf(cm, sc[s]);
+            for (int ks = 0; ks < QS; ++ks) {
+                const bf16x8 kb = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(kl + (pt * 16 + r16) * KSTR + (ks * 32 + kg * 8) * 2));
+#pragma unroll
+                for (int p = 0; p < 3; ++p) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[ks][p], kb, acc, 0, 0, 0);
+            }
+            const int pos = c * CH + pt * 16 + r16;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) sc[pt][q] = (pos <= row_tok + q) ? acc[q] * scale : -INFINITY;
+        }
+        // running softmax per row (rows are replicated over the 16 lanes of a kg group)
+        float f[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            float cm = fmaxf(fmaxf(sc[0][q], sc[1][q]), fmaxf(sc[2][q], sc[3][q]));
+#pragma unroll
+            for (int off = 1; off < 16; off <<= 1) cm = fmaxf(cm, __shfl_xor(cm, off, 64));
+            const float mnew = fmaxf(mrun[q], cm);            // finite: position 0 is visible to every row
+            f[q] = (mrun[q] > -INFINITY) ? expf(mrun[q] - mnew) : 0.f;
+            mrun[q] = mnew;
+            float ps = 0.f;
+#pragma unroll
+            for (int pt = 0; pt < 4; ++pt) {
+                const float e = (sc[pt][q] > -INFINITY) ? expf(sc[pt][q] - mnew) : 0.f;
+                pw[(4 * kg + q) * PSTR + pt * 16 + r16] = e;
+                ps += e;
+            }
+            lsum[q] = lsum[q] * f[q] + ps;
         }
 #pragma unroll
-        for (int off = LPP; off < 64; off <<= 1) cm = fmaxf(cm, __shfl_xor(cm, off, 64));
-        const float mnew = fmaxf(mrun, cm);               // finite: position c*CH <= tok is visible
-        const float f = (mrun > -INFINITY) ? expf(mrun - mnew) : 0.f;
-        l *= f;
+        for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-        for (int j = 0; j < 8; ++j) o[j] *= f;
-        mrun = mnew;
+            for (int q = 0; q < 4; ++q) o[dt][q] *= f[q];
+        // O += P V: P back from LDS in operand layout (lane (kg, i): row i, positions 32*ks2 + 8*kg .. +7)
 #pragma unroll
-        for (int s = 0; s < STEPS; ++s) {
-            const float e = (sc[s] > -INFINITY) ? expf(sc[s] - mnew) : 0.f;
-            const u32x4 vf = *reinterpret_cast<const u32x4 *>(vc + (size_t)(s * PPS + ps) * HD + dg * 8);
-            l += e;
-            o[0] = fmaf(e, bf_lo(vf.x), o[0]); o[1] = fmaf(e, bf_hi(vf.x), o[1]);
-            o[2] = fmaf(e, bf_lo(vf.y), o[2]); o[3] = fmaf(e, bf_hi(vf.y), o[3]);
-            o[4] = fmaf(e, bf_lo(vf.z), o[4]); o[5] = fmaf(e, bf_hi(vf.z), o[5]);
-            o[6] = fmaf(e, bf_lo(vf.w), o[6]); o[7] = fmaf(e, bf_hi(vf.w), o[7]);
+        for (int ks2 = 0; ks2 < 2; ++ks2) {
+            float pv[8];
+            const float4 p0 = *reinterpret_cast<const float4 *>(pw + r16 * PSTR + ks2 * 32 + kg * 8);
+            const float4 p1 = *reinterpret_cast<const float4 *>(pw + r16 * PSTR + ks2 * 32 + kg * 8 + 4);
+            pv[0] = p0.x; pv[1] = p0.y; pv[2] = p0.z; pv[3] = p0.w; pv[4] = p1.x; pv[5] = p1.y; pv[6] = p1.z; pv[7] = p1.w;
+            bf16x8 pa[3];
+            split_planes8(pv, pa);
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) {
+                const bf16x8 vb = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(vl + (dt * 16 + r16) * VSTR + (ks2 * 32 + kg * 8) * 2));
+#pragma unroll
+                for (int p = 0; p < 3; ++p) o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa[p], vb, o[dt], 0, 0, 0);
+            }
         }
     }
-    // sum over the position groups of the wavefront (every lane of a group carries the same l)
+    // row sums over the 16 lanes of a kg group, then the rows' outputs in fragment order
 #pragma unroll
-    for (int off = LPP; off < 64; off <<= 1) {
-        l += __shfl_xor(l, off, 64);
+    for (int q = 0; q < 4; ++q) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) o[j] += __shfl_xor(o[j], off, 64);
+        for (int off = 1; off < 16; off <<= 1) lsum[q] += __shfl_xor(lsum[q], off, 64);
     }
-    if (ps == 0) {
-        const int tt = tok >> 4, m = tok & 15;
-        const float inv = 1.0f / l;
+    if (live) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) store_frag(a.frag_out, qd >> 5, a.TT, tt, m, h * HD + dg * 8 + j, o[j] * inv);
+        for (int q = 0; q < 4; ++q) {
+            const float inv = 1.0f / lsum[q];
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+                store_frag(a.frag_out, qd >> 5, a.TT, rt, 4 * kg + q, h * HD + dt * 16 + r16, o[dt][q] * inv);
+        }
     }
 }
 

@@ -593,8 +593,8 @@ static int32_t prefill_tuned(knnssd_ctx *c, const int32_t *tokens_host, int n_to
         gemm(o, frag_d, nullptr, rstd, nullptr, nullptr);
         PfAttn at{};
         at.q = q; at.kv_block = kvb; at.frag_out = frag_att; at.H = H; at.Hkv = Hkv; at.max_seq = g.max_seq; at.TT = TT; at.n_tok = n_tok;
-        if (hd == 128) hipLaunchKernelGGL(prefill_attn_kernel<128>, dim3(TTL * H), dim3(NT), 0, s, at);
-        else hipLaunchKernelGGL(prefill_attn_kernel<64>, dim3(TTL * H), dim3(NT), 0, s, at);
+        if (hd == 128) hipLaunchKernelGGL(prefill_attn_kernel<128>, dim3(((TTL + 3) / 4) * H), dim3(256), 0, s, at);
+        else hipLaunchKernelGGL(prefill_attn_kernel<64>, dim3(((TTL + 3) / 4) * H), dim3(256), 0, s, at);
         GemmOp r = base;
         r.type = OP_RESID; r.W = (const bf16_t *)c->wo[b]; r.N = d; r.K = qd; r.x = x; r.gain_next = next_gain(c, nullptr, 2 * b);
         gemm(r, frag_att, frag_d, nullptr, ss, &shares);
