@@ -75,6 +75,24 @@ __device__ __forceinline__ float dot8(u32x4 w, float4 x0, float4 x1, float acc) 
     return acc;
 }
 
+// Hand-placed streaming loads: the compiler's own wait insertion drains the whole queue wherever a load sits under
+// a loop-carried or conditional path, which leaves gaps in a wavefront's request stream. These two helpers issue a
+// nontemporal 16-byte load the compiler does not count, and wait until at most KEEP younger loads are still in
+// flight before the register may be used (loads return in order).
+__device__ __forceinline__ u32x4 stream_load(const bf16_t *p) {
+    u32x4 v;
+    asm volatile("global_load_dwordx4 %0, %1, off nt" : "=v"(v) : "v"(p) : "memory");
+    return v;
+}
+template <int KEEP>
+__device__ __forceinline__ void stream_wait(u32x4 &r) {
+    asm volatile("s_waitcnt vmcnt(%1)" : "+v"(r) : "n"(KEEP) : "memory");
+}
+// drain: every register of the batch is named, so that no use of any of them can be moved above the wait
+__device__ __forceinline__ void stream_drain8(u32x4 *r) {
+    asm volatile("s_waitcnt vmcnt(0)" : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]), "+v"(r[4]), "+v"(r[5]), "+v"(r[6]), "+v"(r[7]) : : "memory");
+}
+
 // Rows of W a workgroup owns, as a table of global row indices in LDS. Returns the count.
 // OP_QKV orders them [first halves of np rotary pairs][their second halves][nv value rows],
 // OP_SWIGLU [nf gate rows][the matching nf up rows].
@@ -436,7 +454,34 @@ __device__ __forceinline__ void gemv_device(const GemmOp &op, const PassCtl *ctl
             load_batch(wp, 0, w.cnt, w.unit);
         }
         float acc = 0.f;
-        for (int u0 = 0; u0 < w.cnt; u0 += 8) {
+        int u0 = 0;
+        // the tile's first eight units were loaded with ordinary (compiler-counted) loads: they are used in a block of
+        // their own, so that the compiler's waits stay out of the steady loop below
+        if (w.cnt >= 16) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const float *xp = xs + step_of_unit(s, kpart, i) * 32 + kg * 8;
+                const float4 x0 = *reinterpret_cast<const float4 *>(xp), x1 = *reinterpret_cast<const float4 *>(xp + 4);
+                acc = dot8(wa[i], x0, x1, acc);
+                wa[i] = stream_load(wp + (size_t)(i + 8) * w.unit);
+            }
+            u0 = 8;
+        }
+        // steady state: every unit has a successor eight units on; its register is refilled the moment it has been
+        // used and the wait before a unit leaves the seven younger loads in flight, so the stream never drains
+        for (; u0 + 16 <= w.cnt; u0 += 8) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const float *xp = xs + step_of_unit(s, kpart, u0 + i) * 32 + kg * 8;
+                const float4 x0 = *reinterpret_cast<const float4 *>(xp), x1 = *reinterpret_cast<const float4 *>(xp + 4);
+                stream_wait<7>(wa[i]);
+                acc = dot8(wa[i], x0, x1, acc);
+                wa[i] = stream_load(wp + (size_t)(u0 + i + 8) * w.unit);
+            }
+        }
+        // tail: at most 15 units left, drained batch by batch
+        for (; u0 < w.cnt; u0 += 8) {
+            stream_drain8(wa);
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 if (u0 + i < w.cnt) {
@@ -445,7 +490,9 @@ __device__ __forceinline__ void gemv_device(const GemmOp &op, const PassCtl *ctl
                     acc = dot8(wa[i], x0, x1, acc);
                 }
             }
-            load_batch(wp, u0 + 8, w.cnt, w.unit);
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                if (u0 + 8 + i < w.cnt) wa[i] = stream_load(wp + (size_t)(u0 + 8 + i) * w.unit);
         }
         acc += __shfl_xor(acc, 16, 64);
         acc += __shfl_xor(acc, 32, 64);
