@@ -115,6 +115,9 @@ def main():
                          "cost coefficient of a sublayer-granular mask with skip ratios --s-attn / --s-mlp")
     ap.add_argument("--s-attn", type=float, default=0.48)
     ap.add_argument("--s-mlp", type=float, default=0.42)
+    ap.add_argument("--knn-probe", type=int, default=0, metavar="N",
+                    help="time the K-nearest-anchor scan (knnssd_knn_topk, K = 8) over N anchors of dimension 5120, for 1 and 4 "
+                         "queries per pass, and print its HBM rate instead of the benchmark line")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="run under `rocprofv3 --pmc FETCH_SIZE` (or WRITE_SIZE): one plain 1 GiB copy for calibration, "
                          "then verification passes with only the weight-streaming launches; prints nothing else")
@@ -137,6 +140,9 @@ def main():
         build_library()
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
+    if args.knn_probe:
+        print(json.dumps(knn_probe(args.knn_probe, dev)))
+        return
     wl = synth.workload(args.workload)
     shape = wl.shape
     max_new = args.max_new or wl.max_new
@@ -298,6 +304,33 @@ def stream_mode(args, gpu, wl, shape, centres, prompt_len, max_new, dev):
             "reselect": not args.no_reselect, "prompt_len": prompt_len, "max_new": max_new,
             "domains": domains, "routed": res.routed, "total": fig(res.total),
             "per_domain": {str(d): fig(t) for d, t in sorted(res.per_domain.items())}}
+
+
+def knn_probe(n_anchors, dev):
+    """The anchor scan at a size where it is bound by HBM bandwidth rather than by launch latency."""
+    import torch
+    from paper_2505_16162_amd import binding, synth
+    d, n_dom, k = 5120, 5, 8
+    shape = synth.small_shape("knn_probe", n_blocks=1, d_model=d, n_heads=40, n_kv_heads=40, head_dim=128, d_ffn=64, vocab=64,
+                              max_seq=32)
+    gpu = binding.KnnSsd(shape, synth.make_weights(shape, device=dev), max_anchors=n_anchors)
+    anchors, labels, centres = synth.make_anchors(d, n_anchors, n_dom, 0.1, device=dev)
+    gpu.knnssd_set_anchors(anchors, labels, synth.make_block_masks(1, n_dom, 1))
+    out = {"mode": "knn-probe", "anchors": n_anchors, "dim": d, "k": k, "table_GB": round(n_anchors * d * 4 / 1e9, 3)}
+    for nq in (1, 4):
+        queries = torch.stack([synth.make_domain_query(centres, i % n_dom, 0.1, seed=i) for i in range(nq)])
+        idx, _, dom = gpu.knnssd_knn_topk(queries, k)
+        assert dom == [i % n_dom for i in range(nq)]
+        torch.cuda.synchronize()
+        reps = 5
+        t0 = time.time()
+        for _ in range(reps):
+            gpu.knnssd_knn_topk(queries, k)
+        dt = (time.time() - t0) / reps
+        out[f"q{nq}"] = {"ms": round(dt * 1e3, 3), "scan_GBps": round(n_anchors * d * 4 / dt / 1e9, 1),
+                         "frac_of_peak": round(n_anchors * d * 4 / dt / 1e9 / HBM_PEAK_GBS, 4)}
+    gpu.close()
+    return out
 
 
 def beta_probe(args, gpu, shape, prompt, prompt_len):

@@ -150,6 +150,17 @@ int32_t knnssd_select_skipset(knnssd_ctx *ctx, const float *query_dev, int32_t *
 /* Install a draft mask directly (2*n_blocks bytes on the host; NULL = skip nothing). */
 int32_t knnssd_set_skipset(knnssd_ctx *ctx, const uint8_t *mask_host);
 
+/* K nearest anchors (cosine similarity: Eq. 4 generalised from the arg-max to the K best, lowest index first among
+ * equal scores) of each of n_queries query vectors against the installed anchor table, and the majority domain
+ * among the K (a tie between domains goes to the tied domain whose best anchor ranks first; K = 1 is Eq. 4-5).
+ * Batched: up to 4 queries share one pass over the table. queries_dev: fp32 [n_queries][d_model], 16-byte aligned
+ * (device). anchor_idx_out: int32 [n_queries][k] (host). cosine_out: fp32 [n_queries][k] (host, may be NULL).
+ * domain_out: int32 [n_queries] (host). 1 <= k <= 16 and k <= number of anchors. Installs no mask.
+ * KNNSSD_EDEGENERATE for a zero-norm or non-finite query or anchor, KNNSSD_ESTATE without an anchor table. */
+#define KNNSSD_KNN_KMAX 16
+int32_t knnssd_knn_topk(knnssd_ctx *ctx, const float *queries_dev, int32_t n_queries, int32_t k,
+                        int32_t *anchor_idx_out, float *cosine_out, int32_t *domain_out);
+
 /* Anchor index n* and domain (Eq. 4-5) of the most recent routing on this context, whether it was made by
  * knnssd_select_skipset or inside knnssd_generate; both are -1 before the first routing. Either output
  * pointer may be NULL. Host-only, no device work. */

@@ -196,6 +196,22 @@ def knn_select(query, anchors, labels, masks):
 # decoding loops
 # ----------------------------------------------------------------------------------------------
 
+def knn_topk_vote(query, anchors, labels, k: int):
+    """The K nearest anchors by cosine similarity (Eq. 4 generalised from the arg-max to the K best; equal
+    scores in index order) and the majority domain among them; a tie between domains goes to the tied domain
+    whose best anchor ranks first. Exhaustive: every score is computed and the whole table is sorted."""
+    scores = cosine_scores(np.asarray(query, dtype=np.float64), np.asarray(anchors, dtype=np.float64))
+    s32 = scores.astype(np.float32)              # ties are decided on fp32-rounded scores, as in knn_select
+    order = sorted(range(len(scores)), key=lambda n: (-s32[n], n))[:k]
+    counts = {}
+    for rank, n in enumerate(order):
+        lab = int(labels[n])
+        c, first = counts.get(lab, (0, rank))
+        counts[lab] = (c + 1, first)
+    domain = min(counts, key=lambda lab: (-counts[lab][0], counts[lab][1]))
+    return order, [float(scores[n]) for n in order], domain
+
+
 @dataclasses.dataclass
 class GenStats:
     rounds: int = 0          # verification passes

@@ -23,7 +23,7 @@ _DT = {"fp32": 0, "bf16": 1}
 EXPORTS = [
     "knnssd_workspace_bytes", "knnssd_kvcache_bytes", "knnssd_create", "knnssd_destroy",
     "knnssd_pack_supported", "knnssd_pack_matrix",
-    "knnssd_set_anchors", "knnssd_prefill", "knnssd_select_skipset", "knnssd_set_skipset", "knnssd_last_selection",
+    "knnssd_set_anchors", "knnssd_prefill", "knnssd_select_skipset", "knnssd_set_skipset", "knnssd_last_selection", "knnssd_knn_topk",
     "knnssd_draft_step", "knnssd_verify", "knnssd_generate", "knnssd_profile_pass", "knnssd_get_logits", "knnssd_read_kv",
     "knnssd_strerror",
 ]
@@ -98,6 +98,8 @@ def load_library() -> ctypes.CDLL:
     lib.knnssd_select_skipset.argtypes = [vp, vp, ctypes.POINTER(i32), ctypes.POINTER(i32), vp]
     lib.knnssd_set_skipset.restype = i32
     lib.knnssd_set_skipset.argtypes = [vp, vp]
+    lib.knnssd_knn_topk.restype = i32
+    lib.knnssd_knn_topk.argtypes = [vp, vp, i32, i32, vp, vp, vp]
     lib.knnssd_last_selection.restype = i32
     lib.knnssd_last_selection.argtypes = [vp, ctypes.POINTER(i32), ctypes.POINTER(i32)]
     lib.knnssd_draft_step.restype = i32
@@ -264,6 +266,18 @@ class KnnSsd:
         _check(self.lib.knnssd_verify(self.h, toks, len(tokens), int(start_pos), ctypes.byref(j), ctypes.byref(nxt),
                                       ctypes.byref(new_len)))
         return int(j.value), int(nxt.value), int(new_len.value)
+
+    def knnssd_knn_topk(self, queries: torch.Tensor, k: int):
+        """K nearest anchors and the majority domain for each row of `queries` ([n][d_model])."""
+        q = queries.to(self.device, torch.float32).contiguous()
+        if q.dim() == 1:
+            q = q[None, :]
+        n = q.shape[0]
+        idx = (ctypes.c_int32 * (n * k))()
+        cos = (ctypes.c_float * (n * k))()
+        dom = (ctypes.c_int32 * n)()
+        _check(self.lib.knnssd_knn_topk(self.h, q.data_ptr(), n, int(k), idx, cos, dom))
+        return ([list(idx[i * k:(i + 1) * k]) for i in range(n)], [list(cos[i * k:(i + 1) * k]) for i in range(n)], list(dom))
 
     def knnssd_last_selection(self):
         idx, dom = ctypes.c_int32(), ctypes.c_int32()

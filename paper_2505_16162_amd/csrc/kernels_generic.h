@@ -324,28 +324,9 @@ __global__ __launch_bounds__(1024) void argmax_kernel(const PassCtl *ctl, const 
 // ------------------------------------------------------------------------------------------
 // KNN routing, Eq. 4: score_n = (v . a_n) / |a_n|  (|v| is a common positive factor), then arg-max
 // ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void knn_scores_kernel(const float *__restrict__ query, const float *__restrict__ anchors,
-                                                         int N, int D, float *scores) {
-    const int lane = threadIdx.x & 63;
-    const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
-    const int n_waves = (gridDim.x * blockDim.x) >> 6;
-    for (int n = wave; n < N; n += n_waves) {
-        const float *a = anchors + (size_t)n * D;
-        float dot = 0.f, nn = 0.f;
-        for (int k = lane * 4; k < D; k += 256) {
-            float4 av = *reinterpret_cast<const float4 *>(a + k);
-            float4 qv = *reinterpret_cast<const float4 *>(query + k);
-            dot = fmaf(av.x, qv.x, dot); dot = fmaf(av.y, qv.y, dot);
-            dot = fmaf(av.z, qv.z, dot); dot = fmaf(av.w, qv.w, dot);
-            nn = fmaf(av.x, av.x, nn); nn = fmaf(av.y, av.y, nn);
-            nn = fmaf(av.z, av.z, nn); nn = fmaf(av.w, av.w, nn);
-        }
-        dot = wave_sum(dot);
-        nn = wave_sum(nn);
-        // a zero or non-finite anchor norm leaves a NaN score, which the arg-max kernel reports
-        if (lane == 0) scores[n] = (nn > 0.f && isfinite(nn)) ? dot / sqrtf(nn) : NAN;
-    }
-}
+template <int Q>
+__global__ __launch_bounds__(256) void knn_scores_multi_kernel(const float *__restrict__ queries, const float *__restrict__ anchors,
+                                                               int N, int D, float *scores);
 
 __global__ __launch_bounds__(1024) void knn_argmax_kernel(const float *scores, const float *query, const int32_t *labels,
                                                           int N, int D, KnnResult *res) {
@@ -382,6 +363,172 @@ __global__ __launch_bounds__(1024) void knn_argmax_kernel(const float *scores, c
         res->idx = degenerate ? -1 : bi;
         res->label = degenerate ? -1 : labels[bi];
         res->score = bv;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// K nearest anchors for a few queries at once (Eq. 4 generalised from the arg-max to the K best), then the
+// majority domain among them. One pass over the anchor table serves up to KNN_QMAX queries: a wavefront
+// streams one anchor (16-byte nontemporal loads, all of a block in flight before the first is used) and
+// forms its dot product with every query (the queries are small and stay in cache) and its own norm.
+// ------------------------------------------------------------------------------------------
+#define KNN_QMAX 4
+#define KNN_KMAX 16
+
+__global__ void fill_zero_kernel(int *p, int n) {
+    for (int i = threadIdx.x; i < n; i += blockDim.x) p[i] = 0;
+}
+
+struct KnnTopk {
+    int32_t idx[KNN_KMAX];
+    float cosine[KNN_KMAX];
+    int32_t domain;       // majority label among the K; ties go to the tied label whose best anchor ranks first
+    int32_t degenerate;   // 1: zero-norm / non-finite query or anchor met
+};
+
+template <int Q>
+__global__ __launch_bounds__(256) void knn_scores_multi_kernel(const float *__restrict__ queries, const float *__restrict__ anchors,
+                                                               int N, int D, float *scores /*[Q][N]*/) {
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    const int lane = threadIdx.x & 63;
+    const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int n_waves = (gridDim.x * blockDim.x) >> 6;
+    for (int n = wave; n < N; n += n_waves) {
+        const float *a = anchors + (size_t)n * D;
+        float dot[Q], nn = 0.f;
+#pragma unroll
+        for (int q = 0; q < Q; ++q) dot[q] = 0.f;
+        for (int k0 = 0; k0 < D; k0 += 1024) {           // blocks of four 16-byte loads per lane, issued together
+            f4 av[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int k = min(k0 + j * 256 + lane * 4, D - 4);           // clamped, masked below
+                av[j] = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(a + k));
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int k = k0 + j * 256 + lane * 4;
+                if (k < D) {
+                    nn = fmaf(av[j].x, av[j].x, nn); nn = fmaf(av[j].y, av[j].y, nn);
+                    nn = fmaf(av[j].z, av[j].z, nn); nn = fmaf(av[j].w, av[j].w, nn);
+#pragma unroll
+                    for (int q = 0; q < Q; ++q) {
+                        const float4 qv = *reinterpret_cast<const float4 *>(queries + (size_t)q * D + k);
+                        dot[q] = fmaf(av[j].x, qv.x, dot[q]); dot[q] = fmaf(av[j].y, qv.y, dot[q]);
+                        dot[q] = fmaf(av[j].z, qv.z, dot[q]); dot[q] = fmaf(av[j].w, qv.w, dot[q]);
+                    }
+                }
+            }
+        }
+        nn = wave_sum(nn);
+        const bool ok = nn > 0.f && isfinite(nn);
+        const float inv = ok ? 1.0f / sqrtf(nn) : 0.f;
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+            const float d = wave_sum(dot[q]);
+            if (lane == 0) scores[(size_t)q * N + n] = ok ? d * inv : NAN;
+        }
+    }
+}
+
+// K rounds of arg-max (lowest anchor index on ties) over values not yet taken. Entry i has value val[i] and anchor
+// index (map ? map[i] : first + i). Runs on one workgroup of 1024 threads; the winners land in taken_idx / taken_val.
+__device__ __forceinline__ int knn_rounds(const float *val, const int32_t *map, int first, int n, int K, int *taken_pos,
+                                          int *taken_idx, float *taken_val, float *sv, int *si, int *sp) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int anybad = 0;
+    for (int r = 0; r < K; ++r) {
+        float bv = -INFINITY; int bi = 0x7fffffff, bp = -1;
+        for (int i = threadIdx.x; i < n; i += 1024) {
+            const float v = val[i];
+            if (!isfinite(v)) { anybad = 1; continue; }
+            bool free_ = true;
+            for (int t = 0; t < r; ++t) free_ = free_ && (taken_pos[t] != i);
+            const int gi = map ? map[i] : first + i;
+            if (free_ && gi >= 0 && better(v, gi, bv, bi)) { bv = v; bi = gi; bp = i; }
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            const float ov = __shfl_xor(bv, off, 64); const int oi = __shfl_xor(bi, off, 64), op = __shfl_xor(bp, off, 64);
+            if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; bp = op; }
+        }
+        if (lane == 0) { sv[wave] = bv; si[wave] = bi; sp[wave] = bp; }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            bv = sv[0]; bi = si[0]; bp = sp[0];
+            for (int w = 1; w < 16; ++w) if (better(sv[w], si[w], bv, bi)) { bv = sv[w]; bi = si[w]; bp = sp[w]; }
+            taken_pos[r] = bp; taken_idx[r] = bi; taken_val[r] = bv;
+        }
+        __syncthreads();
+    }
+    return anybad;
+}
+
+// Stage 1 of the top-K: workgroup (query q, slice b) leaves the K best of its slice of the scores as candidates.
+__global__ __launch_bounds__(1024) void knn_topk_part_kernel(const float *scores /*[Q][N]*/, int N, int K, int n_slices,
+                                                             int32_t *cand_idx /*[Q][n_slices][KNN_KMAX]*/, float *cand_val,
+                                                             int *bad_flag /*[Q]*/) {
+    __shared__ float sv[16];
+    __shared__ int si[16], sp[16], tpos[KNN_KMAX], tidx[KNN_KMAX];
+    __shared__ float tval[KNN_KMAX];
+    const int q = blockIdx.x, b = blockIdx.y;
+    const int i0 = (int)((long long)N * b / n_slices), i1 = (int)((long long)N * (b + 1) / n_slices);
+    const int kk = min(K, i1 - i0);
+    const int anybad = knn_rounds(scores + (size_t)q * N + i0, nullptr, i0, i1 - i0, kk, tpos, tidx, tval, sv, si, sp);
+    if (anybad) atomicOr(&bad_flag[q], 1);
+    if (threadIdx.x < KNN_KMAX) {
+        const size_t o = ((size_t)q * n_slices + b) * KNN_KMAX + threadIdx.x;
+        const bool live = (int)threadIdx.x < kk && tidx[threadIdx.x] != 0x7fffffff;
+        cand_idx[o] = live ? tidx[threadIdx.x] : -1;
+        cand_val[o] = live ? tval[threadIdx.x] : -INFINITY;
+    }
+}
+
+// Stage 2: one workgroup per query merges the slices' candidates (K rounds again), then the vote.
+__global__ __launch_bounds__(1024) void knn_topk_kernel(const int32_t *cand_idx, const float *cand_val, int n_slices, const int *bad_flag,
+                                                        const float *queries, const int32_t *labels, int D, int K, KnnTopk *res) {
+    __shared__ float sv[16];
+    __shared__ int si[16], sp[16], tpos[KNN_KMAX];
+    __shared__ int taken[KNN_KMAX];
+    __shared__ float tval[KNN_KMAX];
+    __shared__ float qn[16];
+    const int q = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const float *qv = queries + (size_t)q * D;
+    float q2 = 0.f;
+    for (int i = threadIdx.x; i < D; i += 1024) { const float v = qv[i]; q2 = fmaf(v, v, q2); }
+    q2 = wave_sum(q2);
+    if (lane == 0) qn[wave] = q2;
+    __syncthreads();
+    const size_t o = (size_t)q * n_slices * KNN_KMAX;
+    knn_rounds(cand_val + o, cand_idx + o, 0, n_slices * KNN_KMAX, K, tpos, taken, tval, sv, si, sp);
+    const int bad = bad_flag[q];
+    if (threadIdx.x == 0) {
+        float qtot = 0.f;
+        for (int w = 0; w < 16; ++w) qtot += qn[w];
+        KnnTopk out;
+        const bool degenerate = bad || !(qtot > 0.f) || !isfinite(qtot) || taken[0] == 0x7fffffff;
+        const float invq = degenerate ? 0.f : 1.0f / sqrtf(qtot);
+        int best_label = -1, best_count = 0;
+        for (int r = 0; r < KNN_KMAX; ++r) {
+            const bool live = r < K && !degenerate && taken[r] != 0x7fffffff;
+            out.idx[r] = live ? taken[r] : -1;
+            out.cosine[r] = live ? tval[r] * invq : 0.f;
+        }
+        // ranked order: the first label to reach the highest count wins a tie only if its best anchor ranks first,
+        // i.e. count every label, then take the best-ranked label among those with the highest count
+        for (int r = 0; r < K && !degenerate; ++r) {
+            if (out.idx[r] < 0) break;
+            const int lab = labels[out.idx[r]];
+            bool seen = false;
+            for (int t = 0; t < r; ++t) seen = seen || (labels[out.idx[t]] == lab);
+            if (seen) continue;                       // counted when first met
+            int cnt = 0;
+            for (int t = r; t < K; ++t) if (out.idx[t] >= 0 && labels[out.idx[t]] == lab) ++cnt;
+            if (cnt > best_count) { best_count = cnt; best_label = lab; }
+        }
+        out.domain = degenerate ? -1 : best_label;
+        out.degenerate = degenerate ? 1 : 0;
+        res[q] = out;
     }
 }
 

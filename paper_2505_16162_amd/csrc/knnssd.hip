@@ -41,7 +41,7 @@ static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 // Workspace layout (byte offsets, all 256-byte aligned).
 struct WsLayout {
     size_t draft_ctl, ver_ctl, gen, head, knn, out3;
-    size_t x, xn, qkv, att, u, logits, hidden_last, rope_cos, rope_sin, knn_scores, out_tokens;
+    size_t x, xn, qkv, att, u, logits, hidden_last, rope_cos, rope_sin, knn_scores, knn_topk, knn_cand_idx, knn_cand_val, knn_bad, out_tokens;
     // tuned bf16 path
     size_t act_d, planes_d, qrot, planes_att, planes_u, ss, head_part, attn_part;
     // tuned prompt prefill (stream-order weights only): all prompt rows at once
@@ -90,7 +90,11 @@ static WsLayout ws_layout(const knnssd_model_cfg *c) {
     L.hidden_last = take((size_t)c->d_model * 4);
     L.rope_cos = take((size_t)c->max_seq * (c->head_dim / 2) * 4);
     L.rope_sin = take((size_t)c->max_seq * (c->head_dim / 2) * 4);
-    L.knn_scores = take((size_t)(c->max_anchors > 0 ? c->max_anchors : 1) * 4);
+    L.knn_scores = take((size_t)(c->max_anchors > 0 ? c->max_anchors : 1) * 4 * KNN_QMAX);
+    L.knn_topk = take(sizeof(KnnTopk) * KNN_QMAX);
+    L.knn_cand_idx = take((size_t)KNN_QMAX * 64 * KNN_KMAX * 4);
+    L.knn_cand_val = take((size_t)KNN_QMAX * 64 * KNN_KMAX * 4);
+    L.knn_bad = take(KNN_QMAX * 4);
     L.out_tokens = take((size_t)c->max_seq * 4);
     {
         const size_t qd = (size_t)c->n_heads * c->head_dim;
@@ -669,10 +673,10 @@ extern "C" int32_t knnssd_prefill(knnssd_ctx *ctx, const int32_t *tokens_host, i
 static int32_t select_impl(knnssd_ctx *c, const float *query_dev, int32_t *idx_out, int32_t *dom_out) {
     const int N = c->n_anchors, D = c->cfg.d_model;
     int wgs = (N + 3) / 4;
-    if (wgs > 1024) wgs = 1024;
+    if (wgs > 4096) wgs = 4096;
     float *scores = c->wsp<float>(c->L.knn_scores);
     KnnResult *res = c->wsp<KnnResult>(c->L.knn);
-    hipLaunchKernelGGL(knn_scores_kernel, dim3(wgs), dim3(256), 0, c->stream, query_dev, c->anchors, N, D, scores);
+    hipLaunchKernelGGL(knn_scores_multi_kernel<1>, dim3(wgs), dim3(256), 0, c->stream, query_dev, c->anchors, N, D, scores);
     hipLaunchKernelGGL(knn_argmax_kernel, dim3(1), dim3(1024), 0, c->stream, scores, query_dev, c->labels, N, D, res);
     HIP_TRY(hipGetLastError());
     KS_TRY(read_back(c, res, sizeof(KnnResult)));
@@ -685,6 +689,49 @@ static int32_t select_impl(knnssd_ctx *c, const float *query_dev, int32_t *idx_o
     *idx_out = r.idx;
     *dom_out = r.label;
     c->last_anchor = r.idx; c->last_domain = r.label;
+    return KNNSSD_OK;
+}
+
+extern "C" int32_t knnssd_knn_topk(knnssd_ctx *ctx, const float *queries_dev, int32_t n_queries, int32_t k,
+                                   int32_t *anchor_idx_out, float *cosine_out, int32_t *domain_out) {
+    if (!ctx || !queries_dev || !anchor_idx_out || !domain_out) return KNNSSD_EINVAL;
+    if (!ctx->anchors) return KNNSSD_ESTATE;
+    if ((uintptr_t)queries_dev & 15) return KNNSSD_EINVAL;
+    if (n_queries <= 0 || k < 1 || k > KNN_KMAX || k > ctx->n_anchors) return KNNSSD_ERANGE;
+    const int N = ctx->n_anchors, D = ctx->cfg.d_model;
+    float *scores = ctx->wsp<float>(ctx->L.knn_scores);
+    KnnTopk *res = ctx->wsp<KnnTopk>(ctx->L.knn_topk);
+    int wgs = (N + 3) / 4;
+    if (wgs > 4096) wgs = 4096;
+    for (int q0 = 0; q0 < n_queries; q0 += KNN_QMAX) {
+        const int nq = n_queries - q0 < KNN_QMAX ? n_queries - q0 : KNN_QMAX;
+        const float *qp = queries_dev + (size_t)q0 * D;
+        if (nq == 1) hipLaunchKernelGGL(knn_scores_multi_kernel<1>, dim3(wgs), dim3(256), 0, ctx->stream, qp, ctx->anchors, N, D, scores);
+        else if (nq == 2) hipLaunchKernelGGL(knn_scores_multi_kernel<2>, dim3(wgs), dim3(256), 0, ctx->stream, qp, ctx->anchors, N, D, scores);
+        else if (nq == 3) hipLaunchKernelGGL(knn_scores_multi_kernel<3>, dim3(wgs), dim3(256), 0, ctx->stream, qp, ctx->anchors, N, D, scores);
+        else hipLaunchKernelGGL(knn_scores_multi_kernel<4>, dim3(wgs), dim3(256), 0, ctx->stream, qp, ctx->anchors, N, D, scores);
+        int n_slices = N / 2048;                      // stage 1 slices per query: a few thousand scores each
+        if (n_slices < 1) n_slices = 1;
+        if (n_slices > 64) n_slices = 64;
+        int32_t *cand_idx = ctx->wsp<int32_t>(ctx->L.knn_cand_idx);
+        float *cand_val = ctx->wsp<float>(ctx->L.knn_cand_val);
+        int *bad = ctx->wsp<int>(ctx->L.knn_bad);
+        hipLaunchKernelGGL(fill_zero_kernel, dim3(1), dim3(64), 0, ctx->stream, bad, KNN_QMAX);
+        hipLaunchKernelGGL(knn_topk_part_kernel, dim3(nq, n_slices), dim3(1024), 0, ctx->stream, scores, N, k, n_slices, cand_idx, cand_val, bad);
+        hipLaunchKernelGGL(knn_topk_kernel, dim3(nq), dim3(1024), 0, ctx->stream, cand_idx, cand_val, n_slices, bad, qp, ctx->labels, D, k, res);
+        HIP_TRY(hipGetLastError());
+        KS_TRY(read_back(ctx, res, sizeof(KnnTopk) * nq));
+        const KnnTopk *h = reinterpret_cast<const KnnTopk *>(ctx->h_stage);
+        for (int q = 0; q < nq; ++q) {
+            if (h[q].degenerate) return KNNSSD_EDEGENERATE;
+            if (h[q].domain < 0 || h[q].domain >= ctx->n_domains) return KNNSSD_ERANGE;
+            for (int r = 0; r < k; ++r) {
+                anchor_idx_out[(size_t)(q0 + q) * k + r] = h[q].idx[r];
+                if (cosine_out) cosine_out[(size_t)(q0 + q) * k + r] = h[q].cosine[r];
+            }
+            domain_out[q0 + q] = h[q].domain;
+        }
+    }
     return KNNSSD_OK;
 }
 

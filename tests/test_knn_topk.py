@@ -1,0 +1,83 @@
+"""K > 1 nearest anchors with a majority vote, batched queries: oracle pins (CPU) and GPU parity."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import knnssd_oracle as O
+from paper_2505_16162_amd import synth
+
+
+def _table(n, d, n_dom, seed, sigma=0.3):
+    anchors, labels, centres = synth.make_anchors(d, n, n_dom, sigma, seed=seed)
+    return anchors, labels, centres
+
+
+def test_k1_is_the_routing_argmax():
+    anchors, labels, centres = _table(200, 64, 5, seed=1)
+    masks = np.zeros((5, 8), dtype=np.uint8)
+    for i in range(20):
+        q = synth.make_domain_query(centres, i % 5, 0.3, seed=50 + i).numpy()
+        n_star, dom, _, _ = O.knn_select(q, anchors.numpy(), labels.numpy(), masks)
+        order, cos, d1 = O.knn_topk_vote(q, anchors.numpy(), labels.numpy(), 1)
+        assert order == [n_star] and d1 == dom
+
+
+def test_topk_against_brute_force_and_planted_neighbours():
+    rng = np.random.default_rng(3)
+    anchors = rng.standard_normal((40, 16))
+    labels = np.arange(40) % 4
+    q = rng.standard_normal(16)
+    # brute force written out: cosine of every pair, full sort
+    cos = [float(np.dot(q, a) / (np.linalg.norm(q) * np.linalg.norm(a))) for a in anchors]
+    want = sorted(range(40), key=lambda n: (-np.float32(cos[n]), n))[:7]
+    order, scores, _ = O.knn_topk_vote(q, anchors, labels, 7)
+    assert order == want
+    assert np.allclose(scores, [cos[n] for n in want], atol=1e-12)
+    assert all(scores[i] >= scores[i + 1] for i in range(6))
+    # planted: three anchors are positive multiples of the query -> cosine 1, index order among them
+    anchors[[31, 5, 17]] = np.outer([2.0, 0.5, 7.0], q)
+    order, scores, _ = O.knn_topk_vote(q, anchors, labels, 3)
+    assert order == [5, 17, 31] and np.allclose(scores, 1.0)
+
+
+def test_vote_rule():
+    q = np.array([1.0, 0.0])
+    # ranked by cosine: anchors 0,1,2,3,4 with labels B A A B C
+    ang = [0.01, 0.02, 0.03, 0.04, 0.05]
+    anchors = np.array([[np.cos(t), np.sin(t)] for t in ang])
+    labels = np.array([1, 0, 0, 1, 2])
+    assert O.knn_topk_vote(q, anchors, labels, 1)[2] == 1
+    assert O.knn_topk_vote(q, anchors, labels, 3)[2] == 0          # A has two of three
+    assert O.knn_topk_vote(q, anchors, labels, 2)[2] == 1          # one each: the better-ranked label
+    assert O.knn_topk_vote(q, anchors, labels, 4)[2] == 1          # two each: B's best anchor ranks first
+    assert O.knn_topk_vote(q, anchors, labels, 5)[2] == 1
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("n,k,nq", [(40, 1, 1), (777, 3, 5), (777, 16, 4), (5000, 8, 9)])
+def test_gpu_topk_matches_oracle(n, k, nq):
+    from paper_2505_16162_amd import binding
+    from gpu_common import make_pair
+    shape = synth.small_shape("knnk", d_ffn=704, max_seq=64)
+    n_dom = 5
+    w, orc, gpu = make_pair(shape, seed=2, max_anchors=n)
+    anchors, labels, centres = _table(n, shape.d_model, n_dom, seed=9)
+    masks = synth.make_block_masks(shape.n_blocks, n_dom, 1, seed=6)
+    gpu.knnssd_set_anchors(anchors, labels, masks)
+    queries = torch.stack([synth.make_domain_query(centres, i % n_dom, 0.3, seed=300 + i) for i in range(nq)])
+    idx, cos, dom = gpu.knnssd_knn_topk(queries, k)
+    for i in range(nq):
+        order, scores, d = O.knn_topk_vote(queries[i].numpy(), anchors.numpy(), labels.numpy(), k)
+        # fp32 sums on the GPU against fp64 in the oracle: the ranking is unique wherever neighbouring scores differ
+        # by more than the rounding error, which seeded Gaussian data satisfies with a wide margin
+        assert idx[i] == order, (i, idx[i], order)
+        assert np.allclose(cos[i], scores, atol=2e-6)
+        assert dom[i] == d
+    # the K = 1 result is the routing call's
+    a1, d1, _ = gpu.knnssd_select_skipset(queries[0])
+    assert [a1] == gpu.knnssd_knn_topk(queries[:1], 1)[0][0] and d1 == gpu.knnssd_knn_topk(queries[:1], 1)[2][0]
+    with pytest.raises(binding.KnnSsdError):
+        gpu.knnssd_knn_topk(queries, 17)
+    with pytest.raises(binding.KnnSsdError):
+        gpu.knnssd_knn_topk(torch.zeros_like(queries), k)      # zero-norm query
+    gpu.close()
