@@ -200,25 +200,26 @@ __device__ __forceinline__ void gemm_epilogue(const GemmOp &op, const PassCtl *c
             if (lane == 0) op.ss_out[(size_t)wg * KS_MAX_ROWS + m] = sacc;
         }
     } else if (op.type == OP_SWIGLU) {
-        for (int t = tid; t < n_first; t += NT) {
+        for (int i = tid; i < n_first * n_rows; i += NT) {       // one thread per (gate row, token row)
+            const int t = i / n_rows, m = i - t * n_rows;
             const int n = rowidx[t];
-            for (int m = 0; m < n_rows; ++m) {
-                float a = vals[t * ld + m] * rstd[m], b = vals[(t + n_first) * ld + m] * rstd[m];
-                store_act<PLANES>(op, m, n, op.N, (a / (1.0f + expf(-a))) * b);
-            }
+            const float a = vals[t * ld + m] * rstd[m], b = vals[(t + n_first) * ld + m] * rstd[m];
+            store_act<PLANES>(op, m, n, op.N, (a / (1.0f + expf(-a))) * b);
         }
     } else if (op.type == OP_QKV) {
         const int half = op.hd >> 1, qd = op.H * op.hd;
         const int np = n_first;
         bf16_t *kc = op.kv_block;
         bf16_t *vc = op.kv_block + (size_t)op.Hkv * op.max_seq * op.hd;
-        for (int t = tid; t < R - np; t += NT) {
+        const int start = ctl->start;
+        for (int it = tid; it < (R - np) * n_rows; it += NT) {    // one thread per (pair or value row, token row)
             // t < np: rotary pair (row, row + half);  t >= np: value row (local index t + np)
+            const int t = it / n_rows, m = it - t * n_rows;
             const bool is_pair = t < np;
             const int lr = is_pair ? t : t + np;
             const int n = rowidx[lr];
-            for (int m = 0; m < n_rows; ++m) {
-                const int pos = ctl->start + m;
+            {
+                const int pos = start + m;
                 if (is_pair) {
                     const int head = n / op.hd, i = n - head * op.hd;
                     const float c = op.cos_t[(size_t)pos * half + i], s = op.sin_t[(size_t)pos * half + i];
@@ -240,10 +241,12 @@ __device__ __forceinline__ void gemm_epilogue(const GemmOp &op, const PassCtl *c
             }
         }
     } else if (op.type == OP_HEAD) {
-        // logits of this workgroup's rows, plus (max, lowest arg-max, sum exp(l - max)) over them
-        for (int m = row_lo; m < n_rows; ++m) {
+        // logits of this workgroup's rows, plus (max, lowest arg-max, sum exp(l - max)) over them: one wavefront per
+        // token row, so the rows of a pass are handled side by side and the workgroup never meets
+        const int lane = tid & 63;
+        for (int m = row_lo + (tid >> 6); m < n_rows; m += NWV) {
             float bv = -INFINITY; int bi = 0x7fffffff;
-            for (int t = tid; t < R; t += NT) {
+            for (int t = lane; t < R; t += 64) {
                 const int n = rowidx[t];
                 const float l = vals[t * ld + m] * rstd[m];
                 op.logits[(size_t)m * op.N + n] = l;
@@ -254,19 +257,10 @@ __device__ __forceinline__ void gemm_epilogue(const GemmOp &op, const PassCtl *c
                 float ov = __shfl_xor(bv, off, 64); int oi = __shfl_xor(bi, off, 64);
                 if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
             }
-            __syncthreads();
-            if ((tid & 63) == 0) { scratch[tid >> 6] = bv; scratch[NWV + (tid >> 6)] = __int_as_float(bi); }
-            __syncthreads();
-            bv = scratch[0]; bi = __float_as_int(scratch[NWV]);
-#pragma unroll
-            for (int w = 1; w < NWV; ++w) {
-                float ov = scratch[w]; int oi = __float_as_int(scratch[NWV + w]);
-                if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
-            }
             float se = 0.f;
-            for (int t = tid; t < R; t += NT) se += expf(vals[t * ld + m] * rstd[m] - bv);
-            se = block_sum(se, scratch + 2 * NWV);
-            if (tid == 0) {
+            for (int t = lane; t < R; t += 64) se += expf(vals[t * ld + m] * rstd[m] - bv);
+            se = wave_sum(se);
+            if (lane == 0) {
                 HeadPartial hp; hp.maxv = bv; hp.idx = bi; hp.sumexp = (R > 0) ? se : 0.f; hp.pad = 0;
                 op.head_part[(size_t)m * nwg + wg] = hp;
             }
