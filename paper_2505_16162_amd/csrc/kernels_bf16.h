@@ -18,9 +18,6 @@
 
 namespace ks {
 
-#ifndef KS_GEMV_DB
-#define KS_GEMV_DB 0
-#endif
 constexpr int NT = 1024;       // threads per workgroup
 constexpr int NWV = NT / 64;   // wavefronts per workgroup
 constexpr int MAX_LROWS = 640; // most rows of one matrix a workgroup may own
@@ -93,6 +90,12 @@ __device__ __forceinline__ void stream_drain8(u32x4 *r) {
     asm volatile("s_waitcnt vmcnt(0)" : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]), "+v"(r[4]), "+v"(r[5]), "+v"(r[6]), "+v"(r[7]) : : "memory");
 }
 
+// First of the n items that workgroup wg owns when n items are dealt to the KS_NWG workgroups in balanced contiguous
+// shares: floor(n * wg / KS_NWG), as a multiply and a shift (a 64-bit division costs a wavefront hundreds of cycles,
+// and every wavefront runs several of these before it can issue its first load).
+static_assert(KS_NWG == 256, "wg_share assumes 256 workgroups");
+__device__ __forceinline__ int wg_share(int n, int wg) { return (int)(((unsigned int)n * (unsigned int)wg) >> 8); }
+
 // Rows of W a workgroup owns, as a table of global row indices in LDS. Returns the count.
 // OP_QKV orders them [first halves of np rotary pairs][their second halves][nv value rows],
 // OP_SWIGLU [nf gate rows][the matching nf up rows].
@@ -101,8 +104,8 @@ __device__ __forceinline__ int build_row_table(const GemmOp &op, int wg, int nwg
     if (op.type == OP_QKV) {
         const int half = op.hd >> 1;
         const int P = (op.H + op.Hkv) * half, VR = op.Hkv * op.hd;
-        const int p0 = (int)((long long)P * wg / nwg), p1 = (int)((long long)P * (wg + 1) / nwg);
-        const int v0 = (int)((long long)VR * wg / nwg), v1 = (int)((long long)VR * (wg + 1) / nwg);
+        const int p0 = wg_share(P, wg), p1 = wg_share(P, wg + 1);
+        const int v0 = wg_share(VR, wg), v1 = wg_share(VR, wg + 1);
         const int np = p1 - p0, nv = v1 - v0;
         R = 2 * np + nv;
         for (int t = threadIdx.x; t < R; t += NT) {
@@ -118,13 +121,13 @@ __device__ __forceinline__ int build_row_table(const GemmOp &op, int wg, int nwg
         }
         *n_first = np;
     } else if (op.type == OP_SWIGLU) {
-        const int f0 = (int)((long long)op.N * wg / nwg), f1 = (int)((long long)op.N * (wg + 1) / nwg);
+        const int f0 = wg_share(op.N, wg), f1 = wg_share(op.N, wg + 1);
         const int nf = f1 - f0;
         R = 2 * nf;
         for (int t = threadIdx.x; t < R; t += NT) rowidx[t] = (t < nf) ? f0 + t : op.N + f0 + (t - nf);
         *n_first = nf;
     } else {
-        const int r0 = (int)((long long)op.N * wg / nwg), r1 = (int)((long long)op.N * (wg + 1) / nwg);
+        const int r0 = wg_share(op.N, wg), r1 = wg_share(op.N, wg + 1);
         R = r1 - r0;
         for (int t = threadIdx.x; t < R; t += NT) rowidx[t] = r0 + t;
         *n_first = R;
@@ -289,7 +292,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmOp &op, const PassCtl *c
 // ------------------------------------------------------------------------------------------
 struct WgSplit {
     int R, n_first;   // rows of this workgroup, rows of the first kind (rotary pairs / gate rows)
-    int T, rpt, tl, ksplit, g, gshift;
+    int T, rpt, tl, ksplit, ksshift, g, gshift;
     int KS, nfull, rem;   // 32-column steps in K, full 16-step blocks, steps of the last partial block
     size_t wg_base;       // element offset of the workgroup's region in the packed matrix
 };
@@ -301,18 +304,19 @@ __device__ __forceinline__ WgSplit make_split(const GemmOp &op, int wg, int nwg,
     if (op.type == OP_QKV) {
         const int half = op.hd >> 1;
         const long long P = (long long)(op.H + op.Hkv) * half, VR = (long long)op.Hkv * op.hd;
-        rows_before = (size_t)(2 * (P * wg / nwg) + VR * wg / nwg);
+        rows_before = (size_t)(2 * wg_share((int)P, wg) + wg_share((int)VR, wg));
     } else if (op.type == OP_SWIGLU) {
-        rows_before = (size_t)(2 * ((long long)op.N * wg / nwg));
+        rows_before = (size_t)(2 * wg_share(op.N, wg));
     } else {
-        rows_before = (size_t)((long long)op.N * wg / nwg);
+        rows_before = (size_t)wg_share(op.N, wg);
     }
     s.wg_base = rows_before * op.K;
     s.T = (s.R + 15) >> 4;
     s.rpt = s.T ? (s.R + s.T - 1) / s.T : 0;
     s.tl = s.T >= 4 ? 4 : (s.T >= 2 ? 2 : 1);
-    s.ksplit = NWV / s.tl;
-    s.g = 16 / s.ksplit;
+    s.ksplit = NWV / s.tl;                      // NWV = 16: 4, 8 or 16
+    s.ksshift = (s.tl == 4) ? 2 : (s.tl == 2 ? 3 : 4);
+    s.g = 16 >> s.ksshift;
     s.gshift = (s.g == 4) ? 2 : (s.g == 2 ? 1 : 0);
     s.KS = op.K >> 5;
     s.nfull = s.KS >> 4;
@@ -352,7 +356,7 @@ __global__ __launch_bounds__(NT, 1) void pack_matrix_kernel(GemmOp op, const bf1
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const WgSplit s = make_split(op, blockIdx.x, gridDim.x, rowidx);
     __syncthreads();
-    const int tlane = wave / s.ksplit, kpart = wave - tlane * s.ksplit;
+    const int tlane = wave >> s.ksshift, kpart = wave & (s.ksplit - 1);
     const int r16 = lane & 15, kg = lane >> 4;
     for (int round = 0; round * s.tl < s.T; ++round) {
         const WaveTile w = wave_tile(s, op.K, round, tlane, kpart);
@@ -383,7 +387,7 @@ __device__ __forceinline__ void gemv_device(const GemmOp &op, const PassCtl *ctl
 
     const WgSplit s = make_split(op, wg, nwg, rowidx);
     const int R = s.R;
-    const int tlane = wave / s.ksplit, kpart = wave - tlane * s.ksplit;
+    const int tlane = wave >> s.ksshift, kpart = wave & (s.ksplit - 1);
     const int r16 = lane & 15, kg = lane >> 4;
 
     // Order of the first loads: the input vector and the norm's shares (small, cache hits) go out first and the
@@ -404,7 +408,7 @@ __device__ __forceinline__ void gemv_device(const GemmOp &op, const PassCtl *ctl
     float xpre, gpre;
     {
         const bool resid = op.type == OP_RESID;
-        const int n = resid ? min((int)((long long)op.N * wg / nwg) + tid, op.N - 1) : 0;
+        const int n = resid ? min(wg_share(op.N, wg) + tid, op.N - 1) : 0;
         xpre = (resid ? op.x : op.act_in)[n];
         gpre = (resid ? op.gain_next : op.act_in)[n];
     }
@@ -551,7 +555,7 @@ __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl
     const WgSplit s = make_split(op, wg, nwg, rowidx);
     const int R = s.R;
 
-    const int tlane = wave / s.ksplit, kpart = wave - tlane * s.ksplit;
+    const int tlane = wave >> s.ksshift, kpart = wave & (s.ksplit - 1);
     const int r16 = lane & 15, kg = lane >> 4;
     const size_t plane = (size_t)KS_MAX_ROWS * K;
 
@@ -607,7 +611,7 @@ __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl
     float xpre, gpre;
     {
         const bool resid = op.type == OP_RESID;
-        const int n = resid ? min((int)((long long)op.N * wg / nwg) + (tid >> 4), op.N - 1) : 0;
+        const int n = resid ? min(wg_share(op.N, wg) + (tid >> 4), op.N - 1) : 0;
         const float *fallback = reinterpret_cast<const float *>(op.planes_in);
         xpre = (resid ? op.x : fallback)[resid ? (size_t)min(tid & 15, n_rows - 1) * op.N + n : 0];
         gpre = (resid ? op.gain_next : fallback)[n];
@@ -743,7 +747,7 @@ __global__ __launch_bounds__(NT) void embed_producer_kernel(GemmOp op, const Pas
     if (!ctl->active) return;
     const int n_rows = min(ctl->n_rows, KS_MAX_ROWS);
     const int wg = blockIdx.x, nwg = gridDim.x;
-    const int r0 = (int)((long long)op.N * wg / nwg), r1 = (int)((long long)op.N * (wg + 1) / nwg);
+    const int r0 = wg_share(op.N, wg), r1 = wg_share(op.N, wg + 1);
     for (int m = 0; m < n_rows; ++m) {
         const bf16_t *row = op.embed + (size_t)ctl->tok[m] * op.N;
         float ssq = 0.f;
