@@ -85,6 +85,31 @@ template <int KEEP>
 __device__ __forceinline__ void stream_wait(u32x4 &r) {
     asm volatile("s_waitcnt vmcnt(%1)" : "+v"(r) : "n"(KEEP) : "memory");
 }
+// the same for small operands that are expected in cache (no nontemporal hint)
+__device__ __forceinline__ u32x4 stream_load_x4(const void *p) {
+    u32x4 v;
+    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(v) : "v"(p) : "memory");
+    return v;
+}
+__device__ __forceinline__ float stream_load_f32(const float *p) {
+    float v;
+    asm volatile("global_load_dword %0, %1, off" : "=v"(v) : "v"(p) : "memory");
+    return v;
+}
+// waits that name several registers at once (a kernel's small first operands, issued before the KEEP loads that may
+// stay in flight): N 16-byte pieces, or four norm shares and two epilogue values
+template <int KEEP, int N>
+__device__ __forceinline__ void stream_wait_pieces(u32x4 *x) {
+    static_assert(N == 4 || N == 5, "piece count");
+    if constexpr (N == 4)
+        asm volatile("s_waitcnt vmcnt(%4)" : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]) : "n"(KEEP) : "memory");
+    else
+        asm volatile("s_waitcnt vmcnt(%5)" : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]) : "n"(KEEP) : "memory");
+}
+template <int KEEP>
+__device__ __forceinline__ void stream_wait_scalars(float *sh, float &a, float &b) {
+    asm volatile("s_waitcnt vmcnt(%6)" : "+v"(sh[0]), "+v"(sh[1]), "+v"(sh[2]), "+v"(sh[3]), "+v"(a), "+v"(b) : "n"(KEEP) : "memory");
+}
 // drain: every register of the batch is named, so that no use of any of them can be moved above the wait
 __device__ __forceinline__ void stream_drain8(u32x4 *r) {
     asm volatile("s_waitcnt vmcnt(0)" : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]), "+v"(r[4]), "+v"(r[5]), "+v"(r[6]), "+v"(r[7]) : : "memory");
@@ -385,100 +410,93 @@ __device__ __forceinline__ void gemv_device(const GemmOp &op, const PassCtl *ctl
     float *scratch = vals + MAX_LROWS;                               // [4*NWV + KS_MAX_ROWS]
     float *rstd_s = scratch + 4 * NWV;
 
+    // read through the scalar cache while that is still possible: after the first hand-placed load (whose memory
+    // clobber the compiler must honour) this would become a vector load queued behind the whole weight batch
+    const int active = ctl->active;
     const WgSplit s = make_split(op, wg, nwg, rowidx);
     const int R = s.R;
     const int tlane = wave >> s.ksshift, kpart = wave & (s.ksplit - 1);
     const int r16 = lane & 15, kg = lane >> 4;
 
     // Order of the first loads: the input vector and the norm's shares (small, cache hits) go out first and the
-    // first weight batch right behind them, before the pass control block has even been read; the vector is in
-    // LDS and the workgroup has met long before the weights arrive, so no wavefront sits on a full batch.
-    // Every load of this prologue is unconditional (addresses are clamped instead): only then does the compiler
-    // count the loads in flight exactly and wait for the small ones alone.
+    // first weight batch right behind them; the vector is in LDS and the workgroup has met long before the
+    // weights arrive, so no wavefront sits on a full batch. Every load of this prologue is a hand-placed one and
+    // unconditional (addresses are clamped instead), and one wait that leaves the weight batch in flight covers
+    // all the small ones: the compiler's own counting would charge the weight loads to them.
     constexpr int XQ = 4;
     u32x4 xr[XQ];
 #pragma unroll
-    for (int q = 0; q < XQ; ++q) xr[q] = *reinterpret_cast<const u32x4 *>(op.act_in + min((tid + q * NT) * 4, K - 4));
+    for (int q = 0; q < XQ; ++q) xr[q] = stream_load_x4(op.act_in + min((tid + q * NT) * 4, K - 4));
     float sh[4];
     {
         const float *sp = op.ss_in ? op.ss_in : op.act_in;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) sh[j] = sp[op.ss_in ? (size_t)min(lane + 64 * j, op.n_ss - 1) * KS_MAX_ROWS : 0];
+        for (int j = 0; j < 4; ++j) sh[j] = stream_load_f32(sp + (op.ss_in ? (size_t)min(lane + 64 * j, op.n_ss - 1) * KS_MAX_ROWS : 0));
     }
     float xpre, gpre;
     {
         const bool resid = op.type == OP_RESID;
         const int n = resid ? min(wg_share(op.N, wg) + tid, op.N - 1) : 0;
-        xpre = (resid ? op.x : op.act_in)[n];
-        gpre = (resid ? op.gain_next : op.act_in)[n];
+        xpre = stream_load_f32((resid ? op.x : op.act_in) + n);
+        gpre = stream_load_f32((resid ? op.gain_next : op.act_in) + n);
     }
-    WaveTile w = wave_tile(s, K, 0, tlane, kpart);
+    // Weight loads are hand-placed streaming loads the compiler does not track (see stream_load): all of them, so
+    // that none of the compiler's own waits is ever aimed at a weight register. Each batch is eight unconditional
+    // loads (a wavefront with fewer units re-reads its last one; one without units reads the matrix's first bytes).
+    // A round's batch is issued at ONE place in the code, the first round's included: with two places the compiler
+    // gives them different registers and joins them with copies, which would read registers whose loads are still
+    // in flight. (Round 0 therefore also runs for a workgroup without rows; it then owns no unit.)
     u32x4 wa[8];
-    auto load_batch = [&](const bf16_t *p, int u0, int cnt, int unit) {
+    if (!active) return;           // uniform (read long ago, so no wait here); loads in flight are dropped with the wavefront
+    for (int round = 0; round == 0 || round * s.tl < s.T; ++round) {
+        const WaveTile w = wave_tile(s, K, round, tlane, kpart);
+        const bf16_t *wp = op.W + w.base + (size_t)(kg * w.rows_t + min(r16, w.rows_t - 1)) * 8;
+        {
+            const bf16_t *p0 = w.cnt > 0 ? wp : op.W;
+            const int last = max(w.cnt - 1, 0);
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
-            if (u0 + i < cnt) wa[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p + (size_t)(u0 + i) * unit));
-    };
-    const bf16_t *wp = op.W + w.base + (size_t)(kg * w.rows_t + min(r16, w.rows_t - 1)) * 8;
-    {
-        const bf16_t *p0 = w.cnt > 0 ? wp : op.W;      // a wavefront without units reads the matrix's first bytes
-        const int last = max(w.cnt - 1, 0);
+            for (int i = 0; i < 8; ++i) wa[i] = stream_load(p0 + (size_t)min(i, last) * w.unit);
+        }
+        if (round == 0) {
+            stream_wait_pieces<8, XQ>(xr);                     // the eight weight loads stay in flight
+            stream_wait_scalars<8>(sh, xpre, gpre);
+            // (stores clamped like the loads: a duplicate writes the same value to the same place)
 #pragma unroll
-        for (int i = 0; i < 8; ++i) wa[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p0 + (size_t)min(i, last) * w.unit));
-    }
-    __builtin_amdgcn_sched_barrier(0);     // nothing that waits on a load may move up between the loads
-    if (!ctl->active) return;      // uniform; loads still in flight are dropped with the wavefront
-
-    // (stores clamped like the loads: a duplicate writes the same value to the same place; a conditional store
-    // would pull its load down next to it)
+            for (int q = 0; q < XQ; ++q) *reinterpret_cast<u32x4 *>(xs + min((tid + q * NT) * 4, K - 4)) = xr[q];
+            for (int i = (tid + XQ * NT) * 4; i < K; i += NT * 4) *reinterpret_cast<float4 *>(xs + i) = *reinterpret_cast<const float4 *>(op.act_in + i);
+            if (wave == 0) {
+                float share = 0.f;
 #pragma unroll
-    for (int q = 0; q < XQ; ++q) *reinterpret_cast<u32x4 *>(xs + min((tid + q * NT) * 4, K - 4)) = xr[q];
-    for (int i = (tid + XQ * NT) * 4; i < K; i += NT * 4) *reinterpret_cast<float4 *>(xs + i) = *reinterpret_cast<const float4 *>(op.act_in + i);
-    if (wave == 0) {
-        float share = 0.f;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) share += (lane + 64 * j < op.n_ss) ? sh[j] : 0.f;
-        if (op.ss_in)
-            for (int i = lane + 256; i < op.n_ss; i += 64) share += op.ss_in[(size_t)i * KS_MAX_ROWS];
-        const float r = op.ss_in ? 1.0f / sqrtf(wave_sum(share) * op.inv_dim + op.eps) : 1.0f;
-        if (lane == 0) rstd_s[0] = r;
-    }
-    __syncthreads();
-
-    for (int round = 0; round * s.tl < s.T; ++round) {
-        if (round > 0) {
-            w = wave_tile(s, K, round, tlane, kpart);
-            wp = op.W + w.base + (size_t)(kg * w.rows_t + min(r16, w.rows_t - 1)) * 8;
-            load_batch(wp, 0, w.cnt, w.unit);
+                for (int j = 0; j < 4; ++j) share += (lane + 64 * j < op.n_ss) ? sh[j] : 0.f;
+                if (op.ss_in)
+                    for (int i = lane + 256; i < op.n_ss; i += 64) share += op.ss_in[(size_t)i * KS_MAX_ROWS];
+                const float r = op.ss_in ? 1.0f / sqrtf(wave_sum(share) * op.inv_dim + op.eps) : 1.0f;
+                if (lane == 0) rstd_s[0] = r;
+            }
+            __syncthreads();
         }
         float acc = 0.f;
         int u0 = 0;
-        // the tile's first eight units were loaded with ordinary (compiler-counted) loads: they are used in a block of
-        // their own, so that the compiler's waits stay out of the steady loop below
-        if (w.cnt >= 16) {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const float *xp = xs + step_of_unit(s, kpart, i) * 32 + kg * 8;
-                const float4 x0 = *reinterpret_cast<const float4 *>(xp), x1 = *reinterpret_cast<const float4 *>(xp + 4);
-                acc = dot8(wa[i], x0, x1, acc);
-                wa[i] = stream_load(wp + (size_t)(i + 8) * w.unit);
-            }
-            u0 = 8;
-        }
         // steady state: every unit has a successor eight units on; its register is refilled the moment it has been
-        // used and the wait before a unit leaves the seven younger loads in flight, so the stream never drains
-        for (; u0 + 16 <= w.cnt; u0 += 8) {
+        // used and the wait before a unit leaves the seven younger loads in flight, so the stream never drains.
+        // (The loop sits under its own condition so that it has one way in: a second, empty way in would make the
+        // compiler treat the registers as results of loads it tracks and drain the stream at the loop's head.)
+        if (w.cnt >= 16) {
+            do {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const float *xp = xs + step_of_unit(s, kpart, u0 + i) * 32 + kg * 8;
-                const float4 x0 = *reinterpret_cast<const float4 *>(xp), x1 = *reinterpret_cast<const float4 *>(xp + 4);
-                stream_wait<7>(wa[i]);
-                acc = dot8(wa[i], x0, x1, acc);
-                wa[i] = stream_load(wp + (size_t)(u0 + i + 8) * w.unit);
-            }
+                for (int i = 0; i < 8; ++i) {
+                    const float *xp = xs + step_of_unit(s, kpart, u0 + i) * 32 + kg * 8;
+                    const float4 x0 = *reinterpret_cast<const float4 *>(xp), x1 = *reinterpret_cast<const float4 *>(xp + 4);
+                    stream_wait<7>(wa[i]);
+                    acc = dot8(wa[i], x0, x1, acc);
+                    wa[i] = stream_load(wp + (size_t)(u0 + i + 8) * w.unit);
+                }
+                u0 += 8;
+            } while (u0 + 16 <= w.cnt);
         }
-        // tail: at most 15 units left, drained batch by batch
-        for (; u0 < w.cnt; u0 += 8) {
+        // tail: at most 15 units left, drained batch by batch (at least one drain: no load of this round may be
+        // in flight when the next round's batch is issued into the same registers)
+        do {
             stream_drain8(wa);
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
@@ -488,10 +506,12 @@ __device__ __forceinline__ void gemv_device(const GemmOp &op, const PassCtl *ctl
                     acc = dot8(wa[i], x0, x1, acc);
                 }
             }
+            u0 += 8;
+            if (u0 >= w.cnt) break;        // left with nothing in flight; any load below is followed by a drain
 #pragma unroll
             for (int i = 0; i < 8; ++i)
-                if (u0 + 8 + i < w.cnt) wa[i] = stream_load(wp + (size_t)(u0 + 8 + i) * w.unit);
-        }
+                if (u0 + i < w.cnt) wa[i] = stream_load(wp + (size_t)(u0 + i) * w.unit);
+        } while (true);
         acc += __shfl_xor(acc, 16, 64);
         acc += __shfl_xor(acc, 32, 64);
         if (w.have && kg == 0 && r16 < w.rows_t) part[(w.t * s.rpt + r16) * NWV + kpart] = acc;
@@ -570,13 +590,13 @@ __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl
     const int bstride = KC * 2 + 16;                                     // bytes per staged row (+16: LDS bank spread)
     const int brow = min(r16, n_rows - 1);                               // dead token lanes re-read the last live row
     u32x4 breg[MFMA_BQ];
-    auto bchunk_load = [&](int c) {          // global -> registers: 16-byte pieces of chunk c
+    auto bchunk_load = [&](int c) {          // global -> registers: 16-byte pieces of chunk c (hand-placed loads)
         const int cols = min(KC, K - c * KC), p8 = cols >> 3, pieces = 3 * n_rows * p8;
 #pragma unroll
-        for (int q = 0; q < MFMA_BQ; ++q) {      // unconditional loads (clamped), so that none of them is waited for on the spot
+        for (int q = 0; q < MFMA_BQ; ++q) {      // unconditional (clamped): the waits below count on exactly MFMA_BQ loads
             const int i = min(tid + q * NT, pieces - 1);
             const int pr = i / p8, c8 = i - pr * p8, pl = pr / n_rows, row = pr - pl * n_rows;
-            breg[q] = *reinterpret_cast<const u32x4 *>(op.planes_in + pl * plane + (size_t)row * K + (size_t)c * KC + c8 * 8);
+            breg[q] = stream_load_x4(op.planes_in + pl * plane + (size_t)row * K + (size_t)c * KC + c8 * 8);
         }
     };
     auto bchunk_store = [&](int c) {         // registers -> LDS buffer c & 1
@@ -596,26 +616,29 @@ __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl
     };
 
     // Order of the first loads: activations, norm shares and residual values (small, cache hits) go out first and
-    // the first weight batch right behind them, before the pass control block has been read. The activations
-    // are in LDS and the workgroup has met long before the weights arrive.
-    // Every load of this prologue is unconditional (addresses are clamped instead): only then does the compiler
-    // count the loads in flight exactly and wait for the small ones alone.
+    // the first weight batch right behind them. The activations are in LDS and the workgroup has met long before
+    // the weights arrive. Every load of the main part is a hand-placed one (see stream_load) and unconditional
+    // (addresses are clamped instead), so the number of loads in flight is known at every wait; the compiler's
+    // own counting would charge the weight stream to the small loads and the other way round.
+    const int active = ctl->active;     // through the scalar cache, which only works before the first hand-placed load
     bchunk_load(0);
     float sh[4];
     {
         const float *sp = op.ss_in ? op.ss_in : reinterpret_cast<const float *>(op.planes_in);
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-            sh[j] = sp[op.ss_in ? (size_t)min(lane + 64 * j, op.n_ss - 1) * KS_MAX_ROWS + min(wave, n_rows - 1) : 0];
+            sh[j] = stream_load_f32(sp + (op.ss_in ? (size_t)min(lane + 64 * j, op.n_ss - 1) * KS_MAX_ROWS + min(wave, n_rows - 1) : 0));
     }
     float xpre, gpre;
     {
         const bool resid = op.type == OP_RESID;
         const int n = resid ? min(wg_share(op.N, wg) + (tid >> 4), op.N - 1) : 0;
         const float *fallback = reinterpret_cast<const float *>(op.planes_in);
-        xpre = (resid ? op.x : fallback)[resid ? (size_t)min(tid & 15, n_rows - 1) * op.N + n : 0];
-        gpre = (resid ? op.gain_next : fallback)[n];
+        xpre = stream_load_f32((resid ? op.x : fallback) + (resid ? (size_t)min(tid & 15, n_rows - 1) * op.N + n : 0));
+        gpre = stream_load_f32((resid ? op.gain_next : fallback) + n);
     }
+    if (!active) return;                 // uniform (read long ago, so no wait here); loads in flight are dropped with the wavefront
+    if (s.T == 0) stream_wait_scalars<0>(sh, xpre, gpre);     // a workgroup without rows still takes part in the epilogue
 
     constexpr int DA = 8;                        // weight loads in flight per wavefront
     u32x4 a[DA];
@@ -627,15 +650,18 @@ __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl
         const bf16_t *ap = op.W + w.base + (size_t)(kg * w.rows_t + min(r16, w.rows_t - 1)) * 8;
         int cnt = chunk_count(0, w.have);
         const bool stage = round == 0 || NC > 1;     // a single chunk stays in LDS for every round
-        if (stage && round > 0) bchunk_load(0);
-        {
-            const bf16_t *p0 = cnt > 0 ? ap : op.W;        // a wavefront without units reads the matrix's first bytes
-            const int last = max(cnt - 1, 0);
+        // a batch: eight unconditional loads (a wavefront with fewer units re-reads its last one; one without units
+        // reads the matrix's first bytes). No load of an earlier batch is in flight when one is issued.
+        auto a_batch = [&](const bf16_t *p, int n) {
+            const bf16_t *p0 = n > 0 ? p : op.W;
+            const int last = max(n - 1, 0);
 #pragma unroll
-            for (int j = 0; j < DA; ++j) a[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p0 + (size_t)min(j, last) * w.unit));
-        }
+            for (int j = 0; j < DA; ++j) a[j] = stream_load(p0 + (size_t)min(j, last) * w.unit);
+        };
+        if (stage && round > 0) bchunk_load(0);
+        a_batch(ap, cnt);
         if (round == 0) {
-            if (!ctl->active) return;            // uniform; loads still in flight are dropped with the wavefront
+            stream_wait_scalars<DA>(sh, xpre, gpre);     // the weight batch stays in flight
             if (wave < KS_MAX_ROWS) {
                 float share = 0.f;
 #pragma unroll
@@ -647,42 +673,61 @@ __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl
             }
         }
         if (stage) {
+            stream_wait_pieces<DA, MFMA_BQ>(breg);
             bchunk_store(0);
             __syncthreads();
         }
-        for (int c = 0; c < NC; ++c) {
+        int c = 0;
+        do {                                     // NC >= 1
             if (c + 1 < NC) bchunk_load(c + 1);
             const char *bsrc = bbuf + (c & 1) * BBUF + (size_t)brow * bstride + kg * 16;
-            for (int i = 0; i < cnt; i += DA) {
+            auto unit_mfma = [&](int u, const u32x4 &a4) {
+                const int ls = step_of_unit(s, kpart, u);     // step within the chunk
+                const bf16x8 av = __builtin_bit_cast(bf16x8, a4);
 #pragma unroll
-                for (int j = 0; j < DA; ++j) {
-                    if (i + j < cnt) {
-                        const int ls = step_of_unit(s, kpart, i + j);     // step within the chunk
-                        const bf16x8 av = __builtin_bit_cast(bf16x8, a[j]);
+                for (int p = 0; p < 3; ++p) {
+                    const u32x4 bv = *reinterpret_cast<const u32x4 *>(bsrc + (size_t)p * n_rows * bstride + ls * 64);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bv), acc, 0, 0, 0);
+                }
+            };
+            int u0 = 0;
+            // steady state: a unit's register is refilled the moment the unit has been used, and the wait before a
+            // unit leaves the seven younger weight loads in flight (loads of the next activation chunk, issued
+            // after the batch, only make that wait stricter). One way into the loop: see the draft GEMV.
+            if (cnt >= 2 * DA) {
+                do {
 #pragma unroll
-                        for (int p = 0; p < 3; ++p) {
-                            const u32x4 bv = *reinterpret_cast<const u32x4 *>(bsrc + (size_t)p * n_rows * bstride + ls * 64);
-                            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bv), acc, 0, 0, 0);
-                        }
-                        if (i + j + DA < cnt)
-                            a[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(ap + (size_t)(i + j + DA) * w.unit));
+                    for (int j = 0; j < DA; ++j) {
+                        stream_wait<DA - 1>(a[j]);
+                        unit_mfma(u0 + j, a[j]);
+                        a[j] = stream_load(ap + (size_t)(u0 + j + DA) * w.unit);
                     }
-                }
+                    u0 += DA;
+                } while (u0 + 2 * DA <= cnt);
             }
-            ap += (size_t)cnt * w.unit;
-            if (c + 1 < NC) {
-                // next chunk's first weight loads go out before the workgroup meets, so the stream never drains
-                cnt = chunk_count(c + 1, w.have);
-                {
-                    const bf16_t *p0 = cnt > 0 ? ap : op.W;        // a wavefront without units reads the matrix's first bytes
-                    const int last = max(cnt - 1, 0);
+            // tail: at most 15 units left, drained batch by batch; at least one drain, so that no load (of weights or
+            // of the next activation chunk) is in flight afterwards
+            do {
+                stream_drain8(a);
 #pragma unroll
-                    for (int j = 0; j < DA; ++j) a[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p0 + (size_t)min(j, last) * w.unit));
-                }
-                bchunk_store(c + 1);
-                __syncthreads();
-            }
-        }
+                for (int j = 0; j < DA; ++j)
+                    if (u0 + j < cnt) unit_mfma(u0 + j, a[j]);
+#pragma unroll
+                for (int j = 0; j < DA; ++j)
+                    if (u0 + DA + j < cnt) a[j] = stream_load(ap + (size_t)(u0 + DA + j) * w.unit);
+                u0 += DA;
+            } while (u0 < cnt);        // a load was issued above only if this holds: every load is followed by a drain
+            ap += (size_t)cnt * w.unit;
+            if (c + 1 >= NC) break;                // nothing in flight here
+            // next chunk's first weight loads go out before the workgroup meets
+            ++c;
+            cnt = chunk_count(c, w.have);
+            a_batch(ap, cnt);
+            stream_wait_pieces<DA, MFMA_BQ>(breg);     // long complete (drained above); orders the stores after it
+            bchunk_store(c);
+            __syncthreads();
+        } while (true);
+        stream_drain8(a);      // nothing is in flight here (every way out of the loop passes a drain); costs nothing
         // partial tile of this wavefront -> LDS; lane holds D[row 4*kg + q][token r16]. The partials of
         // consecutive rounds alternate between two buffers, so one meeting per round is enough: a buffer is
         // written again only after every wavefront has passed the next round's meeting, i.e. finished summing it.
@@ -702,7 +747,6 @@ __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl
             }
         }
     }
-    if (s.T == 0 && !ctl->active) return;
     __syncthreads();
     gemm_epilogue<true>(op, ctl, wg, nwg, R, s.n_first, rowidx, vals, KS_MAX_ROWS, rstd_s,
                         op.type == OP_HEAD ? ctl->head_from : 0, n_rows, scratch, xpre, gpre);
