@@ -31,6 +31,7 @@ enum { OP_QKV = 0, OP_RESID = 1, OP_SWIGLU = 2, OP_HEAD = 3, OP_EMBED = 4 };
 struct HeadPartial { float maxv; int idx; float sumexp; int pad; };
 
 // One matrix-vector / small-M matrix product with its epilogue.
+struct WgSplit;
 struct GemmOp {
     int type;
     const bf16_t *W;  // [N][K] row-major; OP_SWIGLU: [2N][K], gate rows then up rows
@@ -58,7 +59,11 @@ struct GemmOp {
     const bf16_t *embed;
     // verification GEMM: LDS plan (dynamic LDS bytes of the launch, most rows any workgroup owns of this matrix)
     int lds_bytes, max_rows;
+    int kc, nc;               // activation chunk length in columns and chunk count (mfma_chunking, set by the host)
     int n_rows;               // token rows of the pass as the host counts them (the same number the control block holds)
+    // [KS_NWG] this matrix shape's workgroup splits, tabulated once (split_table_kernel): a kernel reads its entry
+    // with one scalar load instead of recomputing it in every wavefront of every launch
+    const WgSplit *split;
 };
 
 __device__ __forceinline__ float bf_lo(unsigned int u) { return __uint_as_float(u << 16); }
@@ -121,10 +126,19 @@ __device__ __forceinline__ void stream_drain8(u32x4 *r) {
 static_assert(KS_NWG == 256, "wg_share assumes 256 workgroups");
 __device__ __forceinline__ int wg_share(int n, int wg) { return (int)(((unsigned int)n * (unsigned int)wg) >> 8); }
 
+// A uniform value the optimiser must treat as defined here: arithmetic on it cannot be hoisted above this point.
+__device__ __forceinline__ int pinned_here(int v) {
+    asm volatile("" : "+s"(v));
+    return v;
+}
+
 // Rows of W a workgroup owns, as a table of global row indices in LDS. Returns the count.
 // OP_QKV orders them [first halves of np rotary pairs][their second halves][nv value rows],
 // OP_SWIGLU [nf gate rows][the matching nf up rows].
-__device__ __forceinline__ int build_row_table(const GemmOp &op, int wg, int nwg, int *rowidx, int *n_first) {
+// FILL = false only counts (scalar work): the GEMM kernels need the counts to place their first weight loads and
+// fill the table afterwards, while those loads are in flight.
+template <bool FILL>
+__device__ __forceinline__ int build_row_table(const GemmOp &op, int wg, int *rowidx, int *n_first) {
     int R = 0;
     if (op.type == OP_QKV) {
         const int half = op.hd >> 1;
@@ -133,28 +147,32 @@ __device__ __forceinline__ int build_row_table(const GemmOp &op, int wg, int nwg
         const int v0 = wg_share(VR, wg), v1 = wg_share(VR, wg + 1);
         const int np = p1 - p0, nv = v1 - v0;
         R = 2 * np + nv;
-        for (int t = threadIdx.x; t < R; t += NT) {
-            int row;
-            if (t < 2 * np) {
-                int p = p0 + (t < np ? t : t - np);
-                int head = p / half, i = p - head * half;
-                row = head * op.hd + i + (t < np ? 0 : half);
-            } else {
-                row = (op.H + op.Hkv) * op.hd + v0 + (t - 2 * np);
+        if constexpr (FILL) {
+            for (int t = threadIdx.x; t < R; t += NT) {
+                int row;
+                if (t < 2 * np) {
+                    int p = p0 + (t < np ? t : t - np);
+                    int head = p / half, i = p - head * half;
+                    row = head * op.hd + i + (t < np ? 0 : half);
+                } else {
+                    row = (op.H + op.Hkv) * op.hd + v0 + (t - 2 * np);
+                }
+                rowidx[t] = row;
             }
-            rowidx[t] = row;
         }
         *n_first = np;
     } else if (op.type == OP_SWIGLU) {
         const int f0 = wg_share(op.N, wg), f1 = wg_share(op.N, wg + 1);
         const int nf = f1 - f0;
         R = 2 * nf;
-        for (int t = threadIdx.x; t < R; t += NT) rowidx[t] = (t < nf) ? f0 + t : op.N + f0 + (t - nf);
+        if constexpr (FILL)
+            for (int t = threadIdx.x; t < R; t += NT) rowidx[t] = (t < nf) ? f0 + t : op.N + f0 + (t - nf);
         *n_first = nf;
     } else {
         const int r0 = wg_share(op.N, wg), r1 = wg_share(op.N, wg + 1);
         R = r1 - r0;
-        for (int t = threadIdx.x; t < R; t += NT) rowidx[t] = r0 + t;
+        if constexpr (FILL)
+            for (int t = threadIdx.x; t < R; t += NT) rowidx[t] = r0 + t;
         *n_first = R;
     }
     return R;
@@ -315,16 +333,18 @@ __device__ __forceinline__ void gemm_epilogue(const GemmOp &op, const PassCtl *c
 // The draft GEMV and the verification GEMM read the same units; they differ only in the
 // arithmetic applied to a unit. The packed matrix has the size of the original.
 // ------------------------------------------------------------------------------------------
-struct WgSplit {
+struct alignas(64) WgSplit {
     int R, n_first;   // rows of this workgroup, rows of the first kind (rotary pairs / gate rows)
     int T, rpt, tl, ksplit, ksshift, g, gshift;
     int KS, nfull, rem;   // 32-column steps in K, full 16-step blocks, steps of the last partial block
     size_t wg_base;       // element offset of the workgroup's region in the packed matrix
 };
+static_assert(sizeof(WgSplit) == 64, "one 64-byte scalar load per workgroup");
 
+template <bool FILL = true>
 __device__ __forceinline__ WgSplit make_split(const GemmOp &op, int wg, int nwg, int *rowidx) {
     WgSplit s;
-    s.R = build_row_table(op, wg, nwg, rowidx, &s.n_first);
+    s.R = build_row_table<FILL>(op, wg, rowidx, &s.n_first);
     size_t rows_before;
     if (op.type == OP_QKV) {
         const int half = op.hd >> 1;
@@ -375,6 +395,12 @@ __device__ __forceinline__ int step_of_unit(const WgSplit &s, int kpart, int u) 
     return ((u >> s.gshift) << 4) + kpart * s.g + (u & (s.g - 1));
 }
 
+// Tabulates the splits of one matrix shape (type, N, K and the head counts of op): table[wg], KS_NWG entries.
+__global__ void split_table_kernel(GemmOp op, WgSplit *table) {
+    const int wg = blockIdx.x * blockDim.x + threadIdx.x;
+    if (wg < KS_NWG) table[wg] = make_split<false>(op, wg, KS_NWG, nullptr);
+}
+
 // Rewrites a row-major matrix into stream order (run once per matrix when the model is loaded).
 __global__ __launch_bounds__(NT, 1) void pack_matrix_kernel(GemmOp op, const bf16_t *__restrict__ src, bf16_t *__restrict__ dst) {
     __shared__ int rowidx[MAX_LROWS];
@@ -413,7 +439,7 @@ __device__ __forceinline__ void gemv_device(const GemmOp &op, const PassCtl *ctl
     // read through the scalar cache while that is still possible: after the first hand-placed load (whose memory
     // clobber the compiler must honour) this would become a vector load queued behind the whole weight batch
     const int active = ctl->active;
-    const WgSplit s = make_split(op, wg, nwg, rowidx);
+    const WgSplit s = op.split[wg];                // tabulated; the row table is filled below
     const int R = s.R;
     const int tlane = wave >> s.ksshift, kpart = wave & (s.ksplit - 1);
     const int r16 = lane & 15, kg = lane >> 4;
@@ -458,21 +484,18 @@ __device__ __forceinline__ void gemv_device(const GemmOp &op, const PassCtl *ctl
             for (int i = 0; i < 8; ++i) wa[i] = stream_load(p0 + (size_t)min(i, last) * w.unit);
         }
         if (round == 0) {
-            stream_wait_pieces<8, XQ>(xr);                     // the eight weight loads stay in flight
-            stream_wait_scalars<8>(sh, xpre, gpre);
+            // the row table is read after the next meeting at the earliest; its index arithmetic is pinned behind
+            // the weight loads just issued (it is loop invariant and would otherwise be hoisted in front of them)
+            GemmOp shape;
+            shape.type = pinned_here(op.type); shape.N = pinned_here(op.N);
+            shape.H = pinned_here(op.H); shape.Hkv = pinned_here(op.Hkv); shape.hd = pinned_here(op.hd);
+            int n_first_unused;
+            build_row_table<true>(shape, pinned_here(wg), rowidx, &n_first_unused);
+            stream_wait_pieces<8 + 6, XQ>(xr);          // the six small loads and the eight weight loads stay in flight
             // (stores clamped like the loads: a duplicate writes the same value to the same place)
 #pragma unroll
             for (int q = 0; q < XQ; ++q) *reinterpret_cast<u32x4 *>(xs + min((tid + q * NT) * 4, K - 4)) = xr[q];
             for (int i = (tid + XQ * NT) * 4; i < K; i += NT * 4) *reinterpret_cast<float4 *>(xs + i) = *reinterpret_cast<const float4 *>(op.act_in + i);
-            if (wave == 0) {
-                float share = 0.f;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) share += (lane + 64 * j < op.n_ss) ? sh[j] : 0.f;
-                if (op.ss_in)
-                    for (int i = lane + 256; i < op.n_ss; i += 64) share += op.ss_in[(size_t)i * KS_MAX_ROWS];
-                const float r = op.ss_in ? 1.0f / sqrtf(wave_sum(share) * op.inv_dim + op.eps) : 1.0f;
-                if (lane == 0) rstd_s[0] = r;
-            }
             __syncthreads();
         }
         float acc = 0.f;
@@ -515,6 +538,18 @@ __device__ __forceinline__ void gemv_device(const GemmOp &op, const PassCtl *ctl
         acc += __shfl_xor(acc, 16, 64);
         acc += __shfl_xor(acc, 32, 64);
         if (w.have && kg == 0 && r16 < w.rows_t) part[(w.t * s.rpt + r16) * NWV + kpart] = acc;
+    }
+    // the norm's shares and the epilogue's two values were issued before the first weight batch and are long here
+    // (every round ends drained); the wait only ties their registers to this point
+    stream_wait_scalars<0>(sh, xpre, gpre);
+    if (wave == 0) {
+        float share = 0.f;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) share += (lane + 64 * j < op.n_ss) ? sh[j] : 0.f;
+        if (op.ss_in)
+            for (int i = lane + 256; i < op.n_ss; i += 64) share += op.ss_in[(size_t)i * KS_MAX_ROWS];
+        const float r = op.ss_in ? 1.0f / sqrtf(wave_sum(share) * op.inv_dim + op.eps) : 1.0f;
+        if (lane == 0) rstd_s[0] = r;
     }
     __syncthreads();
     // finished dot products: fixed-order sum over the wavefronts that shared the tile's columns
@@ -559,6 +594,19 @@ __host__ __device__ inline int mfma_bbuf_bytes(size_t lds_total, int max_rows) {
     const long long cap = (long long)MFMA_BQ * NT * 16;
     return (int)(b > cap ? cap : b);
 }
+// The token rows (B operand) are staged through LDS in column chunks shared by all wavefronts: only the live rows
+// are staged, so few rows mean long chunks (often the whole of K). A chunk is a multiple of 512 columns, i.e. whole
+// blocks of the column deal; the deal itself does not depend on the chunk length, so a row's sum is grouped the
+// same way however many rows are live.
+__host__ __device__ inline void mfma_chunking(size_t lds_total, int max_rows, int n_rows, int K, int *kc, int *nc) {
+    const int bbuf = mfma_bbuf_bytes(lds_total, max_rows);
+    int KC = (bbuf / (3 * n_rows) - 16) / 2;
+    KC = KC / 512 * 512;
+    if (KC < 512) KC = 512;
+    if (KC > K) KC = (K + 511) / 512 * 512;
+    *kc = KC;
+    *nc = (K + KC - 1) / KC;
+}
 
 __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl *ctl, int wg, int nwg, char *lds) {
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -572,41 +620,49 @@ __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl
     char *bbuf = lds + mfma_fixed_lds(op.max_rows);                     // [2][BBUF] activation chunks
     const int n_rows = op.n_rows;                                       // the host's count; equals ctl->n_rows
 
-    const WgSplit s = make_split(op, wg, nwg, rowidx);
+    const int active = ctl->active;     // both through the scalar cache, which only works before the first hand-placed load
+    const WgSplit s = op.split[wg];     // tabulated; the row table is filled below, behind the first loads
     const int R = s.R;
 
     const int tlane = wave >> s.ksshift, kpart = wave & (s.ksplit - 1);
     const int r16 = lane & 15, kg = lane >> 4;
-    const size_t plane = (size_t)KS_MAX_ROWS * K;
-
-    // The token rows (B operand) are staged through LDS in column chunks shared by all wavefronts: only the
-    // live rows are staged, so few rows mean long chunks (often the whole of K). A chunk is a multiple of 512
-    // columns, i.e. whole blocks of the column deal; the deal itself does not depend on the chunk length, so a
-    // row's sum is grouped the same way however many rows are live.
-    int KC = (BBUF / (3 * n_rows) - 16) / 2;
-    KC = max(512, KC / 512 * 512);
-    if (KC > K) KC = (K + 511) / 512 * 512;
-    const int NC = (K + KC - 1) / KC;
+    const int KC = op.kc, NC = op.nc;                                    // see mfma_chunking
     const int bstride = KC * 2 + 16;                                     // bytes per staged row (+16: LDS bank spread)
     const int brow = min(r16, n_rows - 1);                               // dead token lanes re-read the last live row
     u32x4 breg[MFMA_BQ];
+    // piece i of a chunk of p8 pieces per staged row -> (staged row, piece in the row). The quotient comes from a
+    // float product (exact for i < 2^13, p8 <= 2^11 with a correctly rounded reciprocal) and is corrected by one
+    // step either way, so it does not depend on the reciprocal's last bit; an integer division costs ten times
+    // the instructions, and every wavefront runs ten of them before its first weight load otherwise.
+    auto piece_of = [&](int i, int p8, float inv_p8, int *pr, int *c8) {
+        int q = (int)(((float)i + 0.5f) * inv_p8);
+        int r = i - q * p8;
+        if (r < 0) { --q; r += p8; }
+        if (r >= p8) { ++q; r -= p8; }
+        *pr = q; *c8 = r;
+    };
     auto bchunk_load = [&](int c) {          // global -> registers: 16-byte pieces of chunk c (hand-placed loads)
         const int cols = min(KC, K - c * KC), p8 = cols >> 3, pieces = 3 * n_rows * p8;
+        const float inv_p8 = 1.0f / (float)p8;
 #pragma unroll
         for (int q = 0; q < MFMA_BQ; ++q) {      // unconditional (clamped): the waits below count on exactly MFMA_BQ loads
             const int i = min(tid + q * NT, pieces - 1);
-            const int pr = i / p8, c8 = i - pr * p8, pl = pr / n_rows, row = pr - pl * n_rows;
-            breg[q] = stream_load_x4(op.planes_in + pl * plane + (size_t)row * K + (size_t)c * KC + c8 * 8);
+            int pr, c8;
+            piece_of(i, p8, inv_p8, &pr, &c8);
+            const int pl = (pr >= n_rows) + (pr >= 2 * n_rows), row = pr - pl * n_rows;
+            breg[q] = stream_load_x4(op.planes_in + ((pl * KS_MAX_ROWS + row) * K + c * KC + c8 * 8));   // < 2^31: 48 K columns at most
         }
     };
     auto bchunk_store = [&](int c) {         // registers -> LDS buffer c & 1
         const int cols = min(KC, K - c * KC), p8 = cols >> 3, pieces = 3 * n_rows * p8;
+        const float inv_p8 = 1.0f / (float)p8;
         char *dst = bbuf + (c & 1) * BBUF;
 #pragma unroll
         for (int q = 0; q < MFMA_BQ; ++q) {      // clamped like the loads: a duplicate writes the same value to the same place
             const int i = min(tid + q * NT, pieces - 1);
-            const int pr = i / p8, c8 = i - pr * p8;
-            *reinterpret_cast<u32x4 *>(dst + (size_t)pr * bstride + c8 * 16) = breg[q];
+            int pr, c8;
+            piece_of(i, p8, inv_p8, &pr, &c8);
+            *reinterpret_cast<u32x4 *>(dst + (pr * bstride + c8 * 16)) = breg[q];
         }
     };
     // units of chunk c this wavefront owns (they are consecutive in its stream)
@@ -620,7 +676,6 @@ __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl
     // the weights arrive. Every load of the main part is a hand-placed one (see stream_load) and unconditional
     // (addresses are clamped instead), so the number of loads in flight is known at every wait; the compiler's
     // own counting would charge the weight stream to the small loads and the other way round.
-    const int active = ctl->active;     // through the scalar cache, which only works before the first hand-placed load
     bchunk_load(0);
     float sh[4];
     {
@@ -638,7 +693,6 @@ __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl
         gpre = stream_load_f32((resid ? op.gain_next : fallback) + n);
     }
     if (!active) return;                 // uniform (read long ago, so no wait here); loads in flight are dropped with the wavefront
-    if (s.T == 0) stream_wait_scalars<0>(sh, xpre, gpre);     // a workgroup without rows still takes part in the epilogue
 
     constexpr int DA = 8;                        // weight loads in flight per wavefront
     u32x4 a[DA];
@@ -661,16 +715,13 @@ __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl
         if (stage && round > 0) bchunk_load(0);
         a_batch(ap, cnt);
         if (round == 0) {
-            stream_wait_scalars<DA>(sh, xpre, gpre);     // the weight batch stays in flight
-            if (wave < KS_MAX_ROWS) {
-                float share = 0.f;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) share += (lane + 64 * j < op.n_ss) ? sh[j] : 0.f;
-                if (op.ss_in && wave < n_rows)
-                    for (int i = lane + 256; i < op.n_ss; i += 64) share += op.ss_in[(size_t)i * KS_MAX_ROWS + wave];
-                const float r = (op.ss_in && wave < n_rows) ? 1.0f / sqrtf(wave_sum(share) * op.inv_dim + op.eps) : 1.0f;
-                if (lane == 0) rstd_s[wave] = r;
-            }
+            // the row table is read after the next meeting at the earliest; its index arithmetic is pinned behind
+            // the weight loads just issued (it is loop invariant and would otherwise be hoisted in front of them)
+            GemmOp shape;
+            shape.type = pinned_here(op.type); shape.N = pinned_here(op.N);
+            shape.H = pinned_here(op.H); shape.Hkv = pinned_here(op.Hkv); shape.hd = pinned_here(op.hd);
+            int n_first_unused;
+            build_row_table<true>(shape, pinned_here(wg), rowidx, &n_first_unused);
         }
         if (stage) {
             stream_wait_pieces<DA, MFMA_BQ>(breg);
@@ -746,6 +797,18 @@ __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl
                 vals[(tt * s.rpt + rit) * KS_MAX_ROWS + (e & 15)] = sum;
             }
         }
+    }
+    // the norm's shares and the epilogue's two values were issued before the first weight batch and are long here
+    // (every round ends drained); the wait only ties their registers to this point
+    stream_wait_scalars<0>(sh, xpre, gpre);
+    if (wave < KS_MAX_ROWS) {
+        float share = 0.f;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) share += (lane + 64 * j < op.n_ss) ? sh[j] : 0.f;
+        if (op.ss_in && wave < n_rows)
+            for (int i = lane + 256; i < op.n_ss; i += 64) share += op.ss_in[(size_t)i * KS_MAX_ROWS + wave];
+        const float r = (op.ss_in && wave < n_rows) ? 1.0f / sqrtf(wave_sum(share) * op.inv_dim + op.eps) : 1.0f;
+        if (lane == 0) rstd_s[wave] = r;
     }
     __syncthreads();
     gemm_epilogue<true>(op, ctl, wg, nwg, R, s.n_first, rowidx, vals, KS_MAX_ROWS, rstd_s,

@@ -43,7 +43,7 @@ struct WsLayout {
     size_t draft_ctl, ver_ctl, gen, head, knn, out3;
     size_t x, xn, qkv, att, u, logits, hidden_last, rope_cos, rope_sin, knn_scores, knn_topk, knn_cand_idx, knn_cand_val, knn_bad, out_tokens;
     // tuned bf16 path
-    size_t act_d, planes_d, qrot, planes_att, planes_u, ss, head_part, attn_part;
+    size_t act_d, planes_d, qrot, planes_att, planes_u, ss, head_part, attn_part, split_tab;
     // tuned prompt prefill (stream-order weights only): all prompt rows at once
     size_t pf_tokens, pf_x, pf_q, pf_frag_d, pf_frag_att, pf_frag_u, pf_ss, pf_rstd;
     int pf_tt;          // token tiles the fragment buffers are laid out for
@@ -107,6 +107,7 @@ static WsLayout ws_layout(const knnssd_model_cfg *c) {
         L.ss = take((size_t)KS_NWG * R * 4);
         L.head_part = take(R * (size_t)KS_NWG * sizeof(HeadPartial));
         L.attn_part = take(R * c->n_heads * max_chunks * (c->head_dim + 2) * 4);
+        L.split_tab = take((size_t)5 * KS_NWG * sizeof(WgSplit));
         if (c->weights_packed) {
             const size_t tt = (((size_t)c->max_seq + 15) / 16 + 15) / 16 * 16, rows = tt * 16;
             L.pf_tt = (int)tt;
@@ -148,6 +149,8 @@ struct knnssd_ctx {
     bool tuned;         // shape fits the tuned bf16 draft kernels
     bool tuned_verify;  // ... and the matrix-core verification kernels (every K a multiple of 32)
     bool tuned_prefill; // ... and the many-row prefill kernels (a row group fits 16 tile slots)
+    // tabulated workgroup splits of the five matrix shapes (tuned kernels)
+    const WgSplit *split_qkv = nullptr, *split_o = nullptr, *split_gu = nullptr, *split_down = nullptr, *split_head = nullptr;
     int32_t cache_len;
     int32_t last_anchor = -1, last_domain = -1;   // most recent routing
     // pinned host staging for small read-backs
@@ -241,6 +244,30 @@ extern "C" int32_t knnssd_create(const knnssd_model_cfg *cfg, const knnssd_weigh
             ea = hipFuncSetAttribute((const void *)prefill_gemm_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pf_gemm_lds_bytes(2));
         if (ea != hipSuccess) {
             snprintf(g_hip_err, sizeof(g_hip_err), "%s (hipFuncSetAttribute)", hipGetErrorString(ea));
+            delete c;
+            return KNNSSD_EHIP;
+        }
+    }
+    if (c->tuned) {
+        // the five matrix shapes' workgroup splits, computed by the same device code that packs and reads the matrices
+        WgSplit *tab = c->wsp<WgSplit>(c->L.split_tab);
+        const int d = cfg->d_model, H = cfg->n_heads, Hkv = cfg->n_kv_heads, hd = cfg->head_dim;
+        GemmOp shape{};
+        shape.H = H; shape.Hkv = Hkv; shape.hd = hd;
+        auto tabulate = [&](int slot, int type, int N, int K) {
+            GemmOp o = shape;
+            o.type = type; o.N = N; o.K = K;
+            hipLaunchKernelGGL(split_table_kernel, dim3(1), dim3(KS_NWG), 0, c->stream, o, tab + (size_t)slot * KS_NWG);
+            return (const WgSplit *)(tab + (size_t)slot * KS_NWG);
+        };
+        c->split_qkv = tabulate(0, OP_QKV, (H + 2 * Hkv) * hd, d);
+        c->split_o = tabulate(1, OP_RESID, d, H * hd);
+        c->split_gu = tabulate(2, OP_SWIGLU, cfg->d_ffn, d);
+        c->split_down = tabulate(3, OP_RESID, d, cfg->d_ffn);
+        c->split_head = tabulate(4, OP_HEAD, cfg->vocab, d);
+        hipError_t et = hipGetLastError();
+        if (et != hipSuccess) {
+            snprintf(g_hip_err, sizeof(g_hip_err), "%s (split_table_kernel)", hipGetErrorString(et));
             delete c;
             return KNNSSD_EHIP;
         }
@@ -437,6 +464,7 @@ static int32_t run_pass_bf16(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, b
             else v.max_rows = per(v.N);
             v.lds_bytes = (int)KS_MAX_DYN_LDS;
             v.n_rows = n_rows;
+            mfma_chunking(KS_MAX_DYN_LDS, v.max_rows, n_rows, v.K, &v.kc, &v.nc);
             if (c->in_prefill) hipLaunchKernelGGL(gemm_mfma_kernel<true>, dim3(KS_NWG), dim3(NT), KS_MAX_DYN_LDS, s, v, ctl);
             else hipLaunchKernelGGL(gemm_mfma_kernel<false>, dim3(KS_NWG), dim3(NT), KS_MAX_DYN_LDS, s, v, ctl);
         }
@@ -466,7 +494,7 @@ static int32_t run_pass_bf16(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, b
         if (!(mask && mask[2 * b])) {
             GemmOp o = base;
             o.type = OP_QKV; o.W = (const bf16_t *)c->wqkv[b]; o.N = qkvd; o.K = d; o.act_in = act_d; o.planes_in = planes_d;
-            o.ss_in = ss; o.q_out = qrot; o.kv_block = kvb;
+            o.ss_in = ss; o.q_out = qrot; o.kv_block = kvb; o.split = c->split_qkv;
             launch(o);
             aa.kv_block = kvb;
             if (!others) {
@@ -478,18 +506,18 @@ static int32_t run_pass_bf16(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, b
             GemmOp r = base;
             r.type = OP_RESID; r.W = (const bf16_t *)c->wo[b]; r.N = d; r.K = qd; r.act_in = att; r.planes_in = planes_att;
             r.ss_in = nullptr; r.x = x; r.gain_next = next_gain(c, mask, 2 * b); r.act_out = act_d; r.planes_out = planes_d;
-            r.ss_out = ss;
+            r.ss_out = ss; r.split = c->split_o;
             launch(r);
         }
         if (!(mask && mask[2 * b + 1])) {
             GemmOp o = base;
             o.type = OP_SWIGLU; o.W = (const bf16_t *)c->wgu[b]; o.N = F; o.K = d; o.act_in = act_d; o.planes_in = planes_d;
-            o.ss_in = ss; o.act_out = u; o.planes_out = planes_u;
+            o.ss_in = ss; o.act_out = u; o.planes_out = planes_u; o.split = c->split_gu;
             launch(o);
             GemmOp r = base;
             r.type = OP_RESID; r.W = (const bf16_t *)c->wdown[b]; r.N = d; r.K = F; r.act_in = u; r.planes_in = planes_u;
             r.ss_in = nullptr; r.x = x; r.gain_next = next_gain(c, mask, 2 * b + 1); r.act_out = act_d; r.planes_out = planes_d;
-            r.ss_out = ss;
+            r.ss_out = ss; r.split = c->split_down;
             launch(r);
         }
     }
@@ -497,6 +525,7 @@ static int32_t run_pass_bf16(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, b
         GemmOp h = base;
         h.type = OP_HEAD; h.W = (const bf16_t *)c->lm_head; h.N = g.vocab; h.K = d; h.act_in = act_d; h.planes_in = planes_d;
         h.ss_in = ss; h.logits = c->wsp<float>(c->L.logits); h.head_part = c->wsp<HeadPartial>(c->L.head_part);
+        h.split = c->split_head;
         launch(h);
         if (others) hipLaunchKernelGGL(head_final_kernel, dim3(KS_MAX_ROWS), dim3(NT), 0, s, c->wsp<HeadPartial>(c->L.head_part), KS_NWG,
                            ctl, c->wsp<HeadResult>(c->L.head));
