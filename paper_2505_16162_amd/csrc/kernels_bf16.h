@@ -213,6 +213,15 @@ __device__ __forceinline__ void store_act(const GemmOp &op, int m, int n, int ld
     }
 }
 
+// i / n for 0 <= i < 2^20 and n >= 1 from a float product (inv = an approximation of 1/n within a few ulp): the
+// quotient is corrected by one step either way, so the result is exact; an integer division costs ten times as much
+__device__ __forceinline__ int div_small(int i, int n, float inv) {
+    int q = (int)(((float)i + 0.5f) * inv);
+    const int r = i - q * n;
+    q += (r >= n) - (r < 0);
+    return q;
+}
+
 template <bool PLANES>
 __device__ __forceinline__ void gemm_epilogue(const GemmOp &op, const PassCtl *ctl, int wg, int nwg, int R, int n_first,
                                               const int *rowidx, const float *vals, int ld, const float *rstd,
@@ -246,8 +255,9 @@ __device__ __forceinline__ void gemm_epilogue(const GemmOp &op, const PassCtl *c
             if (lane == 0) op.ss_out[(size_t)wg * KS_MAX_ROWS + m] = sacc;
         }
     } else if (op.type == OP_SWIGLU) {
+        const float inv_rows = __builtin_amdgcn_rcpf((float)n_rows);
         for (int i = tid; i < n_first * n_rows; i += NT) {       // one thread per (gate row, token row)
-            const int t = i / n_rows, m = i - t * n_rows;
+            const int t = div_small(i, n_rows, inv_rows), m = i - t * n_rows;
             const int n = rowidx[t];
             const float a = vals[t * ld + m] * rstd[m], b = vals[(t + n_first) * ld + m] * rstd[m];
             store_act<PLANES>(op, m, n, op.N, (a / (1.0f + expf(-a))) * b);
@@ -258,16 +268,18 @@ __device__ __forceinline__ void gemm_epilogue(const GemmOp &op, const PassCtl *c
         bf16_t *kc = op.kv_block;
         bf16_t *vc = op.kv_block + (size_t)op.Hkv * op.max_seq * op.hd;
         const int start = ctl->start;
+        const float inv_rows = __builtin_amdgcn_rcpf((float)n_rows);
+        const int hd_shift = 31 - __builtin_clz(op.hd), hd_mask = op.hd - 1;      // head_dim is 64 or 128
         for (int it = tid; it < (R - np) * n_rows; it += NT) {    // one thread per (pair or value row, token row)
             // t < np: rotary pair (row, row + half);  t >= np: value row (local index t + np)
-            const int t = it / n_rows, m = it - t * n_rows;
+            const int t = div_small(it, n_rows, inv_rows), m = it - t * n_rows;
             const bool is_pair = t < np;
             const int lr = is_pair ? t : t + np;
             const int n = rowidx[lr];
             {
                 const int pos = start + m;
                 if (is_pair) {
-                    const int head = n / op.hd, i = n - head * op.hd;
+                    const int head = n >> hd_shift, i = n & hd_mask;
                     const float c = op.cos_t[(size_t)pos * half + i], s = op.sin_t[(size_t)pos * half + i];
                     const float a = vals[lr * ld + m] * rstd[m], b = vals[(lr + np) * ld + m] * rstd[m];
                     const float ra = a * c - b * s, rb = b * c + a * s;
@@ -281,7 +293,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmOp &op, const PassCtl *c
                     }
                 } else {
                     const int vr = n - (op.H + op.Hkv) * op.hd;
-                    const int head = vr / op.hd, i = vr - head * op.hd;
+                    const int head = vr >> hd_shift, i = vr & hd_mask;
                     vc[((size_t)head * op.max_seq + pos) * op.hd + i] = float_to_bf16_rne(vals[lr * ld + m] * rstd[m]);
                 }
             }
@@ -635,15 +647,12 @@ __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl
     // step either way, so it does not depend on the reciprocal's last bit; an integer division costs ten times
     // the instructions, and every wavefront runs ten of them before its first weight load otherwise.
     auto piece_of = [&](int i, int p8, float inv_p8, int *pr, int *c8) {
-        int q = (int)(((float)i + 0.5f) * inv_p8);
-        int r = i - q * p8;
-        if (r < 0) { --q; r += p8; }
-        if (r >= p8) { ++q; r -= p8; }
-        *pr = q; *c8 = r;
+        const int q = div_small(i, p8, inv_p8);
+        *pr = q; *c8 = i - q * p8;
     };
     auto bchunk_load = [&](int c) {          // global -> registers: 16-byte pieces of chunk c (hand-placed loads)
         const int cols = min(KC, K - c * KC), p8 = cols >> 3, pieces = 3 * n_rows * p8;
-        const float inv_p8 = 1.0f / (float)p8;
+        const float inv_p8 = __builtin_amdgcn_rcpf((float)p8);       // within an ulp, which piece_of's correction covers
 #pragma unroll
         for (int q = 0; q < MFMA_BQ; ++q) {      // unconditional (clamped): the waits below count on exactly MFMA_BQ loads
             const int i = min(tid + q * NT, pieces - 1);
@@ -655,7 +664,7 @@ __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl
     };
     auto bchunk_store = [&](int c) {         // registers -> LDS buffer c & 1
         const int cols = min(KC, K - c * KC), p8 = cols >> 3, pieces = 3 * n_rows * p8;
-        const float inv_p8 = 1.0f / (float)p8;
+        const float inv_p8 = __builtin_amdgcn_rcpf((float)p8);       // within an ulp, which piece_of's correction covers
         char *dst = bbuf + (c & 1) * BBUF;
 #pragma unroll
         for (int q = 0; q < MFMA_BQ; ++q) {      // clamped like the loads: a duplicate writes the same value to the same place
