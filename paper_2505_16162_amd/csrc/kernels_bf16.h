@@ -37,7 +37,7 @@ struct GemmOp {
     const bf16_t *W;  // [N][K] row-major; OP_SWIGLU: [2N][K], gate rows then up rows
     int N, K;
     const float *act_in;      // draft: fp32 [K], the next norm's gain already applied
-    const bf16_t *planes_in;  // verify: [3][KS_MAX_ROWS][K] bf16 split of the same values
+    const bf16_t *planes_in;  // verify: bf16 split of the same values (three planes), stored as this GEMM's chunk images
     const float *ss_in;       // [n_ss][KS_MAX_ROWS] shares of sum(x^2); nullptr: input is not normalised
     int n_ss;
     float inv_dim, eps;
@@ -45,7 +45,7 @@ struct GemmOp {
     float *x;                 // [KS_MAX_ROWS][N]
     const float *gain_next;   // [N]
     float *act_out;           // fp32 [KS_MAX_ROWS][N]  (also OP_SWIGLU's output)
-    bf16_t *planes_out;       // [3][KS_MAX_ROWS][N]
+    bf16_t *planes_out;       // three planes as the chunk images of the GEMM that reads them (plane_image_offset)
     float *ss_out;            // [gridDim][KS_MAX_ROWS]
     // OP_QKV
     float *q_out;             // [KS_MAX_ROWS][H*hd], rotated
@@ -60,6 +60,7 @@ struct GemmOp {
     // verification GEMM: LDS plan (dynamic LDS bytes of the launch, most rows any workgroup owns of this matrix)
     int lds_bytes, max_rows;
     int kc, nc;               // activation chunk length in columns and chunk count (mfma_chunking, set by the host)
+    int out_kc;               // chunk length of the GEMM that reads planes_out (the same call for its shape and row count)
     int n_rows;               // token rows of the pass as the host counts them (the same number the control block holds)
     // [KS_NWG] this matrix shape's workgroup splits, tabulated once (split_table_kernel): a kernel reads its entry
     // with one scalar load instead of recomputing it in every wavefront of every launch
@@ -194,25 +195,6 @@ __device__ __forceinline__ float block_sum(float v, float *scratch) {
 // Epilogue shared by the draft (1 row) and verify (n_rows) kernels. vals[lr * ld + m] holds the
 // finished dot product of local row lr and token row m (LDS).
 // ------------------------------------------------------------------------------------------
-template <bool PLANES>
-__device__ __forceinline__ void store_act(const GemmOp &op, int m, int n, int ldn, float v) {
-    if (!PLANES) {
-        op.act_out[(size_t)m * ldn + n] = v;
-    } else {
-        // exact three-way split: v = hi + mid + lo, each a bf16 (truncation keeps every step exact)
-        unsigned int u = __float_as_uint(v);
-        float hi = __uint_as_float(u & 0xffff0000u);
-        float r1 = v - hi;
-        float mid = __uint_as_float(__float_as_uint(r1) & 0xffff0000u);
-        float lo = r1 - mid;
-        const size_t plane = (size_t)KS_MAX_ROWS * ldn;
-        const size_t o = (size_t)m * ldn + n;
-        op.planes_out[o] = (bf16_t)(u >> 16);
-        op.planes_out[plane + o] = (bf16_t)(__float_as_uint(mid) >> 16);
-        op.planes_out[2 * plane + o] = (bf16_t)(__float_as_uint(lo) >> 16);
-    }
-}
-
 // i / n for 0 <= i < 2^20 and n >= 1 from a float product (inv = an approximation of 1/n within a few ulp): the
 // quotient is corrected by one step either way, so the result is exact; an integer division costs ten times as much
 __device__ __forceinline__ int div_small(int i, int n, float inv) {
@@ -222,6 +204,41 @@ __device__ __forceinline__ int div_small(int i, int n, float inv) {
     return q;
 }
 
+// Where the verification GEMM's activations live ("chunk images"). The GEMM stages its token rows through LDS in
+// chunks of kc columns (mfma_chunking); the producer of those activations writes them in exactly the byte order of
+// the LDS stage, so staging a chunk is a straight copy of one contiguous range (no index arithmetic in front of the
+// consumer's first weight load). Chunk c holds columns [c*kc, c*kc + cols_c) of the n_rows live rows for the three
+// planes: 3*n_rows staged rows (plane-major) of cols_c + 8 elements each (8 = the 16 bytes that spread the rows over
+// the LDS banks; never read). All chunks before the last are full, so chunk c starts at c * 3*n_rows*(kc+8).
+// Returns the element offset of (plane 0, row m, column n) and the distance between planes.
+__device__ __forceinline__ int plane_image_offset(int m, int n, int ldn, int kc, int n_rows, float inv_kc, int *plane_step) {
+    const int c = div_small(n, kc, inv_kc);
+    const int cols_c = min(kc, ldn - c * kc);
+    *plane_step = n_rows * (cols_c + 8);
+    return c * (3 * n_rows * (kc + 8)) + m * (cols_c + 8) + (n - c * kc);
+}
+// elements a chunk-image buffer needs for up to KS_MAX_ROWS rows of ldn columns (chunks are at least 512 columns)
+__host__ __device__ inline size_t plane_image_elems(size_t ldn) { return 3 * (size_t)KS_MAX_ROWS * (ldn + 8 * ((ldn + 511) / 512)); }
+
+template <bool PLANES>
+__device__ __forceinline__ void store_act(const GemmOp &op, int m, int n, int ldn, float v, float inv_kc) {
+    if (!PLANES) {
+        op.act_out[(size_t)m * ldn + n] = v;
+    } else {
+        // exact three-way split: v = hi + mid + lo, each a bf16 (truncation keeps every step exact)
+        unsigned int u = __float_as_uint(v);
+        float hi = __uint_as_float(u & 0xffff0000u);
+        float r1 = v - hi;
+        float mid = __uint_as_float(__float_as_uint(r1) & 0xffff0000u);
+        float lo = r1 - mid;
+        int step;
+        const int o = plane_image_offset(m, n, ldn, op.out_kc, op.n_rows, inv_kc, &step);
+        op.planes_out[o] = (bf16_t)(u >> 16);
+        op.planes_out[o + step] = (bf16_t)(__float_as_uint(mid) >> 16);
+        op.planes_out[o + 2 * step] = (bf16_t)(__float_as_uint(lo) >> 16);
+    }
+}
+
 template <bool PLANES>
 __device__ __forceinline__ void gemm_epilogue(const GemmOp &op, const PassCtl *ctl, int wg, int nwg, int R, int n_first,
                                               const int *rowidx, const float *vals, int ld, const float *rstd,
@@ -229,6 +246,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmOp &op, const PassCtl *c
     // xpre / gpre: OP_RESID only, the residual value and the next norm's gain of element i = tid (fetched early by
     // the caller so that the tail of the kernel does not wait on memory)
     const int tid = threadIdx.x;
+    const float inv_kc = PLANES ? __builtin_amdgcn_rcpf((float)op.out_kc) : 0.f;
     if (op.type == OP_RESID) {
         // one thread per (row of W, token row): residual add, operands of the next norm, x^2 left in vals
         float *vw = const_cast<float *>(vals);
@@ -240,7 +258,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmOp &op, const PassCtl *c
                 const bool pre = i == tid;
                 const float xn = (pre ? xpre : op.x[(size_t)m * op.N + n]) + vals[i];
                 op.x[(size_t)m * op.N + n] = xn;
-                store_act<PLANES>(op, m, n, op.N, (pre ? gpre : op.gain_next[n]) * xn);
+                store_act<PLANES>(op, m, n, op.N, (pre ? gpre : op.gain_next[n]) * xn, inv_kc);
                 sq = xn * xn;
             }
             vw[i] = sq;
@@ -260,7 +278,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmOp &op, const PassCtl *c
             const int t = div_small(i, n_rows, inv_rows), m = i - t * n_rows;
             const int n = rowidx[t];
             const float a = vals[t * ld + m] * rstd[m], b = vals[(t + n_first) * ld + m] * rstd[m];
-            store_act<PLANES>(op, m, n, op.N, (a / (1.0f + expf(-a))) * b);
+            store_act<PLANES>(op, m, n, op.N, (a / (1.0f + expf(-a))) * b, inv_kc);
         }
     } else if (op.type == OP_QKV) {
         const int half = op.hd >> 1, qd = op.H * op.hd;
@@ -596,13 +614,22 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int MFMA_BQ = 5;          // 16-byte pieces of an activation chunk a thread may carry (chunk <= 80 KB)
 
-// LDS plan of the verification GEMM: [vals: max_rows x 16 floats][red: 2 x NWV x 256 floats][row table][scratch]
-// and two activation staging buffers sharing what is left of the dynamic LDS the launch asked for.
-__host__ __device__ inline size_t mfma_fixed_lds(int max_rows) {
-    return ((size_t)max_rows * KS_MAX_ROWS * 4 + (size_t)2 * NWV * 256 * 4 + (size_t)max_rows * 4 + (4 * NWV + KS_MAX_ROWS) * 4 + 255) / 256 * 256;
+// LDS plan of the verification GEMM: [vals: max_rows x 16 floats][red: 1 or 2 x NWV x 256 floats][row table][scratch]
+// and two activation staging buffers sharing what is left of the dynamic LDS the launch asked for. A staging buffer
+// must hold the shortest chunk (512 columns) of 16 rows; where a workgroup owns so many rows of the matrix that
+// two partial-tile buffers leave less than that, there is one (and one more meeting per round).
+constexpr int MFMA_MIN_BBUF = 3 * KS_MAX_ROWS * (512 * 2 + 16);
+__host__ __device__ inline size_t mfma_fixed_lds_rb(int max_rows, int red_bufs) {
+    return ((size_t)max_rows * KS_MAX_ROWS * 4 + (size_t)red_bufs * NWV * 256 * 4 + (size_t)max_rows * 4 + (4 * NWV + KS_MAX_ROWS) * 4 + 255) / 256 * 256;
+}
+__host__ __device__ inline int mfma_red_bufs(size_t lds_total, int max_rows) {
+    return ((long long)lds_total - (long long)mfma_fixed_lds_rb(max_rows, 2)) / 2 / 256 * 256 >= MFMA_MIN_BBUF ? 2 : 1;
+}
+__host__ __device__ inline size_t mfma_fixed_lds(size_t lds_total, int max_rows) {
+    return mfma_fixed_lds_rb(max_rows, mfma_red_bufs(lds_total, max_rows));
 }
 __host__ __device__ inline int mfma_bbuf_bytes(size_t lds_total, int max_rows) {
-    long long b = ((long long)lds_total - (long long)mfma_fixed_lds(max_rows)) / 2 / 256 * 256;
+    long long b = ((long long)lds_total - (long long)mfma_fixed_lds(lds_total, max_rows)) / 2 / 256 * 256;
     const long long cap = (long long)MFMA_BQ * NT * 16;
     return (int)(b > cap ? cap : b);
 }
@@ -624,12 +651,13 @@ __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int K = op.K;
     float *vals = reinterpret_cast<float *>(lds);                       // [max_rows][16]
-    float *red = vals + (size_t)op.max_rows * KS_MAX_ROWS;              // [2][NWV][256]
-    int *rowidx = reinterpret_cast<int *>(red + 2 * NWV * 256);
+    float *red = vals + (size_t)op.max_rows * KS_MAX_ROWS;              // [1 or 2][NWV][256]
+    const int RB = mfma_red_bufs(op.lds_bytes, op.max_rows);
+    int *rowidx = reinterpret_cast<int *>(red + RB * NWV * 256);
     float *scratch = reinterpret_cast<float *>(rowidx + op.max_rows);
     float *rstd_s = scratch + 4 * NWV;
     const int BBUF = mfma_bbuf_bytes(op.lds_bytes, op.max_rows);
-    char *bbuf = lds + mfma_fixed_lds(op.max_rows);                     // [2][BBUF] activation chunks
+    char *bbuf = lds + mfma_fixed_lds(op.lds_bytes, op.max_rows);       // [2][BBUF] activation chunks
     const int n_rows = op.n_rows;                                       // the host's count; equals ctl->n_rows
 
     const int active = ctl->active;     // both through the scalar cache, which only works before the first hand-placed load
@@ -639,40 +667,25 @@ __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl
     const int tlane = wave >> s.ksshift, kpart = wave & (s.ksplit - 1);
     const int r16 = lane & 15, kg = lane >> 4;
     const int KC = op.kc, NC = op.nc;                                    // see mfma_chunking
-    const int bstride = KC * 2 + 16;                                     // bytes per staged row (+16: LDS bank spread)
     const int brow = min(r16, n_rows - 1);                               // dead token lanes re-read the last live row
     u32x4 breg[MFMA_BQ];
-    // piece i of a chunk of p8 pieces per staged row -> (staged row, piece in the row). The quotient comes from a
-    // float product (exact for i < 2^13, p8 <= 2^11 with a correctly rounded reciprocal) and is corrected by one
-    // step either way, so it does not depend on the reciprocal's last bit; an integer division costs ten times
-    // the instructions, and every wavefront runs ten of them before its first weight load otherwise.
-    auto piece_of = [&](int i, int p8, float inv_p8, int *pr, int *c8) {
-        const int q = div_small(i, p8, inv_p8);
-        *pr = q; *c8 = i - q * p8;
-    };
-    auto bchunk_load = [&](int c) {          // global -> registers: 16-byte pieces of chunk c (hand-placed loads)
-        const int cols = min(KC, K - c * KC), p8 = cols >> 3, pieces = 3 * n_rows * p8;
-        const float inv_p8 = __builtin_amdgcn_rcpf((float)p8);       // within an ulp, which piece_of's correction covers
+    // The activations arrive as chunk images (plane_image_offset): chunk c is one contiguous range, 3*n_rows staged
+    // rows of cols_c + 8 elements, already in the byte order of the LDS stage. Staging is a straight copy, piece i
+    // of the range to byte 16*i of the buffer.
+    auto chunk_pieces = [&](int c) { return 3 * n_rows * ((min(KC, K - c * KC) >> 3) + 1); };
+    auto bchunk_load = [&](int c) {          // global -> registers (hand-placed loads)
+        const bf16_t *src = op.planes_in + c * (3 * n_rows * (KC + 8));
+        const int last = chunk_pieces(c) - 1;
 #pragma unroll
-        for (int q = 0; q < MFMA_BQ; ++q) {      // unconditional (clamped): the waits below count on exactly MFMA_BQ loads
-            const int i = min(tid + q * NT, pieces - 1);
-            int pr, c8;
-            piece_of(i, p8, inv_p8, &pr, &c8);
-            const int pl = (pr >= n_rows) + (pr >= 2 * n_rows), row = pr - pl * n_rows;
-            breg[q] = stream_load_x4(op.planes_in + ((pl * KS_MAX_ROWS + row) * K + c * KC + c8 * 8));   // < 2^31: 48 K columns at most
-        }
+        for (int q = 0; q < MFMA_BQ; ++q)        // unconditional (clamped): the waits below count on exactly MFMA_BQ loads
+            breg[q] = stream_load_x4(src + min(tid + q * NT, last) * 8);
     };
     auto bchunk_store = [&](int c) {         // registers -> LDS buffer c & 1
-        const int cols = min(KC, K - c * KC), p8 = cols >> 3, pieces = 3 * n_rows * p8;
-        const float inv_p8 = __builtin_amdgcn_rcpf((float)p8);       // within an ulp, which piece_of's correction covers
         char *dst = bbuf + (c & 1) * BBUF;
+        const int last = chunk_pieces(c) - 1;
 #pragma unroll
-        for (int q = 0; q < MFMA_BQ; ++q) {      // clamped like the loads: a duplicate writes the same value to the same place
-            const int i = min(tid + q * NT, pieces - 1);
-            int pr, c8;
-            piece_of(i, p8, inv_p8, &pr, &c8);
-            *reinterpret_cast<u32x4 *>(dst + (pr * bstride + c8 * 16)) = breg[q];
-        }
+        for (int q = 0; q < MFMA_BQ; ++q)        // clamped like the loads: a duplicate writes the same value to the same place
+            *reinterpret_cast<u32x4 *>(dst + min(tid + q * NT, last) * 16) = breg[q];
     };
     // units of chunk c this wavefront owns (they are consecutive in its stream)
     auto chunk_count = [&](int c, bool have) {
@@ -740,13 +753,14 @@ __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl
         int c = 0;
         do {                                     // NC >= 1
             if (c + 1 < NC) bchunk_load(c + 1);
-            const char *bsrc = bbuf + (c & 1) * BBUF + (size_t)brow * bstride + kg * 16;
+            const int bstride = (min(KC, K - c * KC) + 8) * 2;                  // bytes per staged row of this chunk
+            const char *bsrc = bbuf + (c & 1) * BBUF + brow * bstride + kg * 16;
             auto unit_mfma = [&](int u, const u32x4 &a4) {
                 const int ls = step_of_unit(s, kpart, u);     // step within the chunk
                 const bf16x8 av = __builtin_bit_cast(bf16x8, a4);
 #pragma unroll
                 for (int p = 0; p < 3; ++p) {
-                    const u32x4 bv = *reinterpret_cast<const u32x4 *>(bsrc + (size_t)p * n_rows * bstride + ls * 64);
+                    const u32x4 bv = *reinterpret_cast<const u32x4 *>(bsrc + p * n_rows * bstride + ls * 64);
                     acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bv), acc, 0, 0, 0);
                 }
             };
@@ -791,7 +805,7 @@ __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl
         // partial tile of this wavefront -> LDS; lane holds D[row 4*kg + q][token r16]. The partials of
         // consecutive rounds alternate between two buffers, so one meeting per round is enough: a buffer is
         // written again only after every wavefront has passed the next round's meeting, i.e. finished summing it.
-        float *redr = red + (size_t)(round & 1) * NWV * 256;
+        float *redr = red + (size_t)(round & (RB - 1)) * NWV * 256;
         {
             float *rp = redr + (size_t)wave * 256;
 #pragma unroll
@@ -806,6 +820,7 @@ __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl
                 vals[(tt * s.rpt + rit) * KS_MAX_ROWS + (e & 15)] = sum;
             }
         }
+        if (RB == 1) __syncthreads();   // the one buffer is written again in the next round
     }
     // the norm's shares and the epilogue's two values were issued before the first weight batch and are long here
     // (every round ends drained); the wait only ties their registers to this point
@@ -832,11 +847,12 @@ __global__ __launch_bounds__(NT, 1) void gemm_mfma_kernel(GemmOp op, const PassC
 }
 
 // final-RMSNorm hidden state of one row from the head's operands: gain (.) x (three planes) times rstd
-__global__ __launch_bounds__(NT) void hidden_from_planes_kernel(const bf16_t *planes, const float *ss, int n_ss, int d,
-                                                                float eps, const PassCtl *ctl, float *out0, float *out1) {
+__global__ __launch_bounds__(NT) void hidden_from_planes_kernel(const bf16_t *planes, int kc, int n_rows, const float *ss, int n_ss,
+                                                                int d, float eps, const PassCtl *ctl, float *out0, float *out1) {
+    // planes: the LM head's chunk images (chunk length kc, n_rows live rows as the host counts them)
     if (!ctl->active) return;
     __shared__ float rs;
-    const int m = ctl->n_rows - 1;
+    const int m = min(ctl->n_rows, n_rows) - 1;
     if (threadIdx.x < 64) {
         float s = 0.f;
         for (int i = threadIdx.x; i < n_ss; i += 64) s += ss[(size_t)i * KS_MAX_ROWS + m];
@@ -844,10 +860,11 @@ __global__ __launch_bounds__(NT) void hidden_from_planes_kernel(const bf16_t *pl
         if (threadIdx.x == 0) rs = 1.0f / sqrtf(s / (float)d + eps);
     }
     __syncthreads();
-    const size_t plane = (size_t)KS_MAX_ROWS * d;
+    const float inv_kc = __builtin_amdgcn_rcpf((float)kc);
     for (int i = blockIdx.x * NT + threadIdx.x; i < d; i += gridDim.x * NT) {
-        const size_t o = (size_t)m * d + i;
-        float v = (bf16_to_float(planes[o]) + bf16_to_float(planes[plane + o])) + bf16_to_float(planes[2 * plane + o]);
+        int step;
+        const int o = plane_image_offset(m, i, d, kc, n_rows, inv_kc, &step);
+        float v = (bf16_to_float(planes[o]) + bf16_to_float(planes[o + step])) + bf16_to_float(planes[o + 2 * step]);
         v *= rs;
         out0[i] = v;
         if (out1) out1[i] = v;
@@ -861,7 +878,9 @@ template <bool PLANES>
 __global__ __launch_bounds__(NT) void embed_producer_kernel(GemmOp op, const PassCtl *ctl) {
     __shared__ float scratch[NWV];
     if (!ctl->active) return;
-    const int n_rows = min(ctl->n_rows, KS_MAX_ROWS);
+    // the plane layout is the one the host computed for op.n_rows rows: never more rows than that
+    const int n_rows = min(min(ctl->n_rows, KS_MAX_ROWS), PLANES ? op.n_rows : KS_MAX_ROWS);
+    const float inv_kc = PLANES ? __builtin_amdgcn_rcpf((float)op.out_kc) : 0.f;
     const int wg = blockIdx.x, nwg = gridDim.x;
     const int r0 = wg_share(op.N, wg), r1 = wg_share(op.N, wg + 1);
     for (int m = 0; m < n_rows; ++m) {
@@ -870,7 +889,7 @@ __global__ __launch_bounds__(NT) void embed_producer_kernel(GemmOp op, const Pas
         for (int n = r0 + threadIdx.x; n < r1; n += NT) {
             float v = bf16_to_float(row[n]);
             op.x[(size_t)m * op.N + n] = v;
-            store_act<PLANES>(op, m, n, op.N, op.gain_next[n] * v);
+            store_act<PLANES>(op, m, n, op.N, op.gain_next[n] * v, inv_kc);
             ssq = fmaf(v, v, ssq);
         }
         float s = block_sum(ssq, scratch);
@@ -891,7 +910,8 @@ struct AttnArgs {
     int H, Hkv, hd, max_seq, max_chunks;
     // combine
     float *act_out;          // fp32 [KS_MAX_ROWS][H*hd]
-    bf16_t *planes_out;      // [3][KS_MAX_ROWS][H*hd]
+    bf16_t *planes_out;      // three planes as the O projection's chunk images (plane_image_offset)
+    int out_kc, n_rows;      // that GEMM's chunk length and the pass's row count as the host counts them
 };
 
 template <int HD>
@@ -1020,11 +1040,13 @@ __global__ __launch_bounds__(NT) void attn_partial_kernel(AttnArgs a, const Pass
 // merge the chunks of every (row, head) in chunk order and hand the result to the O projection
 template <bool PLANES>
 __device__ __forceinline__ void attn_combine_device(const AttnArgs &a, const PassCtl *ctl, int wg, int nwg) {
-    const int n_rows = min(ctl->n_rows, KS_MAX_ROWS), start = ctl->start;
+    // (the plane layout is the one the host computed for a.n_rows rows: never more rows than that)
+    const int n_rows = min(min(ctl->n_rows, KS_MAX_ROWS), PLANES ? a.n_rows : KS_MAX_ROWS), start = ctl->start;
     const int hd = a.hd, qd = a.H * hd;
     const int total = n_rows * qd;
     GemmOp st{};   // only the fields store_act uses
-    st.act_out = a.act_out; st.planes_out = a.planes_out;
+    st.act_out = a.act_out; st.planes_out = a.planes_out; st.out_kc = a.out_kc; st.n_rows = a.n_rows;
+    const float inv_kc = PLANES ? __builtin_amdgcn_rcpf((float)a.out_kc) : 0.f;
     for (int i = wg * NT + threadIdx.x; i < total; i += nwg * NT) {
         const int m = i / qd, c = i - m * qd, h = c / hd, dim = c - h * hd;
         const int n_chunks = (start + m + 1 + ATT_CHUNK - 1) / ATT_CHUNK;   // chunks row m can see
@@ -1038,7 +1060,7 @@ __device__ __forceinline__ void attn_combine_device(const AttnArgs &a, const Pas
             L = fmaf(cp[hd + 1], f, L);
             O = fmaf(cp[dim], f, O);
         }
-        store_act<PLANES>(st, m, c, qd, O / L);
+        store_act<PLANES>(st, m, c, qd, O / L, inv_kc);
     }
 }
 

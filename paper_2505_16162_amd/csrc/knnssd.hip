@@ -100,10 +100,10 @@ static WsLayout ws_layout(const knnssd_model_cfg *c) {
         const size_t qd = (size_t)c->n_heads * c->head_dim;
         const size_t max_chunks = ((size_t)c->max_seq + ATT_CHUNK - 1) / ATT_CHUNK;
         L.act_d = take(R * c->d_model * 4);
-        L.planes_d = take(3 * R * (size_t)c->d_model * 2);
+        L.planes_d = take(plane_image_elems((size_t)c->d_model) * 2);
         L.qrot = take(R * qd * 4);
-        L.planes_att = take(3 * R * qd * 2);
-        L.planes_u = take(3 * R * (size_t)c->d_ffn * 2);
+        L.planes_att = take(plane_image_elems(qd) * 2);
+        L.planes_u = take(plane_image_elems((size_t)c->d_ffn) * 2);
         L.ss = take((size_t)KS_NWG * R * 4);
         L.head_part = take(R * (size_t)KS_NWG * sizeof(HeadPartial));
         L.attn_part = take(R * c->n_heads * max_chunks * (c->head_dim + 2) * 4);
@@ -427,6 +427,13 @@ static bool tuned_ok(const knnssd_model_cfg &g) {
     if (per(g.vocab) > MAX_LROWS || 2 * per(g.d_ffn) > MAX_LROWS) return false;
     if (2 * per((long long)(g.n_heads + g.n_kv_heads) * g.head_dim / 2) + per((long long)g.n_kv_heads * g.head_dim) > MAX_LROWS) return false;
     if (per(g.d_model) > MAX_LROWS) return false;
+    // the verification GEMM's staging buffers hold the shortest chunk of 16 rows for every matrix
+    {
+        const int mr[4] = {per(g.vocab), 2 * per(g.d_ffn), per(g.d_model),
+                           2 * per((long long)(g.n_heads + g.n_kv_heads) * g.head_dim / 2) + per((long long)g.n_kv_heads * g.head_dim)};
+        for (int i = 0; i < 4; ++i)
+            if (mfma_bbuf_bytes(KS_MAX_DYN_LDS, mr[i]) < MFMA_MIN_BBUF) return false;
+    }
     // every reduction length is a whole number of 32-column MFMA steps
     if (g.d_model % 32 || g.d_ffn % 32 || (g.n_heads * g.head_dim) % 32) return false;
     if (gemv_lds_bytes(g.d_ffn) > KS_MAX_DYN_LDS || gemv_lds_bytes(g.n_heads * g.head_dim) > KS_MAX_DYN_LDS ||
@@ -454,14 +461,30 @@ static int32_t run_pass_bf16(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, b
     bf16_t *planes_d = c->wsp<bf16_t>(c->L.planes_d), *planes_att = c->wsp<bf16_t>(c->L.planes_att);
     bf16_t *planes_u = c->wsp<bf16_t>(c->L.planes_u);
     hipStream_t s = c->stream;
+    // most rows of one matrix a workgroup owns (fixes the verification GEMM's LDS plan), and the chunk length that
+    // GEMM stages its activations in: the producer of those activations writes them as that GEMM's chunk images
+    auto max_rows_of = [&](int type, int N) {
+        auto per = [&](long long n) { return (int)((n + KS_NWG - 1) / KS_NWG); };
+        if (type == OP_QKV) return 2 * per((long long)(H + Hkv) * hd / 2) + per((long long)Hkv * hd);
+        if (type == OP_SWIGLU) return 2 * per(N);
+        return per(N);
+    };
+    auto kc_of = [&](int type, int N, int K) {
+        int kc = 0, nc = 0;
+        mfma_chunking(KS_MAX_DYN_LDS, max_rows_of(type, N), n_rows, K, &kc, &nc);
+        return kc;
+    };
+    // chunk length of the GEMM that reads the residual stream's operands after sublayer index `after`
+    auto kc_next = [&](int after) {
+        for (int sl = after + 1; sl < 2 * g.n_blocks; ++sl)
+            if (!(mask && mask[sl])) return (sl & 1) ? kc_of(OP_SWIGLU, F, d) : kc_of(OP_QKV, qkvd, d);
+        return kc_of(OP_HEAD, g.vocab, d);
+    };
     auto launch = [&](const GemmOp &op) {
         if (rows1) hipLaunchKernelGGL(gemv_kernel, dim3(KS_NWG), dim3(NT), gemv_lds_bytes(op.K), s, op, ctl);
         else {
             GemmOp v = op;
-            auto per = [&](long long n) { return (int)((n + KS_NWG - 1) / KS_NWG); };
-            if (v.type == OP_QKV) v.max_rows = 2 * per((long long)(H + Hkv) * hd / 2) + per((long long)Hkv * hd);
-            else if (v.type == OP_SWIGLU) v.max_rows = 2 * per(v.N);
-            else v.max_rows = per(v.N);
+            v.max_rows = max_rows_of(v.type, v.N);
             v.lds_bytes = (int)KS_MAX_DYN_LDS;
             v.n_rows = n_rows;
             mfma_chunking(KS_MAX_DYN_LDS, v.max_rows, n_rows, v.K, &v.kc, &v.nc);
@@ -481,7 +504,7 @@ static int32_t run_pass_bf16(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, b
 
     GemmOp e = base;
     e.type = OP_EMBED; e.N = d; e.embed = (const bf16_t *)c->embed; e.x = x; e.gain_next = next_gain(c, mask, -1);
-    e.act_out = act_d; e.planes_out = planes_d; e.ss_out = ss;
+    e.act_out = act_d; e.planes_out = planes_d; e.ss_out = ss; e.n_rows = n_rows; e.out_kc = kc_next(-1);
     if (!others) {
     } else if (rows1) hipLaunchKernelGGL((embed_producer_kernel<false>), dim3(KS_NWG), dim3(NT), 0, s, e, ctl);
     else hipLaunchKernelGGL((embed_producer_kernel<true>), dim3(KS_NWG), dim3(NT), 0, s, e, ctl);
@@ -489,6 +512,7 @@ static int32_t run_pass_bf16(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, b
     AttnArgs aa{};
     aa.q = qrot; aa.partial = c->wsp<float>(c->L.attn_part); aa.H = H; aa.Hkv = Hkv; aa.hd = hd; aa.max_seq = g.max_seq;
     aa.max_chunks = (g.max_seq + ATT_CHUNK - 1) / ATT_CHUNK; aa.act_out = att; aa.planes_out = planes_att;
+    aa.n_rows = n_rows; aa.out_kc = kc_of(OP_RESID, d, qd);
     for (int b = 0; b < g.n_blocks; ++b) {
         bf16_t *kvb = (bf16_t *)(c->kv + (size_t)b * c->kv_block_bytes);
         if (!(mask && mask[2 * b])) {
@@ -506,18 +530,18 @@ static int32_t run_pass_bf16(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, b
             GemmOp r = base;
             r.type = OP_RESID; r.W = (const bf16_t *)c->wo[b]; r.N = d; r.K = qd; r.act_in = att; r.planes_in = planes_att;
             r.ss_in = nullptr; r.x = x; r.gain_next = next_gain(c, mask, 2 * b); r.act_out = act_d; r.planes_out = planes_d;
-            r.ss_out = ss; r.split = c->split_o;
+            r.ss_out = ss; r.split = c->split_o; r.out_kc = kc_next(2 * b);
             launch(r);
         }
         if (!(mask && mask[2 * b + 1])) {
             GemmOp o = base;
             o.type = OP_SWIGLU; o.W = (const bf16_t *)c->wgu[b]; o.N = F; o.K = d; o.act_in = act_d; o.planes_in = planes_d;
-            o.ss_in = ss; o.act_out = u; o.planes_out = planes_u; o.split = c->split_gu;
+            o.ss_in = ss; o.act_out = u; o.planes_out = planes_u; o.split = c->split_gu; o.out_kc = kc_of(OP_RESID, d, F);
             launch(o);
             GemmOp r = base;
             r.type = OP_RESID; r.W = (const bf16_t *)c->wdown[b]; r.N = d; r.K = F; r.act_in = u; r.planes_in = planes_u;
             r.ss_in = nullptr; r.x = x; r.gain_next = next_gain(c, mask, 2 * b + 1); r.act_out = act_d; r.planes_out = planes_d;
-            r.ss_out = ss; r.split = c->split_down;
+            r.ss_out = ss; r.split = c->split_down; r.out_kc = kc_next(2 * b + 1);
             launch(r);
         }
     }
@@ -665,8 +689,11 @@ static int32_t prefill_impl(knnssd_ctx *c, const int32_t *tokens, int32_t n, flo
         KS_TRY(rc_pass);
         if (last) {
             if (c->tuned_verify) {
+                // the last pass left the final norm's operands as the LM head's chunk images
+                int head_kc = 0, head_nc = 0;
+                mfma_chunking(KS_MAX_DYN_LDS, (c->cfg.vocab + KS_NWG - 1) / KS_NWG, rows, c->cfg.d_model, &head_kc, &head_nc);
                 hipLaunchKernelGGL(hidden_from_planes_kernel, dim3(8), dim3(NT), 0, c->stream, c->wsp<bf16_t>(c->L.planes_d),
-                                   c->wsp<float>(c->L.ss), KS_NWG, c->cfg.d_model, c->cfg.rms_eps, ver,
+                                   head_kc, rows, c->wsp<float>(c->L.ss), KS_NWG, c->cfg.d_model, c->cfg.rms_eps, ver,
                                    c->wsp<float>(c->L.hidden_last), last_hidden_dev);
                 HIP_TRY(hipGetLastError());
             } else {
