@@ -43,7 +43,7 @@ def traffic_parse(fetch_csv, write_csv):
         copy, gemm = None, []
         for r in rows:
             name = r["Kernel_Name"]
-            if "gemm_mfma_kernel<false>" in name:
+            if "gemm_mfma_kernel<false" in name:      # the verification launches (first template argument: not prefill)
                 gemm.append(float(r["Counter_Value"]))
             elif "MulFunctor" in name and not gemm:
                 copy = float(r["Counter_Value"])           # the last multiply before the passes is the calibration copy
@@ -60,7 +60,7 @@ def traffic_parse(fetch_csv, write_csv):
     for tag in ("read", "write"):
         o = out[tag]
         print(f"{tag}: copy of {COPY_BYTES} B counted as {o['copy_counter_KiB']:.0f} KiB -> scale {o['scale']:.4f}; "
-              f"gemm_mfma_kernel<false>: {o['launches']} launches, avg counter {o['gemm_avg_KiB']:.0f} KiB "
+              f"gemm_mfma_kernel<false, *>: {o['launches']} launches, avg counter {o['gemm_avg_KiB']:.0f} KiB "
               f"-> {o['bytes_per_launch']:.0f} B per launch")
     print(f"traffic_bytes_per_launch: {total:.0f}")
 
@@ -232,7 +232,7 @@ def main():
             r = gpu.knnssd_profile_pass(1, rows, prompt_len)
             acc = {k: acc[k] + r[k] for k in acc}
         gemm_gbs = acc["gemm_bytes"] / (acc["gemm_ns"] * 1e-9) / 1e9
-        roof = {"bound": "hbm", "kernel": "gemm_mfma_kernel<false> (verification GEMM: the 161 launches of one pass, "
+        roof = {"bound": "hbm", "kernel": "gemm_mfma_kernel<false, false> (verification GEMM: the 161 launches of one pass, "
                                           "back to back between two HIP events)",
                 "achieved": round(gemm_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(gemm_gbs / HBM_PEAK_GBS, 4),

@@ -647,6 +647,8 @@ __host__ __device__ inline void mfma_chunking(size_t lds_total, int max_rows, in
     *nc = (K + KC - 1) / KC;
 }
 
+// RING: the weight stream rolls on across the boundaries of the activation chunks (launches with many chunks)
+template <bool RING>
 __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl *ctl, int wg, int nwg, char *lds) {
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int K = op.K;
@@ -673,20 +675,23 @@ __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl
     // rows of cols_c + 8 elements, already in the byte order of the LDS stage. Staging is a straight copy, piece i
     // of the range to byte 16*i of the buffer.
     auto chunk_pieces = [&](int c) { return 3 * n_rows * ((min(KC, K - c * KC) >> 3) + 1); };
-    auto bchunk_load = [&](int c) {          // global -> registers (hand-placed loads)
+    // (t = the thread's index, passed in so that a caller inside the unit loop can hand over a copy the optimiser
+    // cannot see through: the piece offsets are then recomputed on the spot instead of living in registers)
+    auto bchunk_load = [&](int c, int t) {   // global -> registers (hand-placed loads)
         const bf16_t *src = op.planes_in + c * (3 * n_rows * (KC + 8));
         const int last = chunk_pieces(c) - 1;
 #pragma unroll
         for (int q = 0; q < MFMA_BQ; ++q)        // unconditional (clamped): the waits below count on exactly MFMA_BQ loads
-            breg[q] = stream_load_x4(src + min(tid + q * NT, last) * 8);
+            breg[q] = stream_load_x4(src + min(t + q * NT, last) * 8);
     };
-    auto bchunk_store = [&](int c) {         // registers -> LDS buffer c & 1
+    auto bchunk_store = [&](int c, int t) {  // registers -> LDS buffer c & 1
         char *dst = bbuf + (c & 1) * BBUF;
         const int last = chunk_pieces(c) - 1;
 #pragma unroll
         for (int q = 0; q < MFMA_BQ; ++q)        // clamped like the loads: a duplicate writes the same value to the same place
-            *reinterpret_cast<u32x4 *>(dst + min(tid + q * NT, last) * 16) = breg[q];
+            *reinterpret_cast<u32x4 *>(dst + min(t + q * NT, last) * 16) = breg[q];
     };
+
     // units of chunk c this wavefront owns (they are consecutive in its stream)
     auto chunk_count = [&](int c, bool have) {
         const int cs = min(KC, K - c * KC) >> 5, nfull = cs >> 4, rem = cs & 15;
@@ -698,7 +703,7 @@ __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl
     // the weights arrive. Every load of the main part is a hand-placed one (see stream_load) and unconditional
     // (addresses are clamped instead), so the number of loads in flight is known at every wait; the compiler's
     // own counting would charge the weight stream to the small loads and the other way round.
-    bchunk_load(0);
+    bchunk_load(0, tid);
     float sh[4];
     {
         const float *sp = op.ss_in ? op.ss_in : reinterpret_cast<const float *>(op.planes_in);
@@ -724,41 +729,162 @@ __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl
         // lane = (row of the tile, 8-column group); dead rows re-read the tile's last live row: their products land
         // in accumulator rows that are never stored
         const bf16_t *ap = op.W + w.base + (size_t)(kg * w.rows_t + min(r16, w.rows_t - 1)) * 8;
-        int cnt = chunk_count(0, w.have);
-        const bool stage = round == 0 || NC > 1;     // a single chunk stays in LDS for every round
-        // a batch: eight unconditional loads (a wavefront with fewer units re-reads its last one; one without units
-        // reads the matrix's first bytes). No load of an earlier batch is in flight when one is issued.
-        auto a_batch = [&](const bf16_t *p, int n) {
-            const bf16_t *p0 = n > 0 ? p : op.W;
-            const int last = max(n - 1, 0);
-#pragma unroll
-            for (int j = 0; j < DA; ++j) a[j] = stream_load(p0 + (size_t)min(j, last) * w.unit);
-        };
-        if (stage && round > 0) bchunk_load(0);
-        a_batch(ap, cnt);
-        if (round == 0) {
-            // the row table is read after the next meeting at the earliest; its index arithmetic is pinned behind
-            // the weight loads just issued (it is loop invariant and would otherwise be hoisted in front of them)
-            GemmOp shape;
-            shape.type = pinned_here(op.type); shape.N = pinned_here(op.N);
-            shape.H = pinned_here(op.H); shape.Hkv = pinned_here(op.Hkv); shape.hd = pinned_here(op.hd);
-            int n_first_unused;
-            build_row_table<true>(shape, pinned_here(wg), rowidx, &n_first_unused);
-        }
-        if (stage) {
-            stream_wait_pieces<DA, MFMA_BQ>(breg);
-            bchunk_store(0);
-            __syncthreads();
-        }
-        int c = 0;
-        do {                                     // NC >= 1
-            if (c + 1 < NC) bchunk_load(c + 1);
-            const int bstride = (min(KC, K - c * KC) + 8) * 2;                  // bytes per staged row of this chunk
-            const char *bsrc = bbuf + (c & 1) * BBUF + brow * bstride + kg * 16;
+        if constexpr (!RING) {
+            // few chunks: one loop nest per chunk, the weight stream drained at each boundary
+            int cnt = chunk_count(0, w.have);
+            const bool stage = round == 0 || NC > 1;     // a single chunk stays in LDS for every round
+            // a batch: eight unconditional loads (a wavefront with fewer units re-reads its last one; one without units
+            // reads the matrix's first bytes). No load of an earlier batch is in flight when one is issued.
+            auto a_batch = [&](const bf16_t *p, int n) {
+                const bf16_t *p0 = n > 0 ? p : op.W;
+                const int last = max(n - 1, 0);
+    #pragma unroll
+                for (int j = 0; j < DA; ++j) a[j] = stream_load(p0 + (size_t)min(j, last) * w.unit);
+            };
+            if (stage && round > 0) bchunk_load(0, tid);
+            a_batch(ap, cnt);
+            if (round == 0) {
+                // the row table is read after the next meeting at the earliest; its index arithmetic is pinned behind
+                // the weight loads just issued (it is loop invariant and would otherwise be hoisted in front of them)
+                GemmOp shape;
+                shape.type = pinned_here(op.type); shape.N = pinned_here(op.N);
+                shape.H = pinned_here(op.H); shape.Hkv = pinned_here(op.Hkv); shape.hd = pinned_here(op.hd);
+                int n_first_unused;
+                build_row_table<true>(shape, pinned_here(wg), rowidx, &n_first_unused);
+            }
+            if (stage) {
+                stream_wait_pieces<DA, MFMA_BQ>(breg);
+                bchunk_store(0, tid);
+                __syncthreads();
+            }
+            int c = 0;
+            do {                                     // NC >= 1
+                if (c + 1 < NC) bchunk_load(c + 1, tid);
+                const int bstride = (min(KC, K - c * KC) + 8) * 2;                  // bytes per staged row of this chunk
+                const char *bsrc = bbuf + (c & 1) * BBUF + brow * bstride + kg * 16;
+                auto unit_mfma = [&](int u, const u32x4 &a4) {
+                    const int ls = step_of_unit(s, kpart, u);     // step within the chunk
+                    const bf16x8 av = __builtin_bit_cast(bf16x8, a4);
+    #pragma unroll
+                    for (int p = 0; p < 3; ++p) {
+                        const u32x4 bv = *reinterpret_cast<const u32x4 *>(bsrc + p * n_rows * bstride + ls * 64);
+                        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bv), acc, 0, 0, 0);
+                    }
+                };
+                int u0 = 0;
+                // steady state: a unit's register is refilled the moment the unit has been used, and the wait before a
+                // unit leaves the seven younger weight loads in flight (loads of the next activation chunk, issued
+                // after the batch, only make that wait stricter). One way into the loop: see the draft GEMV.
+                if (cnt >= 2 * DA) {
+                    do {
+    #pragma unroll
+                        for (int j = 0; j < DA; ++j) {
+                            stream_wait<DA - 1>(a[j]);
+                            unit_mfma(u0 + j, a[j]);
+                            a[j] = stream_load(ap + (size_t)(u0 + j + DA) * w.unit);
+                        }
+                        u0 += DA;
+                    } while (u0 + 2 * DA <= cnt);
+                }
+                // tail: at most 15 units left, drained batch by batch; at least one drain, so that no load (of weights or
+                // of the next activation chunk) is in flight afterwards
+                do {
+                    stream_drain8(a);
+    #pragma unroll
+                    for (int j = 0; j < DA; ++j)
+                        if (u0 + j < cnt) unit_mfma(u0 + j, a[j]);
+    #pragma unroll
+                    for (int j = 0; j < DA; ++j)
+                        if (u0 + DA + j < cnt) a[j] = stream_load(ap + (size_t)(u0 + DA + j) * w.unit);
+                    u0 += DA;
+                } while (u0 < cnt);        // a load was issued above only if this holds: every load is followed by a drain
+                ap += (size_t)cnt * w.unit;
+                if (c + 1 >= NC) break;                // nothing in flight here
+                // next chunk's first weight loads go out before the workgroup meets
+                ++c;
+                cnt = chunk_count(c, w.have);
+                a_batch(ap, cnt);
+                stream_wait_pieces<DA, MFMA_BQ>(breg);     // long complete (drained above); orders the stores after it
+                bchunk_store(c, tid);
+                __syncthreads();
+            } while (true);
+            stream_drain8(a);      // nothing is in flight here (every way out of the loop passes a drain); costs nothing
+        } else {
+            // The wavefront's units of this round form ONE stream over all activation chunks: unit U belongs to chunk
+            // U / CU (CU units per full chunk), and the weight loads roll on across chunk boundaries. Only the arithmetic
+            // has to stop at a boundary until the next chunk is staged.
+            const int total = w.cnt;
+            const int CU = (KC >> 9) * s.g;
+            const bool stage = round == 0 || NC > 1;     // a single chunk stays in LDS for every round
+            // a batch: eight unconditional loads (a wavefront with fewer units re-reads its last one; one without units
+            // reads the matrix's first bytes). No load of an earlier batch is in flight when one is issued.
+            if (stage && round > 0) bchunk_load(0, tid);
+            {
+                const bf16_t *p0 = total > 0 ? ap : op.W;
+                const int last = max(total - 1, 0);
+    #pragma unroll
+                for (int j = 0; j < DA; ++j) a[j] = stream_load(p0 + (size_t)min(j, last) * w.unit);
+            }
+            if (round == 0) {
+                // the row table is read after the next meeting at the earliest; its index arithmetic is pinned behind
+                // the weight loads just issued (it is loop invariant and would otherwise be hoisted in front of them)
+                GemmOp shape;
+                shape.type = pinned_here(op.type); shape.N = pinned_here(op.N);
+                shape.H = pinned_here(op.H); shape.Hkv = pinned_here(op.Hkv); shape.hd = pinned_here(op.hd);
+                int n_first_unused;
+                build_row_table<true>(shape, pinned_here(wg), rowidx, &n_first_unused);
+            }
+            if (stage) {
+                stream_wait_pieces<DA, MFMA_BQ>(breg);
+                bchunk_store(0, tid);
+                __syncthreads();
+            }
+            // state of the chunk being consumed
+            int c = 0;                                   // its index
+            int bnd = NC > 1 ? CU : 0x7fffffff;          // first unit of the next chunk
+            int young = 0;                               // weight loads issued since the next chunk's pieces were requested
+            int ls0 = 0;                                 // 32-column steps in front of the chunk
+            int bstride = (min(KC, K) + 8) * 2;          // bytes per staged row of the chunk
+            const char *bsrc = bbuf + brow * bstride + kg * 16;
+            if (NC > 1) bchunk_load(1, tid);
+            // A boundary: the next chunk's pieces (requested one chunk ago) go to LDS, the workgroup meets, the chunk
+            // after that is requested. DRAINED = false: the weight stream stays in flight, so the wait for the pieces
+            // leaves as many loads in flight as were issued after them (at most eight are ever outstanding).
+            auto boundary = [&](auto drained) {
+                // (the waits that depend on the count name no register: a wait that names the pieces in several
+                // alternative branches would make the compiler join the alternatives with register copies, placed
+                // in front of the wait; the one wait that names them comes last and is satisfied by then)
+                if constexpr (decltype(drained)::value) {
+                    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                } else {
+                    switch (min(young, DA)) {
+                        case 0: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
+                        case 1: asm volatile("s_waitcnt vmcnt(1)" ::: "memory"); break;
+                        case 2: asm volatile("s_waitcnt vmcnt(2)" ::: "memory"); break;
+                        case 3: asm volatile("s_waitcnt vmcnt(3)" ::: "memory"); break;
+                        case 4: asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); break;
+                        case 5: asm volatile("s_waitcnt vmcnt(5)" ::: "memory"); break;
+                        case 6: asm volatile("s_waitcnt vmcnt(6)" ::: "memory"); break;
+                        case 7: asm volatile("s_waitcnt vmcnt(7)" ::: "memory"); break;
+                        default: break;
+                    }
+                }
+                stream_wait_pieces<DA, MFMA_BQ>(breg);
+                int t = tid;
+                asm volatile("" : "+v"(t));
+                ++c;
+                bchunk_store(c, t);
+                __syncthreads();
+                if (c + 1 < NC) { bchunk_load(c + 1, t); young = 0; bnd += CU; }
+                else bnd = 0x7fffffff;
+                ls0 = c * (KC >> 5);
+                bstride = (min(KC, K - c * KC) + 8) * 2;
+                bsrc = bbuf + (c & 1) * BBUF + brow * bstride + kg * 16;
+            };
             auto unit_mfma = [&](int u, const u32x4 &a4) {
-                const int ls = step_of_unit(s, kpart, u);     // step within the chunk
+                const int ls = step_of_unit(s, kpart, u) - ls0;     // step within the chunk
                 const bf16x8 av = __builtin_bit_cast(bf16x8, a4);
-#pragma unroll
+    #pragma unroll
                 for (int p = 0; p < 3; ++p) {
                     const u32x4 bv = *reinterpret_cast<const u32x4 *>(bsrc + p * n_rows * bstride + ls * 64);
                     acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bv), acc, 0, 0, 0);
@@ -766,42 +892,44 @@ __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl
             };
             int u0 = 0;
             // steady state: a unit's register is refilled the moment the unit has been used, and the wait before a
-            // unit leaves the seven younger weight loads in flight (loads of the next activation chunk, issued
-            // after the batch, only make that wait stricter). One way into the loop: see the draft GEMV.
-            if (cnt >= 2 * DA) {
+            // unit leaves the seven younger weight loads in flight (loads of activation pieces, issued in between,
+            // only make that wait stricter). One way into the loop: see the draft GEMV.
+            if (total >= 2 * DA) {
                 do {
-#pragma unroll
+    #pragma unroll
                     for (int j = 0; j < DA; ++j) {
+                        if (u0 + j == bnd) boundary(std::false_type{});
                         stream_wait<DA - 1>(a[j]);
                         unit_mfma(u0 + j, a[j]);
                         a[j] = stream_load(ap + (size_t)(u0 + j + DA) * w.unit);
+                        ++young;
                     }
                     u0 += DA;
-                } while (u0 + 2 * DA <= cnt);
+                } while (u0 + 2 * DA <= total);
             }
-            // tail: at most 15 units left, drained batch by batch; at least one drain, so that no load (of weights or
-            // of the next activation chunk) is in flight afterwards
+            // tail: at most 15 units left, drained batch by batch; at least one drain, so that no load is in flight
+            // afterwards
             do {
                 stream_drain8(a);
-#pragma unroll
+    #pragma unroll
                 for (int j = 0; j < DA; ++j)
-                    if (u0 + j < cnt) unit_mfma(u0 + j, a[j]);
-#pragma unroll
+                    if (u0 + j < total) {
+                        if (u0 + j == bnd) boundary(std::true_type{});
+                        unit_mfma(u0 + j, a[j]);
+                    }
+    #pragma unroll
                 for (int j = 0; j < DA; ++j)
-                    if (u0 + DA + j < cnt) a[j] = stream_load(ap + (size_t)(u0 + DA + j) * w.unit);
+                    if (u0 + DA + j < total) a[j] = stream_load(ap + (size_t)(u0 + DA + j) * w.unit);
                 u0 += DA;
-            } while (u0 < cnt);        // a load was issued above only if this holds: every load is followed by a drain
-            ap += (size_t)cnt * w.unit;
-            if (c + 1 >= NC) break;                // nothing in flight here
-            // next chunk's first weight loads go out before the workgroup meets
-            ++c;
-            cnt = chunk_count(c, w.have);
-            a_batch(ap, cnt);
-            stream_wait_pieces<DA, MFMA_BQ>(breg);     // long complete (drained above); orders the stores after it
-            bchunk_store(c);
-            __syncthreads();
-        } while (true);
-        stream_drain8(a);      // nothing is in flight here (every way out of the loop passes a drain); costs nothing
+            } while (u0 < total);          // a load was issued above only if this holds: every load is followed by a drain
+            // boundaries this wavefront's stream did not reach (it ended earlier, or the wavefront owns no unit): every
+            // wavefront stages its pieces of every chunk and meets the others
+            while (c + 1 < NC) {
+                stream_drain8(a);
+                boundary(std::true_type{});
+            }
+            stream_drain8(a);      // nothing is in flight here (every way out of the loops passes a drain); costs nothing
+        }
         // partial tile of this wavefront -> LDS; lane holds D[row 4*kg + q][token r16]. The partials of
         // consecutive rounds alternate between two buffers, so one meeting per round is enough: a buffer is
         // written again only after every wavefront has passed the next round's meeting, i.e. finished summing it.
@@ -840,10 +968,10 @@ __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl
 }
 
 // PREFILL only names the launch site (prompt chunks vs verification passes) so that a profile keeps the two apart
-template <bool PREFILL>
+template <bool PREFILL, bool RING>
 __global__ __launch_bounds__(NT, 1) void gemm_mfma_kernel(GemmOp op, const PassCtl *ctl) {
     extern __shared__ __align__(16) char lds[];
-    gemm_mfma_device(op, ctl, blockIdx.x, gridDim.x, lds);
+    gemm_mfma_device<RING>(op, ctl, blockIdx.x, gridDim.x, lds);
 }
 
 // final-RMSNorm hidden state of one row from the head's operands: gain (.) x (three planes) times rstd

@@ -235,9 +235,13 @@ extern "C" int32_t knnssd_create(const knnssd_model_cfg *cfg, const knnssd_weigh
     if (c->tuned) {
         hipError_t ea = hipFuncSetAttribute((const void *)gemv_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, KS_MAX_DYN_LDS);
         if (ea == hipSuccess)
-            ea = hipFuncSetAttribute((const void *)gemm_mfma_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, KS_MAX_DYN_LDS);
+            ea = hipFuncSetAttribute((const void *)gemm_mfma_kernel<false, false>, hipFuncAttributeMaxDynamicSharedMemorySize, KS_MAX_DYN_LDS);
         if (ea == hipSuccess)
-            ea = hipFuncSetAttribute((const void *)gemm_mfma_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, KS_MAX_DYN_LDS);
+            ea = hipFuncSetAttribute((const void *)gemm_mfma_kernel<false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, KS_MAX_DYN_LDS);
+        if (ea == hipSuccess)
+            ea = hipFuncSetAttribute((const void *)gemm_mfma_kernel<true, false>, hipFuncAttributeMaxDynamicSharedMemorySize, KS_MAX_DYN_LDS);
+        if (ea == hipSuccess)
+            ea = hipFuncSetAttribute((const void *)gemm_mfma_kernel<true, true>, hipFuncAttributeMaxDynamicSharedMemorySize, KS_MAX_DYN_LDS);
         if (ea == hipSuccess)
             ea = hipFuncSetAttribute((const void *)prefill_gemm_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pf_gemm_lds_bytes(4));
         if (ea == hipSuccess)
@@ -488,8 +492,16 @@ static int32_t run_pass_bf16(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, b
             v.lds_bytes = (int)KS_MAX_DYN_LDS;
             v.n_rows = n_rows;
             mfma_chunking(KS_MAX_DYN_LDS, v.max_rows, n_rows, v.K, &v.kc, &v.nc);
-            if (c->in_prefill) hipLaunchKernelGGL(gemm_mfma_kernel<true>, dim3(KS_NWG), dim3(NT), KS_MAX_DYN_LDS, s, v, ctl);
-            else hipLaunchKernelGGL(gemm_mfma_kernel<false>, dim3(KS_NWG), dim3(NT), KS_MAX_DYN_LDS, s, v, ctl);
+            // many activation chunks (many token rows, long K): the variant whose weight stream rolls on across the
+            // chunk boundaries; few chunks: the leaner per-chunk loops
+            const bool ring = v.nc >= 4;
+            if (c->in_prefill) {
+                if (ring) hipLaunchKernelGGL((gemm_mfma_kernel<true, true>), dim3(KS_NWG), dim3(NT), KS_MAX_DYN_LDS, s, v, ctl);
+                else hipLaunchKernelGGL((gemm_mfma_kernel<true, false>), dim3(KS_NWG), dim3(NT), KS_MAX_DYN_LDS, s, v, ctl);
+            } else {
+                if (ring) hipLaunchKernelGGL((gemm_mfma_kernel<false, true>), dim3(KS_NWG), dim3(NT), KS_MAX_DYN_LDS, s, v, ctl);
+                else hipLaunchKernelGGL((gemm_mfma_kernel<false, false>), dim3(KS_NWG), dim3(NT), KS_MAX_DYN_LDS, s, v, ctl);
+            }
         }
         if (c->gemm_only) {    // measurement aid: count what this launch streams
             c->prof_launches += 1;
