@@ -1036,6 +1036,7 @@ struct AttnArgs {
     const bf16_t *kv_block;  // [2][Hkv][max_seq][hd]
     float *partial;          // [KS_MAX_ROWS*H][max_chunks][hd + 2]
     int H, Hkv, hd, max_seq, max_chunks;
+    int group;               // H / Hkv
     // combine
     float *act_out;          // fp32 [KS_MAX_ROWS][H*hd]
     bf16_t *planes_out;      // three planes as the O projection's chunk images (plane_image_offset)
@@ -1050,7 +1051,8 @@ __device__ __forceinline__ void attn_partial_device(const AttnArgs &a, const Pas
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int ps = lane / LPP, dg = lane % LPP;
     const int n_rows = min(ctl->n_rows, KS_MAX_ROWS), start = ctl->start;
-    const int group = a.H / a.Hkv;
+    const int group = a.group;                          // H / Hkv, from the host
+    const float inv_group = __builtin_amdgcn_rcpf((float)group);
     const int P = n_rows * group;                       // (row, head-in-group) pairs per kv head
     const int n_pg = (P + ATT_PG - 1) / ATT_PG;
     const int n_chunks = (start + n_rows + ATT_CHUNK - 1) / ATT_CHUNK;
@@ -1061,9 +1063,12 @@ __device__ __forceinline__ void attn_partial_device(const AttnArgs &a, const Pas
     const size_t kv_head_stride = (size_t)a.max_seq * HD;
 
     for (int item = wg; item < n_items; item += nwg) {
-        const int pg = item % n_pg;
-        const int chunk = (item / n_pg) % n_chunks;
-        const int kvh = item / (n_pg * n_chunks);
+        // item -> (kv head, chunk, pair group), pair group fastest (float-product divisions, see div_small)
+        const int per_head = n_pg * n_chunks;
+        const int kvh = div_small(item, per_head, __builtin_amdgcn_rcpf((float)per_head));
+        const int in_head = item - kvh * per_head;
+        const int chunk = div_small(in_head, n_pg, __builtin_amdgcn_rcpf((float)n_pg));
+        const int pg = in_head - chunk * n_pg;
         const int p_base = pg * ATT_PG;
         const int n_p = min(ATT_PG, P - p_base);
         __syncthreads();   // previous item's LDS reads are done
@@ -1082,13 +1087,13 @@ __device__ __forceinline__ void attn_partial_device(const AttnArgs &a, const Pas
         }
         for (int i = tid; i < n_p * HD; i += NT) {
             const int pl = i / HD, dim = i - pl * HD, p = p_base + pl;
-            const int m = p / group, h = kvh * group + (p - m * group);
+            const int m = div_small(p, group, inv_group), h = kvh * group + (p - m * group);
             qs[pl * HD + dim] = a.q[(size_t)m * a.H * HD + h * HD + dim];
         }
         __syncthreads();
         for (int pl = 0; pl < n_p; ++pl) {
             const int p = p_base + pl;
-            const int m = p / group;
+            const int m = div_small(p, group, inv_group);
             const int len = start + m + 1;          // row m attends positions [0, len)
             const float *qp = qs + pl * HD + dg * 8;
             const float4 q0 = *reinterpret_cast<const float4 *>(qp), q1 = *reinterpret_cast<const float4 *>(qp + 4);
@@ -1137,7 +1142,7 @@ __device__ __forceinline__ void attn_partial_device(const AttnArgs &a, const Pas
         // merge the wavefronts' partials: thread (pl, dim)
         for (int i = tid; i < n_p * HD; i += NT) {
             const int pl = i / HD, dim = i - pl * HD, p = p_base + pl;
-            const int m = p / group, h = kvh * group + (p - m * group);
+            const int m = div_small(p, group, inv_group), h = kvh * group + (p - m * group);
             float M = -INFINITY;
 #pragma unroll
             for (int w = 0; w < NWV; ++w) M = fmaxf(M, red[((size_t)w * ATT_PG + pl) * (HD + 2) + HD]);
@@ -1175,18 +1180,39 @@ __device__ __forceinline__ void attn_combine_device(const AttnArgs &a, const Pas
     GemmOp st{};   // only the fields store_act uses
     st.act_out = a.act_out; st.planes_out = a.planes_out; st.out_kc = a.out_kc; st.n_rows = a.n_rows;
     const float inv_kc = PLANES ? __builtin_amdgcn_rcpf((float)a.out_kc) : 0.f;
+    const float inv_qd = __builtin_amdgcn_rcpf((float)qd);
+    const int hd_shift = 31 - __builtin_clz(hd);                           // head_dim is 64 or 128
+    constexpr int CB = 8;                                                  // chunks whose partials are fetched together
     for (int i = wg * NT + threadIdx.x; i < total; i += nwg * NT) {
-        const int m = i / qd, c = i - m * qd, h = c / hd, dim = c - h * hd;
+        const int m = div_small(i, qd, inv_qd), c = i - m * qd, h = c >> hd_shift, dim = c & (hd - 1);
         const int n_chunks = (start + m + 1 + ATT_CHUNK - 1) / ATT_CHUNK;   // chunks row m can see
         const float *pp = a.partial + ((size_t)m * a.H + h) * a.max_chunks * (hd + 2);
+        // Two passes in chunk order (largest maximum, then the weighted sums), each fetching the partials of CB chunks
+        // with unconditional loads before using any of them: a load per loop iteration would cost one memory round
+        // trip per chunk. Entries past the last chunk re-read it and enter the sums with weight zero, which leaves
+        // the sums bit for bit as if they had been skipped.
         float M = -INFINITY;
-        for (int ch = 0; ch < n_chunks; ++ch) M = fmaxf(M, pp[(size_t)ch * (hd + 2) + hd]);
+        for (int base = 0; base < n_chunks; base += CB) {
+            float mv[CB];
+#pragma unroll
+            for (int k = 0; k < CB; ++k) mv[k] = pp[(size_t)min(base + k, n_chunks - 1) * (hd + 2) + hd];
+#pragma unroll
+            for (int k = 0; k < CB; ++k) M = fmaxf(M, mv[k]);
+        }
         float L = 0.f, O = 0.f;
-        for (int ch = 0; ch < n_chunks; ++ch) {
-            const float *cp = pp + (size_t)ch * (hd + 2);
-            const float f = (cp[hd] > -INFINITY) ? expf(cp[hd] - M) : 0.f;
-            L = fmaf(cp[hd + 1], f, L);
-            O = fmaf(cp[dim], f, O);
+        for (int base = 0; base < n_chunks; base += CB) {
+            float mv[CB], lv[CB], ov[CB];
+#pragma unroll
+            for (int k = 0; k < CB; ++k) {
+                const float *cp = pp + (size_t)min(base + k, n_chunks - 1) * (hd + 2);
+                mv[k] = cp[hd]; lv[k] = cp[hd + 1]; ov[k] = cp[dim];
+            }
+#pragma unroll
+            for (int k = 0; k < CB; ++k) {
+                const float f = (base + k < n_chunks && mv[k] > -INFINITY) ? expf(mv[k] - M) : 0.f;
+                L = fmaf(lv[k], f, L);
+                O = fmaf(ov[k], f, O);
+            }
         }
         store_act<PLANES>(st, m, c, qd, O / L, inv_kc);
     }

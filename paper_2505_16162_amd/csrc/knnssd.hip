@@ -522,7 +522,7 @@ static int32_t run_pass_bf16(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, b
     else hipLaunchKernelGGL((embed_producer_kernel<true>), dim3(KS_NWG), dim3(NT), 0, s, e, ctl);
 
     AttnArgs aa{};
-    aa.q = qrot; aa.partial = c->wsp<float>(c->L.attn_part); aa.H = H; aa.Hkv = Hkv; aa.hd = hd; aa.max_seq = g.max_seq;
+    aa.q = qrot; aa.partial = c->wsp<float>(c->L.attn_part); aa.H = H; aa.Hkv = Hkv; aa.hd = hd; aa.max_seq = g.max_seq; aa.group = H / Hkv;
     aa.max_chunks = (g.max_seq + ATT_CHUNK - 1) / ATT_CHUNK; aa.act_out = att; aa.planes_out = planes_att;
     aa.n_rows = n_rows; aa.out_kc = kc_of(OP_RESID, d, qd);
     for (int b = 0; b < g.n_blocks; ++b) {
