@@ -111,3 +111,38 @@ def test_round_loop_edges():
     with pytest.raises(binding.KnnSsdError):
         gpu.knnssd_generate(prompt, 21, 4, 0.0)
     gpu.close()
+
+
+@pytest.mark.timeout(600)
+def test_many_rows_long_k_many_activation_chunks():
+    """Verification of 16, 11 and 6 rows on a shape whose reduction lengths (2048 and 3072 columns) make the
+    matrix-core GEMM stage its token rows in four to six chunks: the launches take the variant whose weight
+    stream runs on across chunk boundaries. Its logits must equal, bit for bit, those of the same rows verified
+    alone (one chunk, the other variant), and match the oracle."""
+    shape = synth.small_shape("long_k", n_blocks=2, d_model=2048, n_heads=16, n_kv_heads=16, head_dim=128,
+                              d_ffn=3072, vocab=2500, max_seq=80)
+    w, orc, gpu = make_pair(shape, seed=17, std=0.02)
+    prompt = synth.make_prompt(shape.vocab, 21, seed=3).tolist()
+    first_o, _, _ = O.prefill(orc, prompt)
+    first_g, _ = gpu.knnssd_prefill(prompt)
+    assert first_g == first_o
+    rows_in = [first_o] + synth.make_prompt(shape.vocab, 15, seed=8).tolist()
+    rows_o = orc.forward(rows_in, len(prompt), None)
+    kept = {}
+    for n in (16, 11, 6):
+        print("rows", n, flush=True)
+        gpu.knnssd_prefill(prompt)
+        gpu.knnssd_verify(rows_in[:n], len(prompt))
+        for r in range(n):
+            got = gpu.knnssd_get_logits(r).clone()
+            ok, err = logits_close(got.numpy(), rows_o[r], shape)
+            assert ok, (n, r, err)
+            if r in kept:
+                assert torch.equal(got, kept[r]), (n, r)     # independent of how many rows share the pass
+            kept[r] = got
+    # the same rows one at a time: a single chunk per launch, i.e. the other kernel variant
+    gpu.knnssd_prefill(prompt)
+    for r in range(3):
+        gpu.knnssd_verify(rows_in[r:r + 1], len(prompt) + r)
+        assert torch.equal(gpu.knnssd_get_logits(0), kept[r]), r
+    gpu.close()
