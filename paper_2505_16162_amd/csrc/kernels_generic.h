@@ -276,7 +276,7 @@ __global__ __launch_bounds__(256) void attention_kernel(const PassCtl *ctl, cons
         for (int t = part; t < len; t += nparts) acc = fmaf(scores[t], load_as_float(vc, (size_t)t * hd + i), acc);
     if (part < 4) outp[part][i] = acc;
     __syncthreads();
-    if (threadIdx.x < hd) {
+    if ((int)threadIdx.x < hd) {
         float s = 0.f;
         for (int p = 0; p < nparts; ++p) s += outp[p][threadIdx.x];
         att[(size_t)r * (H * hd) + h * hd + threadIdx.x] = s / den;

@@ -287,7 +287,7 @@ extern "C" int32_t knnssd_create(const knnssd_model_cfg *cfg, const knnssd_weigh
     e = hipHostGetDevicePointer((void **)&c->d_flags, c->h_stage + 512, 0);
     if (e != hipSuccess) {
         snprintf(g_hip_err, sizeof(g_hip_err), "%s (hipHostGetDevicePointer)", hipGetErrorString(e));
-        hipHostFree(c->h_stage);
+        (void)hipHostFree(c->h_stage);
         delete c;
         return KNNSSD_EHIP;
     }
@@ -299,7 +299,7 @@ extern "C" int32_t knnssd_create(const knnssd_model_cfg *cfg, const knnssd_weigh
     if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
     if (e != hipSuccess) {
         snprintf(g_hip_err, sizeof(g_hip_err), "%s (rope table)", hipGetErrorString(e));
-        hipHostFree(c->h_stage);
+        (void)hipHostFree(c->h_stage);
         delete c;
         return KNNSSD_EHIP;
     }
@@ -336,9 +336,9 @@ extern "C" int32_t knnssd_pack_matrix(const knnssd_model_cfg *cfg, int32_t which
 
 extern "C" int32_t knnssd_destroy(knnssd_ctx *ctx) {
     if (!ctx) return KNNSSD_EINVAL;
-    hipStreamSynchronize(ctx->stream);
-    for (hipEvent_t ev : ctx->events) hipEventDestroy(ev);
-    if (ctx->h_stage) hipHostFree(ctx->h_stage);
+    (void)hipStreamSynchronize(ctx->stream);
+    for (hipEvent_t ev : ctx->events) (void)hipEventDestroy(ev);
+    if (ctx->h_stage) (void)hipHostFree(ctx->h_stage);
     delete ctx;
     return KNNSSD_OK;
 }
