@@ -1009,7 +1009,7 @@ __global__ __launch_bounds__(NT) void embed_producer_kernel(GemmOp op, const Pas
     // the plane layout is the one the host computed for op.n_rows rows: never more rows than that
     const int n_rows = min(min(ctl->n_rows, KS_MAX_ROWS), PLANES ? op.n_rows : KS_MAX_ROWS);
     const float inv_kc = PLANES ? __builtin_amdgcn_rcpf((float)op.out_kc) : 0.f;
-    const int wg = blockIdx.x, nwg = gridDim.x;
+    const int wg = blockIdx.x;         // launched with KS_NWG workgroups (wg_share)
     const int r0 = wg_share(op.N, wg), r1 = wg_share(op.N, wg + 1);
     for (int m = 0; m < n_rows; ++m) {
         const bf16_t *row = op.embed + (size_t)ctl->tok[m] * op.N;
