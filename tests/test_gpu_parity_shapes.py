@@ -146,3 +146,36 @@ def test_many_rows_long_k_many_activation_chunks():
         gpu.knnssd_verify(rows_in[r:r + 1], len(prompt) + r)
         assert torch.equal(gpu.knnssd_get_logits(0), kept[r]), r
     gpu.close()
+
+
+def test_fewer_rows_than_workgroups():
+    """d_model = 128: the output projections have 128 rows for 256 workgroups, so every other workgroup owns no row
+    of them (it still stages its share of the activations and meets the others); QKV and gate/up shares of 0-2 rows.
+    Draft steps, 1-, 5- and 16-row verification, a generation."""
+    shape = synth.small_shape("narrow", n_blocks=2, d_model=128, n_heads=2, n_kv_heads=2, head_dim=64, d_ffn=352,
+                              vocab=700, max_seq=96)
+    w, orc, gpu = make_pair(shape, seed=29, std=0.06)
+    assert gpu.packed                                   # the tuned kernels, not the any-shape fallback
+    prompt = synth.make_prompt(shape.vocab, 19, seed=12).tolist()
+    mask = np.array([0, 1, 0, 0], dtype=np.uint8)
+    toks_o, st_o, rounds = O.ssd_generate(orc, prompt, mask, 24, 6, 0.0)
+    gpu.knnssd_set_skipset(mask.tolist())
+    toks_g, st_g = gpu.knnssd_generate(prompt, 24, 6, 0.0)
+    assert toks_g == toks_o, [min(r.margins) for r in rounds if r.margins]
+    assert (st_g["rounds"], st_g["drafted"], st_g["accepted"]) == (st_o.rounds, st_o.drafted, st_o.accepted)
+    orc2 = O.OracleModel(shape, w)
+    first_o, _, _ = O.prefill(orc2, prompt)
+    first_g, _ = gpu.knnssd_prefill(prompt)
+    assert first_g == first_o
+    gpu.knnssd_draft_step(first_o, len(prompt))
+    row = orc2.forward([first_o], len(prompt), mask)[0]
+    ok, err = logits_close(gpu.knnssd_get_logits(0).numpy(), row, shape)
+    assert ok, err
+    rows_in = [first_o] + synth.make_prompt(shape.vocab, 15, seed=5).tolist()
+    rows_o = orc2.forward(rows_in, len(prompt), None)
+    for n in (1, 5, 16):
+        gpu.knnssd_verify(rows_in[:n], len(prompt))
+        for r in range(n):
+            ok, err = logits_close(gpu.knnssd_get_logits(r).numpy(), rows_o[r], shape)
+            assert ok, (n, r, err)
+    gpu.close()
