@@ -38,15 +38,15 @@ struct GemmOp {
     int N, K;
     const float *act_in;      // draft: fp32 [K], the next norm's gain already applied
     const bf16_t *planes_in;  // verify: bf16 split of the same values (three planes), stored as this GEMM's chunk images
-    const float *ss_in;       // [n_ss][KS_MAX_ROWS] shares of sum(x^2); nullptr: input is not normalised
-    int n_ss;
+    const float *ss_in;       // [KS_MAX_ROWS][KS_NWG] the workgroups' shares of sum(x^2) per token row; nullptr: input is not normalised
+    int n_ss;                 // = KS_NWG (the tuned kernels rely on it)
     float inv_dim, eps;
     // OP_RESID / OP_EMBED: residual stream and the operands of the next norm
     float *x;                 // [KS_MAX_ROWS][N]
     const float *gain_next;   // [N]
     float *act_out;           // fp32 [KS_MAX_ROWS][N]  (also OP_SWIGLU's output)
     bf16_t *planes_out;       // three planes as the chunk images of the GEMM that reads them (plane_image_offset)
-    float *ss_out;            // [gridDim][KS_MAX_ROWS]
+    float *ss_out;            // [KS_MAX_ROWS][KS_NWG] (a row's shares are contiguous: its reader fetches them with four loads)
     // OP_QKV
     float *q_out;             // [KS_MAX_ROWS][H*hd], rotated
     bf16_t *kv_block;         // this block's cache: [2][Hkv][max_seq][hd]
@@ -60,6 +60,7 @@ struct GemmOp {
     // verification GEMM: LDS plan (dynamic LDS bytes of the launch, most rows any workgroup owns of this matrix)
     int lds_bytes, max_rows;
     int kc, nc;               // activation chunk length in columns and chunk count (mfma_chunking, set by the host)
+    int bbuf_bytes, fixed_lds, red_bufs;   // the rest of that kernel's LDS plan (mfma_bbuf_bytes, mfma_fixed_lds, mfma_red_bufs)
     int out_kc;               // chunk length of the GEMM that reads planes_out (the same call for its shape and row count)
     int n_rows;               // token rows of the pass as the host counts them (the same number the control block holds)
     // [KS_NWG] this matrix shape's workgroup splits, tabulated once (split_table_kernel): a kernel reads its entry
@@ -270,7 +271,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmOp &op, const PassCtl *c
             float sacc = 0.f;
             for (int t = lane; t < R; t += 64) sacc += vals[t * ld + m];
             sacc = wave_sum(sacc);
-            if (lane == 0) op.ss_out[(size_t)wg * KS_MAX_ROWS + m] = sacc;
+            if (lane == 0) op.ss_out[(size_t)m * KS_NWG + wg] = sacc;
         }
     } else if (op.type == OP_SWIGLU) {
         const float inv_rows = __builtin_amdgcn_rcpf((float)n_rows);
@@ -370,6 +371,8 @@ struct alignas(64) WgSplit {
     size_t wg_base;       // element offset of the workgroup's region in the packed matrix
 };
 static_assert(sizeof(WgSplit) == 64, "one 64-byte scalar load per workgroup");
+static_assert(KS_NWG * sizeof(WgSplit) >= (size_t)KS_NWG * KS_MAX_ROWS * sizeof(float),
+              "a split table doubles as a dummy share array (a GEMM without a norm in front reads it and drops the result)");
 
 template <bool FILL = true>
 __device__ __forceinline__ WgSplit make_split(const GemmOp &op, int wg, int nwg, int *rowidx) {
@@ -485,9 +488,11 @@ __device__ __forceinline__ void gemv_device(const GemmOp &op, const PassCtl *ctl
     for (int q = 0; q < XQ; ++q) xr[q] = stream_load_x4(op.act_in + min((tid + q * NT) * 4, K - 4));
     float sh[4];
     {
-        const float *sp = op.ss_in ? op.ss_in : op.act_in;
+        // KS_NWG = 4 x 64 shares per token row; without a norm in front of this GEMM the loads read the split table
+        // instead (as large as the share array) and their result is dropped
+        const float *sp = op.ss_in ? op.ss_in : reinterpret_cast<const float *>(op.split);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) sh[j] = stream_load_f32(sp + (op.ss_in ? (size_t)min(lane + 64 * j, op.n_ss - 1) * KS_MAX_ROWS : 0));
+        for (int j = 0; j < 4; ++j) sh[j] = stream_load_f32(sp + lane + 64 * j);
     }
     float xpre, gpre;
     {
@@ -575,9 +580,7 @@ __device__ __forceinline__ void gemv_device(const GemmOp &op, const PassCtl *ctl
     if (wave == 0) {
         float share = 0.f;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) share += (lane + 64 * j < op.n_ss) ? sh[j] : 0.f;
-        if (op.ss_in)
-            for (int i = lane + 256; i < op.n_ss; i += 64) share += op.ss_in[(size_t)i * KS_MAX_ROWS];
+        for (int j = 0; j < 4; ++j) share += sh[j];
         const float r = op.ss_in ? 1.0f / sqrtf(wave_sum(share) * op.inv_dim + op.eps) : 1.0f;
         if (lane == 0) rstd_s[0] = r;
     }
@@ -654,12 +657,12 @@ __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl
     const int K = op.K;
     float *vals = reinterpret_cast<float *>(lds);                       // [max_rows][16]
     float *red = vals + (size_t)op.max_rows * KS_MAX_ROWS;              // [1 or 2][NWV][256]
-    const int RB = mfma_red_bufs(op.lds_bytes, op.max_rows);
+    const int RB = op.red_bufs;
     int *rowidx = reinterpret_cast<int *>(red + RB * NWV * 256);
     float *scratch = reinterpret_cast<float *>(rowidx + op.max_rows);
     float *rstd_s = scratch + 4 * NWV;
-    const int BBUF = mfma_bbuf_bytes(op.lds_bytes, op.max_rows);
-    char *bbuf = lds + mfma_fixed_lds(op.lds_bytes, op.max_rows);       // [2][BBUF] activation chunks
+    const int BBUF = op.bbuf_bytes;
+    char *bbuf = lds + op.fixed_lds;                                    // [2][BBUF] activation chunks
     const int n_rows = op.n_rows;                                       // the host's count; equals ctl->n_rows
 
     const int active = ctl->active;     // both through the scalar cache, which only works before the first hand-placed load
@@ -706,10 +709,11 @@ __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl
     bchunk_load(0, tid);
     float sh[4];
     {
-        const float *sp = op.ss_in ? op.ss_in : reinterpret_cast<const float *>(op.planes_in);
+        // KS_NWG = 4 x 64 shares per token row, wavefront m sums row m's; without a norm in front of this GEMM the
+        // loads read the split table instead (as large as the share array) and their result is dropped
+        const float *sp = (op.ss_in ? op.ss_in : reinterpret_cast<const float *>(op.split)) + min(wave, n_rows - 1) * KS_NWG;
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            sh[j] = stream_load_f32(sp + (op.ss_in ? (size_t)min(lane + 64 * j, op.n_ss - 1) * KS_MAX_ROWS + min(wave, n_rows - 1) : 0));
+        for (int j = 0; j < 4; ++j) sh[j] = stream_load_f32(sp + lane + 64 * j);
     }
     float xpre, gpre;
     {
@@ -956,9 +960,7 @@ __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl
     if (wave < KS_MAX_ROWS) {
         float share = 0.f;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) share += (lane + 64 * j < op.n_ss) ? sh[j] : 0.f;
-        if (op.ss_in && wave < n_rows)
-            for (int i = lane + 256; i < op.n_ss; i += 64) share += op.ss_in[(size_t)i * KS_MAX_ROWS + wave];
+        for (int j = 0; j < 4; ++j) share += sh[j];
         const float r = (op.ss_in && wave < n_rows) ? 1.0f / sqrtf(wave_sum(share) * op.inv_dim + op.eps) : 1.0f;
         if (lane == 0) rstd_s[wave] = r;
     }
@@ -983,7 +985,7 @@ __global__ __launch_bounds__(NT) void hidden_from_planes_kernel(const bf16_t *pl
     const int m = min(ctl->n_rows, n_rows) - 1;
     if (threadIdx.x < 64) {
         float s = 0.f;
-        for (int i = threadIdx.x; i < n_ss; i += 64) s += ss[(size_t)i * KS_MAX_ROWS + m];
+        for (int i = threadIdx.x; i < n_ss; i += 64) s += ss[(size_t)m * n_ss + i];
         s = wave_sum(s);
         if (threadIdx.x == 0) rs = 1.0f / sqrtf(s / (float)d + eps);
     }
@@ -1021,7 +1023,7 @@ __global__ __launch_bounds__(NT) void embed_producer_kernel(GemmOp op, const Pas
             ssq = fmaf(v, v, ssq);
         }
         float s = block_sum(ssq, scratch);
-        if (threadIdx.x == 0) op.ss_out[(size_t)wg * KS_MAX_ROWS + m] = s;
+        if (threadIdx.x == 0) op.ss_out[(size_t)m * KS_NWG + wg] = s;
     }
 }
 

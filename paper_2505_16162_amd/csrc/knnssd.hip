@@ -492,6 +492,9 @@ static int32_t run_pass_bf16(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, b
             v.lds_bytes = (int)KS_MAX_DYN_LDS;
             v.n_rows = n_rows;
             mfma_chunking(KS_MAX_DYN_LDS, v.max_rows, n_rows, v.K, &v.kc, &v.nc);
+            v.bbuf_bytes = mfma_bbuf_bytes(KS_MAX_DYN_LDS, v.max_rows);
+            v.fixed_lds = (int)mfma_fixed_lds(KS_MAX_DYN_LDS, v.max_rows);
+            v.red_bufs = mfma_red_bufs(KS_MAX_DYN_LDS, v.max_rows);
             // many activation chunks (many token rows, long K): the variant whose weight stream rolls on across the
             // chunk boundaries; few chunks: the leaner per-chunk loops
             const bool ring = v.nc >= 4;
