@@ -118,6 +118,10 @@ def main():
     ap.add_argument("--knn-probe", type=int, default=0, metavar="N",
                     help="time the K-nearest-anchor scan (knnssd_knn_topk, K = 8) over N anchors of dimension 5120, for 1 and 4 "
                          "queries per pass, and print its HBM rate instead of the benchmark line")
+    ap.add_argument("--full-acceptance", action="store_true",
+                    help="probe, not the benchmark line: the skipped blocks' output projections are zeroed in the synthetic "
+                         "weights, so the draft model equals the full model and every draft is accepted; no confidence "
+                         "stop. Prints tokens/s of KNN-SSD rounds of max_draft drafts against AR on the same weights")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="run under `rocprofv3 --pmc FETCH_SIZE` (or WRITE_SIZE): one plain 1 GiB copy for calibration, "
                          "then verification passes with only the weight-streaming launches; prints nothing else")
@@ -150,6 +154,9 @@ def main():
 
     t0 = time.time()
     w = synth.make_weights(shape, device=dev)
+    if args.full_acceptance:
+        print(json.dumps(full_acceptance_probe(args, wl, shape, w, prompt_len, max_new)))
+        return
     gpu = binding.KnnSsd(shape, w, max_anchors=wl.n_anchors)
     anchors, labels, centres = synth.make_anchors(shape.d_model, wl.n_anchors, wl.n_domains, wl.anchor_sigma,
                                                   device=dev, clustered=wl.n_domains < wl.n_anchors)
@@ -329,6 +336,45 @@ def knn_probe(n_anchors, dev):
         dt = (time.time() - t0) / reps
         out[f"q{nq}"] = {"ms": round(dt * 1e3, 3), "scan_GBps": round(n_anchors * d * 4 / dt / 1e9, 1),
                          "frac_of_peak": round(n_anchors * d * 4 / dt / 1e9 / HBM_PEAK_GBS, 4)}
+    gpu.close()
+    return out
+
+
+def full_acceptance_probe(args, wl, shape, w, prompt_len, max_new):
+    """What the rounds cost when every draft is accepted (alpha = 1, the upper end of the regime the paper
+    works in: App. C.2 reports alpha 0.8-0.95). Random-init weights accept nothing, so this probe plants the
+    acceptance: the output projections (attention O, MLP down) of the blocks the mask skips are zeroed, which
+    makes those blocks identities, so the draft model IS the full model. Rounds then draft max_draft tokens
+    (no confidence stop), verify max_draft + 1 rows and emit max_draft + 1 tokens."""
+    import torch
+    from paper_2505_16162_amd import binding, synth
+    mask = synth.make_block_masks(shape.n_blocks, 1, wl.skipped_blocks)[0].tolist()
+    for b, blk in enumerate(w["blocks"]):
+        if mask[2 * b]:
+            blk["wo"].zero_()
+        if mask[2 * b + 1]:
+            blk["wd"].zero_()
+    gpu = binding.KnnSsd(shape, w)
+    prompt = synth.make_prompt(shape.vocab, prompt_len).tolist()
+    gpu.knnssd_set_skipset(mask)
+    out = {"probe": "full acceptance (planted: skipped blocks are identities)", "workload": shape.name,
+           "skipped_blocks": wl.skipped_blocks, "prompt": prompt_len, "generate": max_new}
+    ar_toks, ar_st = gpu.knnssd_generate(prompt, max_new, 0)
+    ar_toks, ar_st = gpu.knnssd_generate(prompt, max_new, 0)
+    ar_tps = (ar_st["emitted"] - 1) / (ar_st["ns_verify"] * 1e-9)
+    out["ar_tokens_per_s"] = round(ar_tps, 2)
+    rows = []
+    for k in (1, 2, 4, 8, 15):
+        gpu.knnssd_generate(prompt, max_new, k, 0.0)
+        toks, st = gpu.knnssd_generate(prompt, max_new, k, 0.0)
+        dec = st["ns_draft"] + st["ns_verify"]
+        tps = (st["emitted"] - 1) / (dec * 1e-9)
+        rows.append({"max_draft": k, "tokens_per_s": round(tps, 2), "speedup_over_ar": round(tps / ar_tps, 3),
+                     "mean_generated_length_M": round((st["emitted"] - 1) / max(st["rounds"], 1), 3),
+                     "acceptance_rate_alpha": round(st["accepted"] / max(st["drafted"], 1), 4),
+                     "ms_per_round": round(dec * 1e-6 / max(st["rounds"], 1), 3),
+                     "equals_ar_tokens": toks == ar_toks})
+    out["rounds_by_max_draft"] = rows
     gpu.close()
     return out
 
