@@ -239,8 +239,11 @@ def main():
             r = gpu.knnssd_profile_pass(1, rows, prompt_len)
             acc = {k: acc[k] + r[k] for k in acc}
         gemm_gbs = acc["gemm_bytes"] / (acc["gemm_ns"] * 1e-9) / 1e9
-        roof = {"bound": "hbm", "kernel": "gemm_mfma_kernel<false, false> (verification GEMM: the 161 launches of one pass, "
-                                          "back to back between two HIP events)",
+        # the library runs the <false, true> instance instead when a launch stages its activations in four chunks or
+        # more (many rows); the headline workload's two-row passes never do
+        inst = "gemm_mfma_kernel<false, false>" if args.workload == "llama13b" else "gemm_mfma_kernel<false, *>"
+        roof = {"bound": "hbm", "kernel": f"{inst} (verification GEMM: the {acc['n_launches'] // reps} launches of one "
+                                          "pass, back to back between two HIP events)",
                 "achieved": round(gemm_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(gemm_gbs / HBM_PEAK_GBS, 4),
                 "traffic": recorded_traffic() if args.workload == "llama13b" else None,

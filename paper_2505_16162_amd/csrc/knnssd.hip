@@ -14,6 +14,7 @@
 #include "kernels_generic.h"
 #include "kernels_bf16.h"
 #include "kernels_prefill.h"
+#include "kernels_vattn.h"
 
 using namespace ks;
 
@@ -149,6 +150,7 @@ struct knnssd_ctx {
     bool tuned;         // shape fits the tuned bf16 draft kernels
     bool tuned_verify;  // ... and the matrix-core verification kernels (every K a multiple of 32)
     bool tuned_prefill; // ... and the many-row prefill kernels (a row group fits 16 tile slots)
+    bool verify_attn_mfma;  // verification passes run their split-KV attention on the matrix cores
     // tabulated workgroup splits of the five matrix shapes (tuned kernels)
     const WgSplit *split_qkv = nullptr, *split_o = nullptr, *split_gu = nullptr, *split_down = nullptr, *split_head = nullptr;
     int32_t cache_len;
@@ -232,6 +234,16 @@ extern "C" int32_t knnssd_create(const knnssd_model_cfg *cfg, const knnssd_weigh
     c->tuned = cfg->weights_packed != 0;     // stream-order weights <=> tuned kernels (checked above)
     c->tuned_verify = c->tuned;
     c->tuned_prefill = c->tuned && prefill_tuned_ok(*cfg) && !getenv("KNNSSD_CHUNKED_PREFILL");
+    // Attention of the verification passes: the vector-ALU kernel walks a work item's (row, head) pairs one by one,
+    // the matrix-core kernel takes 16 at a time at a higher fixed cost. With grouped-query attention every row brings
+    // H / Hkv pairs per kv head and the matrix cores win at any row count; with one pair per row they only win from
+    // about four rows on, and the common short verification passes lose. The choice is per model (not per pass), so
+    // a row's result never depends on how many rows share its pass. KNNSSD_VERIFY_ATTN = mfma | valu overrides it.
+    c->verify_attn_mfma = cfg->n_heads / cfg->n_kv_heads >= 2;
+    if (const char *ev = getenv("KNNSSD_VERIFY_ATTN")) {
+        if (!strcmp(ev, "mfma")) c->verify_attn_mfma = true;
+        else if (!strcmp(ev, "valu")) c->verify_attn_mfma = false;
+    }
     if (c->tuned) {
         hipError_t ea = hipFuncSetAttribute((const void *)gemv_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, KS_MAX_DYN_LDS);
         if (ea == hipSuccess)
@@ -242,6 +254,10 @@ extern "C" int32_t knnssd_create(const knnssd_model_cfg *cfg, const knnssd_weigh
             ea = hipFuncSetAttribute((const void *)gemm_mfma_kernel<true, false>, hipFuncAttributeMaxDynamicSharedMemorySize, KS_MAX_DYN_LDS);
         if (ea == hipSuccess)
             ea = hipFuncSetAttribute((const void *)gemm_mfma_kernel<true, true>, hipFuncAttributeMaxDynamicSharedMemorySize, KS_MAX_DYN_LDS);
+        if (ea == hipSuccess)
+            ea = hipFuncSetAttribute((const void *)attn_partial_mfma_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)vattn_lds_bytes<128>());
+        if (ea == hipSuccess)
+            ea = hipFuncSetAttribute((const void *)attn_partial_mfma_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)vattn_lds_bytes<64>());
         if (ea == hipSuccess)
             ea = hipFuncSetAttribute((const void *)prefill_gemm_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pf_gemm_lds_bytes(4));
         if (ea == hipSuccess)
@@ -537,6 +553,10 @@ static int32_t run_pass_bf16(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, b
             launch(o);
             aa.kv_block = kvb;
             if (!others) {
+            } else if (!rows1 && c->verify_attn_mfma) {
+                // verification: the pairs of a work item side by side on the matrix cores
+                if (hd == 128) hipLaunchKernelGGL((attn_partial_mfma_kernel<128>), dim3(2 * KS_NWG), dim3(VA_NT), vattn_lds_bytes<128>(), s, aa, ctl);
+                else hipLaunchKernelGGL((attn_partial_mfma_kernel<64>), dim3(2 * KS_NWG), dim3(VA_NT), vattn_lds_bytes<64>(), s, aa, ctl);
             } else if (hd == 128) hipLaunchKernelGGL((attn_partial_kernel<128>), dim3(KS_NWG), dim3(NT), attn_lds_bytes(128), s, aa, ctl);
             else hipLaunchKernelGGL((attn_partial_kernel<64>), dim3(KS_NWG), dim3(NT), attn_lds_bytes(64), s, aa, ctl);
             if (!others) {

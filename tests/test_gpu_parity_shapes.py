@@ -179,3 +179,33 @@ def test_fewer_rows_than_workgroups():
             ok, err = logits_close(gpu.knnssd_get_logits(r).numpy(), rows_o[r], shape)
             assert ok, (n, r, err)
     gpu.close()
+
+
+@pytest.mark.parametrize("kernel", ["mfma", "valu"])
+@pytest.mark.parametrize("gqa", [False, True])
+def test_verification_attention_kernels(kernel, gqa, monkeypatch):
+    """Both split-KV attention kernels of the verification pass (matrix cores / vector ALUs; the library picks one
+    per model, KNNSSD_VERIFY_ATTN forces either) on a multi-head and a grouped-query shape: 1, 3, 9 and 16 rows behind
+    a prompt that spans two 256-position chunks, logits against the oracle, and rows independent of the row count."""
+    monkeypatch.setenv("KNNSSD_VERIFY_ATTN", kernel)
+    shape = synth.small_shape("va_gqa" if gqa else "va_mha", n_blocks=2, d_model=512, n_heads=8, n_kv_heads=2 if gqa else 8,
+                              head_dim=64, d_ffn=1408, vocab=900, max_seq=320)
+    w, orc, gpu = make_pair(shape, seed=31, std=0.04)
+    prompt = synth.make_prompt(shape.vocab, 283, seed=2).tolist()            # chunk 0 full, chunk 1 holds 27 + rows
+    first_o, _, _ = O.prefill(orc, prompt)
+    first_g, _ = gpu.knnssd_prefill(prompt)
+    assert first_g == first_o
+    rows_in = [first_o] + synth.make_prompt(shape.vocab, 15, seed=4).tolist()
+    rows_o = orc.forward(rows_in, len(prompt), None)
+    kept = {}
+    for n in (16, 9, 3, 1):
+        gpu.knnssd_prefill(prompt)
+        gpu.knnssd_verify(rows_in[:n], len(prompt))
+        for r in range(n):
+            got = gpu.knnssd_get_logits(r).clone()
+            ok, err = logits_close(got.numpy(), rows_o[r], shape)
+            assert ok, (kernel, gqa, n, r, err)
+            if r in kept:
+                assert torch.equal(got, kept[r]), (kernel, gqa, n, r)
+            kept[r] = got
+    gpu.close()
