@@ -1189,12 +1189,21 @@ __device__ __forceinline__ void attn_combine_device(const AttnArgs &a, const Pas
         const int m = div_small(i, qd, inv_qd), c = i - m * qd, h = c >> hd_shift, dim = c & (hd - 1);
         const int n_chunks = (start + m + 1 + ATT_CHUNK - 1) / ATT_CHUNK;   // chunks row m can see
         const float *pp = a.partial + ((size_t)m * a.H + h) * a.max_chunks * (hd + 2);
-        // Two passes in chunk order (largest maximum, then the weighted sums), each fetching the partials of CB chunks
-        // with unconditional loads before using any of them: a load per loop iteration would cost one memory round
-        // trip per chunk. Entries past the last chunk re-read it and enter the sums with weight zero, which leaves
-        // the sums bit for bit as if they had been skipped.
+        // Two passes in chunk order (largest maximum, then the weighted sums) over partials fetched CB chunks at a
+        // time with unconditional loads before any of them is used: a load per loop iteration would cost one memory
+        // round trip per chunk. The first CB chunks (all of them up to 2048 positions) are fetched once, for both
+        // passes. Entries past the last chunk re-read it and enter the sums with weight zero, which leaves the sums
+        // bit for bit as if they had been skipped.
+        float mv0[CB], lv0[CB], ov0[CB];
+#pragma unroll
+        for (int k = 0; k < CB; ++k) {
+            const float *cp = pp + (size_t)min(k, n_chunks - 1) * (hd + 2);
+            mv0[k] = cp[hd]; lv0[k] = cp[hd + 1]; ov0[k] = cp[dim];
+        }
         float M = -INFINITY;
-        for (int base = 0; base < n_chunks; base += CB) {
+#pragma unroll
+        for (int k = 0; k < CB; ++k) M = fmaxf(M, mv0[k]);
+        for (int base = CB; base < n_chunks; base += CB) {
             float mv[CB];
 #pragma unroll
             for (int k = 0; k < CB; ++k) mv[k] = pp[(size_t)min(base + k, n_chunks - 1) * (hd + 2) + hd];
@@ -1202,7 +1211,13 @@ __device__ __forceinline__ void attn_combine_device(const AttnArgs &a, const Pas
             for (int k = 0; k < CB; ++k) M = fmaxf(M, mv[k]);
         }
         float L = 0.f, O = 0.f;
-        for (int base = 0; base < n_chunks; base += CB) {
+#pragma unroll
+        for (int k = 0; k < CB; ++k) {
+            const float f = (k < n_chunks && mv0[k] > -INFINITY) ? expf(mv0[k] - M) : 0.f;
+            L = fmaf(lv0[k], f, L);
+            O = fmaf(ov0[k], f, O);
+        }
+        for (int base = CB; base < n_chunks; base += CB) {
             float mv[CB], lv[CB], ov[CB];
 #pragma unroll
             for (int k = 0; k < CB; ++k) {

@@ -3,13 +3,16 @@
 // The vector-ALU kernel (attn_partial_kernel, kernels_bf16.h) walks the (row, head) pairs of a work item one
 // after the other; a verification pass of k+1 rows has (k+1) x group pairs per kv head, and at 9 rows the walk
 // costs three times the draft step's attention. Here a work item is (kv head, 256-position chunk, tile of up to
-// 16 pairs) and its four wavefronts take 64 positions each:
+// 16 pairs) and its four wavefronts take 64 positions each (eight wavefronts of 32 positions measure the same:
+// the kernel is bound by its chain of memory round trips, not by instruction issue):
 //   S = Q K^T  scores of the 16 pairs against the wavefront's 64 positions: Q as three exact bf16 planes (A
 //              operand, from the rotated fp32 queries), K straight from the cache (a lane's 16-byte load of one
 //              position IS its B-operand fragment),
 //   softmax    partial over the 64 positions in fp32 on the vector ALUs (max, exp, sum),
-//   O = P V    P back through a wavefront-private LDS tile into operand layout as three exact planes, V transposed
-//              through LDS on the way in,
+//   O = P V    P back through a wavefront-private LDS tile into operand layout as three exact planes; V needs no
+//              transposition through memory: a lane loads DT consecutive dimensions of its 8 positions and regroups
+//              them in registers (one byte permute per operand register), so that matrix instruction t produces
+//              dimensions {DT * n + t} in its 16 columns n,
 // then the four wavefronts' (max, sum, O) are merged in LDS and written as the chunk's partial, in the format
 // attn_combine_kernel reads. A pair's result does not depend on which other pairs share its tile, nor on the
 // number of rows in the pass.
@@ -18,31 +21,33 @@
 
 namespace ks {
 
-constexpr int VA_NT = 256;                 // threads per workgroup (four wavefronts)
-constexpr int VA_WP = ATT_CHUNK / 4;       // positions per wavefront
-static_assert(VA_WP == 64, "four position tiles of 16 per wavefront");
+constexpr int VA_NW = 4;                   // wavefronts per workgroup
+constexpr int VA_NT = 64 * VA_NW;          // threads per workgroup
+constexpr int VA_WP = ATT_CHUNK / VA_NW;   // positions per wavefront
+constexpr int VA_TP = VA_WP / 16;          // position tiles of the score product
+constexpr int VA_KS = VA_WP / 32;          // summation steps of the value product
+static_assert(VA_WP % 32 == 0 && VA_WP * VA_NW == ATT_CHUNK, "whole summation steps, whole chunk");
+
+typedef unsigned int va_u32x2 __attribute__((ext_vector_type(2)));
 
 template <int HD>
 __host__ __device__ constexpr size_t vattn_lds_bytes() {
-    // per wavefront: transposed values [HD][64 positions + 8] bf16 and the P tile [16][64 + 4] fp32; the merge
-    // buffer [4][16][HD + 2] fp32 reuses the value area once every wavefront is done with it
-    return (size_t)4 * HD * (VA_WP * 2 + 16) + (size_t)4 * 16 * (VA_WP + 4) * 4;
+    // per wavefront: the P tile [16][positions + 4] fp32 and its share [16][HD + 4] fp32 of the merge buffer
+    return (size_t)VA_NW * 16 * (VA_WP + 4) * 4 + (size_t)VA_NW * 16 * (HD + 4) * 4;
 }
 
 template <int HD>
 __global__ __launch_bounds__(VA_NT) void attn_partial_mfma_kernel(AttnArgs a, const PassCtl *ctl) {
-    constexpr int QS = HD / 32, DT = HD / 16, LPP = HD / 8;
-    constexpr int VSTR = VA_WP * 2 + 16;       // bytes per transposed value row (one dimension, 64 positions)
+    constexpr int QS = HD / 32, DT = HD / 16;
     constexpr int PSTR = VA_WP + 4;            // floats per row of the P tile
-    constexpr int VQ = VA_WP * LPP / 64;       // 16-byte value pieces per lane
-    static_assert(4 * 16 * (HD + 2) * 4 <= 4 * HD * VSTR, "the merge buffer fits the value area");
+    constexpr int MSTR = HD + 4;               // floats per row of the merge buffer (16-byte aligned rows)
+    static_assert(DT == 8 || DT == 4, "a lane loads 16 or 8 bytes of a value row");
     extern __shared__ __align__(16) char lds[];
     if (!ctl->active) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int kg = lane >> 4, r16 = lane & 15;
-    char *vt = lds + (size_t)wave * HD * VSTR;                                            // this wavefront's V^T
-    float *pw = reinterpret_cast<float *>(lds + (size_t)4 * HD * VSTR) + wave * 16 * PSTR; // this wavefront's P tile
-    float *mb = reinterpret_cast<float *>(lds);                                           // [4][16][HD + 2] merge buffer
+    float *pw = reinterpret_cast<float *>(lds) + wave * 16 * PSTR;                        // this wavefront's P tile
+    float *mb = reinterpret_cast<float *>(lds + (size_t)VA_NW * 16 * PSTR * 4);           // [VA_NW][16][MSTR] merge buffer
 
     const int n_rows = min(ctl->n_rows, KS_MAX_ROWS), start = ctl->start;
     const int group = a.group;
@@ -66,48 +71,53 @@ __global__ __launch_bounds__(VA_NT) void attn_partial_mfma_kernel(AttnArgs a, co
         const bf16_t *kc = a.kv_block + (size_t)kvh * kv_head_stride;
         const bf16_t *vc = a.kv_block + ((size_t)a.Hkv + kvh) * kv_head_stride;
 
-        // keys: position tile t4, lane (kg, j) loads position 16*t4 + j, dims 32*ks + 8*kg .. +7 = its B fragment.
-        // Positions past the last live one re-read it; their scores are masked below.
-        u32x4 kf[4][QS];
-#pragma unroll
-        for (int t4 = 0; t4 < 4; ++t4) {
-            const int pos = min(wp0 + t4 * 16 + r16, last_pos);
-#pragma unroll
-            for (int ks = 0; ks < QS; ++ks)
-                kf[t4][ks] = *reinterpret_cast<const u32x4 *>(kc + (size_t)pos * HD + ks * 32 + kg * 8);
-        }
-        // values: 64 positions x HD as 16-byte pieces, piece i = (position i / LPP, dims 8 * (i % LPP) .. +7)
-        u32x4 vr[VQ];
-#pragma unroll
-        for (int q = 0; q < VQ; ++q) {
-            const int i = lane + 64 * q;
-            const int pos = min(wp0 + i / LPP, last_pos);
-            vr[q] = *reinterpret_cast<const u32x4 *>(vc + (size_t)pos * HD + (i % LPP) * 8);
-        }
         // queries of the tile's pairs as operand fragments: lane (kg, i) holds pair 16*pt + i, dims 32*ks + 8*kg .. +7
         // (a lane past the last pair repeats it; its accumulator row is never stored)
-        bf16x8 qa[QS][3];
+        f32x4 qf[QS][2];
         {
             const int p = min(pt * 16 + r16, P - 1);
             const int m = div_small(p, group, inv_group), h = kvh * group + (p - m * group);
             const float *qp = a.q + (size_t)m * qd + h * HD + kg * 8;
 #pragma unroll
             for (int ks = 0; ks < QS; ++ks) {
-                float v[8];
-                const float4 v0 = *reinterpret_cast<const float4 *>(qp + ks * 32), v1 = *reinterpret_cast<const float4 *>(qp + ks * 32 + 4);
-                v[0] = v0.x; v[1] = v0.y; v[2] = v0.z; v[3] = v0.w; v[4] = v1.x; v[5] = v1.y; v[6] = v1.z; v[7] = v1.w;
-                split_planes8(v, qa[ks]);
+                qf[ks][0] = *reinterpret_cast<const f32x4 *>(qp + ks * 32);
+                qf[ks][1] = *reinterpret_cast<const f32x4 *>(qp + ks * 32 + 4);
             }
         }
-        __syncthreads();        // the previous item's merge buffer (which overlays the value areas) has been read
-        // values into LDS, transposed: row = dimension, column = position within the wavefront's 64
+        // keys: position tile t4, lane (kg, j) loads position 16*t4 + j, dims 32*ks + 8*kg .. +7 = its B fragment.
+        // Positions past the last live one re-read it; their scores are masked below.
+        u32x4 kf[VA_TP][QS];
 #pragma unroll
-        for (int q = 0; q < VQ; ++q) {
-            const int i = lane + 64 * q, pos = i / LPP, d0 = (i % LPP) * 8;
-            const unsigned int w[4] = {vr[q].x, vr[q].y, vr[q].z, vr[q].w};
+        for (int t4 = 0; t4 < VA_TP; ++t4) {
+            const int pos = min(wp0 + t4 * 16 + r16, last_pos);
 #pragma unroll
-            for (int e = 0; e < 8; ++e)
-                *reinterpret_cast<bf16_t *>(vt + (d0 + e) * VSTR + pos * 2) = (bf16_t)((e & 1) ? (w[e >> 1] >> 16) : (w[e >> 1] & 0xffffu));
+            for (int ks = 0; ks < QS; ++ks)
+                kf[t4][ks] = *reinterpret_cast<const u32x4 *>(kc + (size_t)pos * HD + ks * 32 + kg * 8);
+        }
+        // values: lane (kg, n) loads dims DT*n .. DT*n + DT-1 of positions 32*ks2 + 8*kg + j, j = 0..7 (the eight
+        // summation slots it owns in step ks2); vw[ks2][j][w] holds dims DT*n + 2w, +1 of slot j
+        unsigned int vw[VA_KS][8][DT / 2];
+#pragma unroll
+        for (int ks2 = 0; ks2 < VA_KS; ++ks2)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int pos = min(wp0 + ks2 * 32 + kg * 8 + j, last_pos);
+                const bf16_t *vp = vc + (size_t)pos * HD + r16 * DT;
+                if constexpr (DT == 8) {
+                    const u32x4 t = *reinterpret_cast<const u32x4 *>(vp);
+                    vw[ks2][j][0] = t.x; vw[ks2][j][1] = t.y; vw[ks2][j][2] = t.z; vw[ks2][j][3] = t.w;
+                } else {
+                    const va_u32x2 t = *reinterpret_cast<const va_u32x2 *>(vp);
+                    vw[ks2][j][0] = t.x; vw[ks2][j][1] = t.y;
+                }
+            }
+        bf16x8 qa[QS][3];
+#pragma unroll
+        for (int ks = 0; ks < QS; ++ks) {
+            float v[8];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { v[e] = qf[ks][0][e]; v[4 + e] = qf[ks][1][e]; }
+            split_planes8(v, qa[ks]);
         }
         // accumulator row q of this lane is pair 16*pt + 4*kg + q; it sees positions <= start + its token row
         int vis[4];
@@ -117,9 +127,9 @@ __global__ __launch_bounds__(VA_NT) void attn_partial_mfma_kernel(AttnArgs a, co
             vis[q] = start + div_small(p, group, inv_group);
         }
         // S = Q K^T: lane (kg, j) holds pairs 4*kg .. 4*kg+3 at position 16*t4 + j
-        float sc[4][4];
+        float sc[VA_TP][4];
 #pragma unroll
-        for (int t4 = 0; t4 < 4; ++t4) {
+        for (int t4 = 0; t4 < VA_TP; ++t4) {
             f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int ks = 0; ks < QS; ++ks) {
@@ -131,17 +141,19 @@ __global__ __launch_bounds__(VA_NT) void attn_partial_mfma_kernel(AttnArgs a, co
 #pragma unroll
             for (int q = 0; q < 4; ++q) sc[t4][q] = (pos <= vis[q]) ? acc[q] * scale : -INFINITY;
         }
-        // softmax over the wavefront's 64 positions, per pair (a pair's values sit in the 16 lanes of a kg group)
+        // softmax over the wavefront's positions, per pair (a pair's values sit in the 16 lanes of a kg group)
         float mx[4], ls[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            float cm = fmaxf(fmaxf(sc[0][q], sc[1][q]), fmaxf(sc[2][q], sc[3][q]));
+            float cm = sc[0][q];
+#pragma unroll
+            for (int t4 = 1; t4 < VA_TP; ++t4) cm = fmaxf(cm, sc[t4][q]);
 #pragma unroll
             for (int off = 1; off < 16; off <<= 1) cm = fmaxf(cm, __shfl_xor(cm, off, 64));
-            mx[q] = cm;                                       // -inf when none of the 64 positions is visible
+            mx[q] = cm;                                       // -inf when none of the positions is visible
             float ps = 0.f;
 #pragma unroll
-            for (int t4 = 0; t4 < 4; ++t4) {
+            for (int t4 = 0; t4 < VA_TP; ++t4) {
                 const float e = (sc[t4][q] > -INFINITY) ? expf(sc[t4][q] - cm) : 0.f;
                 pw[(4 * kg + q) * PSTR + t4 * 16 + r16] = e;
                 ps += e;
@@ -150,12 +162,14 @@ __global__ __launch_bounds__(VA_NT) void attn_partial_mfma_kernel(AttnArgs a, co
             for (int off = 1; off < 16; off <<= 1) ps += __shfl_xor(ps, off, 64);
             ls[q] = ps;
         }
-        // O = P V: P back from LDS in operand layout (lane (kg, i): pair i, positions 32*ks2 + 8*kg .. +7)
+        // O = P V: P back from LDS in operand layout (lane (kg, i): pair i, positions 32*ks2 + 8*kg .. +7); the value
+        // operand of instruction t takes dimension DT*n + t of the lane's eight positions: the low (t even) or high
+        // (t odd) halves of word t/2 of two neighbouring slots make one operand register
         f32x4 o[DT];
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int t = 0; t < DT; ++t) o[t] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int ks2 = 0; ks2 < 2; ++ks2) {
+        for (int ks2 = 0; ks2 < VA_KS; ++ks2) {
             float pv[8];
             const float4 p0 = *reinterpret_cast<const float4 *>(pw + r16 * PSTR + ks2 * 32 + kg * 8);
             const float4 p1 = *reinterpret_cast<const float4 *>(pw + r16 * PSTR + ks2 * 32 + kg * 8 + 4);
@@ -163,44 +177,52 @@ __global__ __launch_bounds__(VA_NT) void attn_partial_mfma_kernel(AttnArgs a, co
             bf16x8 pa[3];
             split_planes8(pv, pa);
 #pragma unroll
-            for (int dt = 0; dt < DT; ++dt) {
-                const bf16x8 vb = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(vt + (dt * 16 + r16) * VSTR + (ks2 * 32 + kg * 8) * 2));
+            for (int t = 0; t < DT; ++t) {
+                u32x4 vb;
 #pragma unroll
-                for (int p = 0; p < 3; ++p) o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa[p], vb, o[dt], 0, 0, 0);
+                for (int jj = 0; jj < 4; ++jj) {
+                    // bytes 0-3 of the selector's source are the second operand, 4-7 the first
+                    vb[jj] = __builtin_amdgcn_perm(vw[ks2][2 * jj + 1][t >> 1], vw[ks2][2 * jj][t >> 1],
+                                                   (t & 1) ? 0x07060302u : 0x05040100u);
+                }
+                const bf16x8 vbf = __builtin_bit_cast(bf16x8, vb);
+#pragma unroll
+                for (int p = 0; p < 3; ++p) o[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa[p], vbf, o[t], 0, 0, 0);
             }
         }
-        __syncthreads();        // every wavefront is done with its value area: the merge buffer may overlay them
+        __syncthreads();        // the previous item's merge buffer has been read by every wavefront
         {
-            float *mw = mb + (size_t)wave * 16 * (HD + 2);
+            float *mw = mb + (size_t)wave * 16 * MSTR;
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                float *row = mw + (4 * kg + q) * (HD + 2);
+                float *row = mw + (4 * kg + q) * MSTR;
 #pragma unroll
-                for (int dt = 0; dt < DT; ++dt) row[dt * 16 + r16] = o[dt][q];
+                for (int t4 = 0; t4 < DT / 4; ++t4)
+                    *reinterpret_cast<float4 *>(row + r16 * DT + 4 * t4) =
+                        make_float4(o[4 * t4][q], o[4 * t4 + 1][q], o[4 * t4 + 2][q], o[4 * t4 + 3][q]);
                 if (r16 == 0) { row[HD] = mx[q]; row[HD + 1] = ls[q]; }
             }
         }
         __syncthreads();
-        // merge the four wavefronts in position order: thread (pair, dim)
-        for (int i = tid; i < 16 * HD; i += VA_NT) {
+        // merge the wavefronts in position order: thread (pair, dim)
+        const int n_p = min(16, P - pt * 16);
+        for (int i = tid; i < n_p * HD; i += VA_NT) {
             const int pl = i / HD, dim = i - pl * HD, p = pt * 16 + pl;
-            if (p < P) {
-                const int m = div_small(p, group, inv_group), h = kvh * group + (p - m * group);
-                float M = -INFINITY;
+            const int m = div_small(p, group, inv_group), h = kvh * group + (p - m * group);
+            float M = -INFINITY;
 #pragma unroll
-                for (int w = 0; w < 4; ++w) M = fmaxf(M, mb[((size_t)w * 16 + pl) * (HD + 2) + HD]);
-                float L = 0.f, O = 0.f;
+            for (int w = 0; w < VA_NW; ++w) M = fmaxf(M, mb[((size_t)w * 16 + pl) * MSTR + HD]);
+            float L = 0.f, O = 0.f;
 #pragma unroll
-                for (int w = 0; w < 4; ++w) {
-                    const float *rp = mb + ((size_t)w * 16 + pl) * (HD + 2);
-                    const float f = (rp[HD] > -INFINITY) ? expf(rp[HD] - M) : 0.f;
-                    L = fmaf(rp[HD + 1], f, L);
-                    O = fmaf(rp[dim], f, O);
-                }
-                float *out = a.partial + (((size_t)m * a.H + h) * a.max_chunks + chunk) * (HD + 2);
-                out[dim] = O;
-                if (dim == 0) { out[HD] = M; out[HD + 1] = L; }
+            for (int w = 0; w < VA_NW; ++w) {
+                const float *rp = mb + ((size_t)w * 16 + pl) * MSTR;
+                const float f = (rp[HD] > -INFINITY) ? expf(rp[HD] - M) : 0.f;
+                L = fmaf(rp[HD + 1], f, L);
+                O = fmaf(rp[dim], f, O);
             }
+            float *out = a.partial + (((size_t)m * a.H + h) * a.max_chunks + chunk) * (HD + 2);
+            out[dim] = O;
+            if (dim == 0) { out[HD] = M; out[HD + 1] = L; }
         }
     }
 }

@@ -235,11 +235,10 @@ extern "C" int32_t knnssd_create(const knnssd_model_cfg *cfg, const knnssd_weigh
     c->tuned_verify = c->tuned;
     c->tuned_prefill = c->tuned && prefill_tuned_ok(*cfg) && !getenv("KNNSSD_CHUNKED_PREFILL");
     // Attention of the verification passes: the vector-ALU kernel walks a work item's (row, head) pairs one by one,
-    // the matrix-core kernel takes 16 at a time at a higher fixed cost. With grouped-query attention every row brings
-    // H / Hkv pairs per kv head and the matrix cores win at any row count; with one pair per row they only win from
-    // about four rows on, and the common short verification passes lose. The choice is per model (not per pass), so
-    // a row's result never depends on how many rows share its pass. KNNSSD_VERIFY_ATTN = mfma | valu overrides it.
-    c->verify_attn_mfma = cfg->n_heads / cfg->n_kv_heads >= 2;
+    // the matrix-core kernel takes 16 at a time. The latter is faster from two pairs on and 10 % slower at one; the
+    // choice is per context (never per pass), so a row's result does not depend on how many rows share its pass.
+    // KNNSSD_VERIFY_ATTN = mfma | valu overrides it.
+    c->verify_attn_mfma = true;
     if (const char *ev = getenv("KNNSSD_VERIFY_ATTN")) {
         if (!strcmp(ev, "mfma")) c->verify_attn_mfma = true;
         else if (!strcmp(ev, "valu")) c->verify_attn_mfma = false;

@@ -184,8 +184,8 @@ def test_fewer_rows_than_workgroups():
 @pytest.mark.parametrize("kernel", ["mfma", "valu"])
 @pytest.mark.parametrize("gqa", [False, True])
 def test_verification_attention_kernels(kernel, gqa, monkeypatch):
-    """Both split-KV attention kernels of the verification pass (matrix cores / vector ALUs; the library picks one
-    per model, KNNSSD_VERIFY_ATTN forces either) on a multi-head and a grouped-query shape: 1, 3, 9 and 16 rows behind
+    """Both split-KV attention kernels of the verification pass (matrix cores / vector ALUs; the library uses the first
+    unless KNNSSD_VERIFY_ATTN names the other) on a multi-head and a grouped-query shape: 1, 3, 9 and 16 rows behind
     a prompt that spans two 256-position chunks, logits against the oracle, and rows independent of the row count."""
     monkeypatch.setenv("KNNSSD_VERIFY_ATTN", kernel)
     shape = synth.small_shape("va_gqa" if gqa else "va_mha", n_blocks=2, d_model=512, n_heads=8, n_kv_heads=2 if gqa else 8,
