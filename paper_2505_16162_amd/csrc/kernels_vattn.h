@@ -55,18 +55,21 @@ __global__ __launch_bounds__(VA_NT) void attn_partial_mfma_kernel(AttnArgs a, co
     const int P = n_rows * group;                       // (row, head-in-group) pairs per kv head
     const int n_pt = (P + 15) >> 4;
     const int n_chunks = (start + n_rows + ATT_CHUNK - 1) / ATT_CHUNK;
-    const int n_items = a.Hkv * n_chunks * n_pt;
+    // Work items in launch order: pair tile slowest, and a tile's (kv head, chunk) items padded to a multiple of 8,
+    // so that the tiles of one (kv head, chunk) run on workgroups 8k apart, i.e. (workgroups are dealt round-robin
+    // over the 8 XCDs) behind the same L2, which then fetches that chunk's keys and values from HBM once
+    const int per_tile = a.Hkv * n_chunks, tile_stride = (per_tile + 7) & ~7;
+    const int n_items = n_pt * tile_stride;
     const int last_pos = start + n_rows - 1, qd = a.H * HD;
     const float scale = 1.0f / sqrtf((float)HD);
     const size_t kv_head_stride = (size_t)a.max_seq * HD;
 
     for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
-        // item -> (kv head, chunk, pair tile), pair tile fastest
-        const int per_head = n_pt * n_chunks;
-        const int kvh = div_small(item, per_head, __builtin_amdgcn_rcpf((float)per_head));
-        const int in_head = item - kvh * per_head;
-        const int chunk = div_small(in_head, n_pt, __builtin_amdgcn_rcpf((float)n_pt));
-        const int pt = in_head - chunk * n_pt;
+        const int pt = div_small(item, tile_stride, __builtin_amdgcn_rcpf((float)tile_stride));
+        const int in_tile = item - pt * tile_stride;
+        if (in_tile >= per_tile) continue;              // padding (the whole workgroup skips it together)
+        const int kvh = div_small(in_tile, n_chunks, __builtin_amdgcn_rcpf((float)n_chunks));
+        const int chunk = in_tile - kvh * n_chunks;
         const int wp0 = chunk * ATT_CHUNK + wave * VA_WP;          // this wavefront's first position
         const bf16_t *kc = a.kv_block + (size_t)kvh * kv_head_stride;
         const bf16_t *vc = a.kv_block + ((size_t)a.Hkv + kvh) * kv_head_stride;
