@@ -952,12 +952,9 @@ extern "C" int32_t knnssd_generate(knnssd_ctx *ctx, const int32_t *prompt_host, 
             KS_TRY(run_pass(ctx, dr, ctx->draft_mask.data(), 1, 1));
             hipLaunchKernelGGL(draft_end_kernel, dim3(1), dim3(1), 0, s, st, dr, head, ctx->d_flags);
             ++n_draft_passes; ++k_host;
-            // the host decides whether to enqueue another draft pass; without a confidence threshold a round always
-            // drafts kmax tokens (draft_end_kernel), so nothing is waited for and the passes are enqueued back to back
-            if (gen->conf_threshold > 0.f) {
-                HIP_TRY(hipStreamSynchronize(s));
-                if (!((volatile int32_t *)ctx->h_stage)[512]) break;
-            }
+            // the host decides whether to enqueue another draft pass
+            HIP_TRY(hipStreamSynchronize(s));
+            if (!((volatile int32_t *)ctx->h_stage)[512]) break;
         }
         size_t eb = ev++;
         KS_TRY(mark(ctx, eb));
