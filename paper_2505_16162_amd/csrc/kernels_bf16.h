@@ -727,6 +727,19 @@ __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl
 
     constexpr int DA = 8;                        // weight loads in flight per wavefront
     u32x4 a[DA];
+    const bool defer = RB == 2 && NC == 1 && s.T > s.tl && 2 * (s.T - s.tl) <= s.tl;    // see the end of the round loop
+    // fixed-order sum of a round's partial tiles over the wavefronts that shared each tile's columns
+    auto sum_round = [&](int rnd) {
+        const float *rr = red + (size_t)(rnd & (RB - 1)) * NWV * 256;
+        for (int i = tid; i < s.tl * 256; i += NT) {
+            const int l = i >> 8, e = i & 255, tt = rnd * s.tl + l, rit = e >> 4;
+            if (tt < s.T && rit < s.rpt && tt * s.rpt + rit < R) {
+                float sum = 0.f;
+                for (int k = 0; k < s.ksplit; ++k) sum += rr[(size_t)(l * s.ksplit + k) * 256 + e];
+                vals[(tt * s.rpt + rit) * KS_MAX_ROWS + (e & 15)] = sum;
+            }
+        }
+    };
     for (int round = 0; round * s.tl < s.T; ++round) {   // T = 0 when this workgroup owns no rows
         const WaveTile w = wave_tile(s, K, round, tlane, kpart);
         f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -937,22 +950,28 @@ __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl
         // partial tile of this wavefront -> LDS; lane holds D[row 4*kg + q][token r16]. The partials of
         // consecutive rounds alternate between two buffers, so one meeting per round is enough: a buffer is
         // written again only after every wavefront has passed the next round's meeting, i.e. finished summing it.
+        // With two rounds over activations that stay staged (one chunk) every round has a buffer of its own and
+        // nothing is restaged, so the wavefronts need not meet between the rounds: a wavefront that is done with its
+        // first tile goes straight on to its second, and both rounds are summed after the loop. That pays where the
+        // second round keeps at most half of the tile lanes busy (3 tiles on 2 lanes, 6 on 4: the wavefronts with a
+        // second tile fill what would be a half-idle round; measured -0.7 % per verification pass on the 7B shapes)
+        // and costs 0.3 % where it is nearly full (7 or 8 tiles on 4 lanes), so only the former do it.
         float *redr = red + (size_t)(round & (RB - 1)) * NWV * 256;
         {
             float *rp = redr + (size_t)wave * 256;
 #pragma unroll
             for (int q = 0; q < 4; ++q) rp[(4 * kg + q) * 16 + r16] = acc[q];
         }
-        __syncthreads();    // also: every wavefront is done with the staging buffers of this round
-        for (int i = tid; i < s.tl * 256; i += NT) {
-            const int l = i >> 8, e = i & 255, tt = round * s.tl + l, rit = e >> 4;
-            if (tt < s.T && rit < s.rpt && tt * s.rpt + rit < R) {
-                float sum = 0.f;
-                for (int k = 0; k < s.ksplit; ++k) sum += redr[(size_t)(l * s.ksplit + k) * 256 + e];
-                vals[(tt * s.rpt + rit) * KS_MAX_ROWS + (e & 15)] = sum;
-            }
+        if (!defer) {
+            __syncthreads();    // also: every wavefront is done with the staging buffers of this round
+            sum_round(round);
+            if (RB == 1) __syncthreads();   // the one buffer is written again in the next round
         }
-        if (RB == 1) __syncthreads();   // the one buffer is written again in the next round
+    }
+    if (defer) {
+        __syncthreads();
+        sum_round(0);
+        if (s.tl < s.T) sum_round(1);
     }
     // the norm's shares and the epilogue's two values were issued before the first weight batch and are long here
     // (every round ends drained); the wait only ties their registers to this point
