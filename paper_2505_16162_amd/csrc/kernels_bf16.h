@@ -391,7 +391,7 @@ __device__ __forceinline__ WgSplit make_split(const GemmOp &op, int wg, int nwg,
     s.wg_base = rows_before * op.K;
     s.T = (s.R + 15) >> 4;
     s.rpt = s.T ? (s.R + s.T - 1) / s.T : 0;
-    s.tl = s.T >= 4 ? 4 : (s.T >= 2 ? 2 : 1);
+    s.tl = s.T >= 3 ? 4 : (s.T >= 2 ? 2 : 1);   // three tiles: one round on three of four lanes, not two rounds on two
     s.ksplit = NWV / s.tl;                      // NWV = 16: 4, 8 or 16
     s.ksshift = (s.tl == 4) ? 2 : (s.tl == 2 ? 3 : 4);
     s.g = 16 >> s.ksshift;

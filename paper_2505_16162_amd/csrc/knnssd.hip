@@ -515,7 +515,7 @@ static int32_t run_pass_bf16(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, b
             // is cheap against a chunk of two batches or more per wavefront and dear against less (measured: the down
             // projection in three chunks is 1 % faster per-chunk at 18 units per wavefront and chunk, K = 13824 with
             // 20 rows per workgroup, and 6 % faster rolling at 9, K = 11008 with 16 rows per workgroup).
-            const int tiles = (v.max_rows + 15) / 16, ksplit = NWV / (tiles >= 4 ? 4 : (tiles >= 2 ? 2 : 1));
+            const int tiles = (v.max_rows + 15) / 16, ksplit = NWV / (tiles >= 3 ? 4 : (tiles >= 2 ? 2 : 1));   // as make_split deals the tile lanes
             const bool ring = v.nc >= 4 || (v.nc >= 2 && (v.kc >> 5) / ksplit < 16);
             if (c->in_prefill) {
                 if (ring) hipLaunchKernelGGL((gemm_mfma_kernel<true, true>), dim3(KS_NWG), dim3(NT), KS_MAX_DYN_LDS, s, v, ctl);
