@@ -556,8 +556,9 @@ static int32_t run_pass_bf16(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, b
             launch(o);
             aa.kv_block = kvb;
             if (!others) {
-            } else if (!rows1 && c->verify_attn_mfma) {
-                // verification: the pairs of a work item side by side on the matrix cores
+            } else if ((!rows1 || aa.group >= 2) && c->verify_attn_mfma) {
+                // verification, and draft steps of grouped-query models (one row still brings H / Hkv pairs per kv
+                // head): the pairs of a work item side by side on the matrix cores
                 if (hd == 128) hipLaunchKernelGGL((attn_partial_mfma_kernel<128>), dim3(2 * KS_NWG), dim3(VA_NT), vattn_lds_bytes<128>(), s, aa, ctl);
                 else hipLaunchKernelGGL((attn_partial_mfma_kernel<64>), dim3(2 * KS_NWG), dim3(VA_NT), vattn_lds_bytes<64>(), s, aa, ctl);
             } else if (hd == 128) hipLaunchKernelGGL((attn_partial_kernel<128>), dim3(KS_NWG), dim3(NT), attn_lds_bytes(128), s, aa, ctl);
