@@ -125,7 +125,9 @@ size_t knnssd_kvcache_bytes(const knnssd_model_cfg *cfg);
  * stream). Launches a few set-up kernels (RoPE table, the workgroups' shares of each matrix) on the stream.
  * Two environment variables are read here, both for testing: KNNSSD_CHUNKED_PREFILL (any value: prompts go through
  * 16-row passes instead of the many-row prefill kernels) and KNNSSD_VERIFY_ATTN = mfma | valu (which of the two
- * attention kernels verification passes, and the draft steps of grouped-query models, use; the matrix-core one by default). Results stay within the tolerances either way; one context never mixes the two. */
+ * attention kernels verification passes, and the draft steps of grouped-query models, use; the matrix-core one by
+ * default). Results stay within the tolerances either way; all verification passes of one context use the same
+ * kernel, so a row's result never depends on how many rows share its pass. */
 int32_t knnssd_create(const knnssd_model_cfg *cfg, const knnssd_weights *w, void *kv_dev, size_t kv_bytes,
                       void *ws_dev, size_t ws_bytes, void *hip_stream, knnssd_ctx **out);
 int32_t knnssd_destroy(knnssd_ctx *ctx);
