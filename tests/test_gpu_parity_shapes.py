@@ -212,3 +212,44 @@ def test_verification_attention_kernels(kernel, gqa, plen, monkeypatch):
                 assert torch.equal(got, kept[r]), (kernel, gqa, n, r)
             kept[r] = got
     gpu.close()
+
+
+def test_tile_counts_of_three_five_and_six_per_workgroup():
+    """Shares of 33-48, 65-80 and 81-96 matrix rows per workgroup (3, 5 and 6 tiles of 16): three tiles run on three
+    of four tile lanes in one round; five or six take two rounds whose second keeps at most half of the lanes busy,
+    so the verification GEMM sums both rounds after its loop without a meeting in between. QKV has 48 rows per
+    workgroup here, gate/up 88, the LM head 79. Draft step, verification rows (also bit-identical across row counts)
+    and a generation against the oracle."""
+    shape = synth.small_shape("tiles356", n_blocks=2, d_model=256, n_heads=64, n_kv_heads=64, head_dim=64,
+                              d_ffn=11264, vocab=20000, max_seq=64)
+    w, orc, gpu = make_pair(shape, seed=41, std=0.03)
+    assert gpu.packed
+    prompt = synth.make_prompt(shape.vocab, 21, seed=3).tolist()
+    first_o, _, _ = O.prefill(orc, prompt)
+    first_g, _ = gpu.knnssd_prefill(prompt)
+    assert first_g == first_o
+    mask = np.array([0, 0, 1, 0], dtype=np.uint8)
+    gpu.knnssd_set_skipset(mask.tolist())
+    gpu.knnssd_draft_step(first_o, len(prompt))
+    row = orc.forward([first_o], len(prompt), mask)[0]
+    ok, err = logits_close(gpu.knnssd_get_logits(0).numpy(), row, shape)
+    assert ok, err
+    rows_in = [first_o] + synth.make_prompt(shape.vocab, 15, seed=9).tolist()
+    rows_o = orc.forward(rows_in, len(prompt), None)
+    kept = {}
+    for n in (16, 2, 1):
+        gpu.knnssd_prefill(prompt)
+        gpu.knnssd_verify(rows_in[:n], len(prompt))
+        for r in range(n):
+            got = gpu.knnssd_get_logits(r).clone()
+            ok, err = logits_close(got.numpy(), rows_o[r], shape)
+            assert ok, (n, r, err)
+            if r in kept:
+                assert torch.equal(got, kept[r]), (n, r)
+            kept[r] = got
+    orc2 = O.OracleModel(shape, w)
+    toks_o, st_o, rounds = O.ssd_generate(orc2, prompt, mask, 12, 4, 0.0)
+    gpu.knnssd_set_skipset(mask.tolist())
+    toks_g, st_g = gpu.knnssd_generate(prompt, 12, 4, 0.0)
+    assert toks_g == toks_o, [min(r.margins) for r in rounds if r.margins]
+    gpu.close()
