@@ -166,6 +166,23 @@ int32_t knnssd_set_skipset(knnssd_ctx *ctx, const uint8_t *mask_host);
 int32_t knnssd_knn_topk(knnssd_ctx *ctx, const float *queries_dev, int32_t n_queries, int32_t k,
                         int32_t *anchor_idx_out, float *cosine_out, int32_t *domain_out);
 
+/* The routing step for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc. Same scan and arg-max kernels as
+ * knnssd_select_skipset, no context: the per-anchor scores (the kernels' scratch buffer) live in a device array
+ * inside the library (KNNSSD_ROUTE_MAX_ANCHORS floats = 256 KB on every GPU the library runs on, held until the
+ * process ends); the call allocates and frees nothing and never waits for the GPU. Everything is enqueued on
+ * hip_stream (a hipStream_t of the CURRENT device); result_dev (device, int32[4]) receives, in stream order:
+ * [0] the arg-max anchor n* (lowest index on ties), [1] its label, [2] 1 if a zero-norm or non-finite query or
+ * anchor was met (then [0] = [1] = -1), [3] the bits of the fp32 score (v . a) / |a|. query_dev: fp32 [dim];
+ * anchors_dev: fp32 [n_anchors][dim]; labels_dev: int32 [n_anchors]; all device pointers, query and anchors 16-byte
+ * aligned; dim a multiple of 4. KNNSSD_ERANGE when n_anchors is not in [1, KNNSSD_ROUTE_MAX_ANCHORS], KNNSSD_ESHAPE
+ * for a bad dim, KNNSSD_EINVAL for null or misaligned pointers; nothing is enqueued on an error. All calls on one
+ * GPU share that GPU's array: calls whose kernels may overlap on one GPU (different streams, no ordering between
+ * them) race on it. */
+#define KNNSSD_ROUTE_MAX_ANCHORS 65536
+int32_t knnssd_route_static(const float *query_dev, const float *anchors_dev, const int32_t *labels_dev,
+                            int32_t n_anchors, int32_t dim, void *hip_stream, int32_t *result_dev);
+
 /* Anchor index n* and domain (Eq. 4-5) of the most recent routing on this context, whether it was made by
  * knnssd_select_skipset or inside knnssd_generate; both are -1 before the first routing. Either output
  * pointer may be NULL. Host-only, no device work. */

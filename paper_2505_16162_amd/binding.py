@@ -23,7 +23,7 @@ _DT = {"fp32": 0, "bf16": 1}
 EXPORTS = [
     "knnssd_workspace_bytes", "knnssd_kvcache_bytes", "knnssd_create", "knnssd_destroy",
     "knnssd_pack_supported", "knnssd_pack_matrix",
-    "knnssd_set_anchors", "knnssd_prefill", "knnssd_select_skipset", "knnssd_set_skipset", "knnssd_last_selection", "knnssd_knn_topk",
+    "knnssd_set_anchors", "knnssd_prefill", "knnssd_select_skipset", "knnssd_set_skipset", "knnssd_last_selection", "knnssd_knn_topk", "knnssd_route_static",
     "knnssd_draft_step", "knnssd_verify", "knnssd_generate", "knnssd_profile_pass", "knnssd_get_logits", "knnssd_read_kv",
     "knnssd_strerror",
 ]
@@ -100,6 +100,8 @@ def load_library() -> ctypes.CDLL:
     lib.knnssd_set_skipset.argtypes = [vp, vp]
     lib.knnssd_knn_topk.restype = i32
     lib.knnssd_knn_topk.argtypes = [vp, vp, i32, i32, vp, vp, vp]
+    lib.knnssd_route_static.restype = i32
+    lib.knnssd_route_static.argtypes = [vp, vp, vp, i32, i32, vp, vp]
     lib.knnssd_last_selection.restype = i32
     lib.knnssd_last_selection.argtypes = [vp, ctypes.POINTER(i32), ctypes.POINTER(i32)]
     lib.knnssd_draft_step.restype = i32
@@ -134,6 +136,16 @@ def make_cfg(shape, max_anchors: int = 0) -> ModelCfg:
 def _i32_array(values: Sequence[int]):
     arr = (ctypes.c_int32 * len(values))(*[int(v) for v in values])
     return arr
+
+
+def knnssd_route_static(query: torch.Tensor, anchors: torch.Tensor, labels: torch.Tensor, result: torch.Tensor,
+                        stream: Optional[torch.cuda.Stream] = None) -> None:
+    """Routing without a context or a workspace (argument marshalling only; the caller owns every tensor, result
+    included: int32[4] on the device, filled in stream order)."""
+    lib = load_library()
+    s = stream if stream is not None else torch.cuda.current_stream(query.device)
+    _check(lib.knnssd_route_static(query.data_ptr(), anchors.data_ptr(), labels.data_ptr(), anchors.shape[0], anchors.shape[1],
+                                   ctypes.c_void_p(s.cuda_stream), result.data_ptr()))
 
 
 class KnnSsd:

@@ -850,6 +850,53 @@ extern "C" int32_t knnssd_select_skipset(knnssd_ctx *ctx, const float *query_dev
     return KNNSSD_OK;
 }
 
+// ------------------------------------------------------------------------------------------
+// Routing for callers that cannot allocate. The scan's per-anchor scores (the one scratch buffer of the routing
+// kernels) live in a file-scope device array instead of the caller's workspace. `route_scratch` below is only the
+// host-side stand-in of that array: the device address comes from hipGetSymbolAddress, once per device, and host
+// code uses that address (never the array's name) wherever it needs the memory.
+// ------------------------------------------------------------------------------------------
+static __device__ __align__(256) float route_scratch[KNNSSD_ROUTE_MAX_ANCHORS];
+
+static const int ROUTE_MAX_DEVICES = 64;
+static float *g_route_scratch_dev[ROUTE_MAX_DEVICES];      // per device: its own copy of the array, at its own address
+
+// Address of the current device's copy of the scratch array (looked up on the first call made with that device
+// current; allocates nothing).
+static int32_t route_scratch_ptr(float **out) {
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= ROUTE_MAX_DEVICES) return KNNSSD_ERANGE;
+    if (!g_route_scratch_dev[dev]) {
+        float *p = nullptr;
+        HIP_TRY(hipGetSymbolAddress((void **)&p, HIP_SYMBOL(route_scratch)));
+        if (!p) return KNNSSD_EHIP;
+        g_route_scratch_dev[dev] = p;
+    }
+    *out = g_route_scratch_dev[dev];
+    return KNNSSD_OK;
+}
+
+extern "C" int32_t knnssd_route_static(const float *query_dev, const float *anchors_dev, const int32_t *labels_dev,
+                                       int32_t n_anchors, int32_t dim, void *hip_stream, int32_t *result_dev) {
+    if (!query_dev || !anchors_dev || !labels_dev || !result_dev) return KNNSSD_EINVAL;
+    if (((uintptr_t)query_dev | (uintptr_t)anchors_dev) & 15) return KNNSSD_EINVAL;
+    if ((uintptr_t)result_dev & 3) return KNNSSD_EINVAL;
+    if (dim < 4 || (dim & 3)) return KNNSSD_ESHAPE;                 // the scan reads anchors in 16-byte pieces
+    if (n_anchors <= 0 || n_anchors > KNNSSD_ROUTE_MAX_ANCHORS) return KNNSSD_ERANGE;
+    float *scores = nullptr;
+    KS_TRY(route_scratch_ptr(&scores));
+    hipStream_t s = (hipStream_t)hip_stream;
+    int wgs = (n_anchors + 3) / 4;
+    if (wgs > 4096) wgs = 4096;
+    // every score the arg-max reads is written by the scan of the same call, so nothing has to start at zero
+    hipLaunchKernelGGL(knn_scores_multi_kernel<1>, dim3(wgs), dim3(256), 0, s, query_dev, anchors_dev, n_anchors, dim, scores);
+    hipLaunchKernelGGL(knn_argmax_kernel, dim3(1), dim3(1024), 0, s, (const float *)scores, query_dev, labels_dev, n_anchors, dim,
+                       reinterpret_cast<KnnResult *>(result_dev));
+    HIP_TRY(hipGetLastError());
+    return KNNSSD_OK;
+}
+
 extern "C" int32_t knnssd_draft_step(knnssd_ctx *ctx, int32_t token_in, int32_t pos, int32_t *token_out,
                                      float *top1_prob_out) {
     if (!ctx || !token_out) return KNNSSD_EINVAL;

@@ -73,3 +73,22 @@ def test_create_rejects_buffers_smaller_than_the_size_queries(lib):
     assert lib.knnssd_create(ctypes.byref(cfg), ctypes.byref(w), fake, kv, fake, plain, None, ctypes.byref(h)) == -1
     assert lib.knnssd_create(ctypes.byref(cfg), ctypes.byref(w), fake, kv - 1, fake, packed, None, ctypes.byref(h)) == -1
     assert not h.value
+
+
+def test_route_static_checks_its_arguments_before_touching_the_device(lib):
+    """knnssd_route_static: every refusal below is decided on the host, in front of the first HIP call."""
+    fake = ctypes.c_void_p(0x100000)
+    odd = ctypes.c_void_p(0x100004)
+    f = lib.knnssd_route_static
+    assert f(None, fake, fake, 8, 256, None, fake) == -1
+    assert f(fake, None, fake, 8, 256, None, fake) == -1
+    assert f(fake, fake, None, 8, 256, None, fake) == -1
+    assert f(fake, fake, fake, 8, 256, None, None) == -1
+    assert f(odd, fake, fake, 8, 256, None, fake) == -1          # 16-byte alignment of query and anchors
+    assert f(fake, odd, fake, 8, 256, None, fake) == -1
+    assert f(fake, fake, fake, 8, 255, None, fake) == -2         # the scan reads 16-byte pieces of an anchor
+    assert f(fake, fake, fake, 8, 0, None, fake) == -2
+    assert f(fake, fake, fake, 0, 256, None, fake) == -3
+    assert f(fake, fake, fake, 65537, 256, None, fake) == -3     # beyond KNNSSD_ROUTE_MAX_ANCHORS
+    header = open(os.path.join(ROOT, "include", "knnssd.h")).read()
+    assert "#define KNNSSD_ROUTE_MAX_ANCHORS 65536" in header
