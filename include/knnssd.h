@@ -48,6 +48,11 @@ extern "C" {
 #define KNNSSD_FP32 0
 #define KNNSSD_BF16 1
 
+#define KNNSSD_PREFILL_AUTO 0
+#define KNNSSD_PREFILL_CHUNKED 1
+#define KNNSSD_ATTN_MFMA 0
+#define KNNSSD_ATTN_VALU 1
+
 #define KNNSSD_MAX_ROWS 16  /* rows one verification pass can carry: max_draft + 1 <= 16 */
 
 typedef struct knnssd_model_cfg {
@@ -60,6 +65,14 @@ typedef struct knnssd_model_cfg {
     int32_t kv_dtype;     /* KNNSSD_FP32 | KNNSSD_BF16 */
     int32_t weights_packed; /* 1: wqkv/wo/wgu/wdown/lm_head are in stream order (knnssd_pack_matrix) and the
                                tuned bf16 kernels run; 0: row-major, generic kernels. embed is always row-major. */
+    int32_t prefill_mode;   /* KNNSSD_PREFILL_AUTO: prompts go through the many-row prefill kernels where the shape
+                               fits them; KNNSSD_PREFILL_CHUNKED: through 16-row passes of the verification kernels.
+                               Only read with weights_packed = 1. */
+    int32_t verify_attn;    /* which split-KV attention kernel verification passes (and the draft steps of
+                               grouped-query models) use: KNNSSD_ATTN_MFMA (matrix cores, the default) or
+                               KNNSSD_ATTN_VALU (vector ALUs). One kernel per context, never chosen per pass, so a
+                               row's result does not depend on how many rows share its pass. Only read with
+                               weights_packed = 1. Results stay within the stated tolerances either way. */
 } knnssd_model_cfg;
 
 /* Device pointers to the model. The four per-block members are HOST arrays of
@@ -123,11 +136,7 @@ size_t knnssd_kvcache_bytes(const knnssd_model_cfg *cfg);
  * KNNSSD_EINVAL when either is smaller than the size queries above say for THIS cfg (the queries
  * depend on every field, weights_packed included). hip_stream is a hipStream_t (NULL = the null
  * stream). Launches a few set-up kernels (RoPE table, the workgroups' shares of each matrix) on the stream.
- * Two environment variables are read here, both for testing: KNNSSD_CHUNKED_PREFILL (any value: prompts go through
- * 16-row passes instead of the many-row prefill kernels) and KNNSSD_VERIFY_ATTN = mfma | valu (which of the two
- * attention kernels verification passes, and the draft steps of grouped-query models, use; the matrix-core one by
- * default). Results stay within the tolerances either way; all verification passes of one context use the same
- * kernel, so a row's result never depends on how many rows share its pass. */
+ * The library reads no environment variable: every switch is a cfg field. */
 int32_t knnssd_create(const knnssd_model_cfg *cfg, const knnssd_weights *w, void *kv_dev, size_t kv_bytes,
                       void *ws_dev, size_t ws_bytes, void *hip_stream, knnssd_ctx **out);
 int32_t knnssd_destroy(knnssd_ctx *ctx);

@@ -59,6 +59,8 @@ static bool cfg_valid(const knnssd_model_cfg *c) {
     if (c->weight_dtype != KNNSSD_FP32 && c->weight_dtype != KNNSSD_BF16) return false;
     if (c->kv_dtype != KNNSSD_FP32 && c->kv_dtype != KNNSSD_BF16) return false;
     if (!(c->rope_base > 0.f) || !(c->rms_eps >= 0.f)) return false;
+    if (c->prefill_mode != KNNSSD_PREFILL_AUTO && c->prefill_mode != KNNSSD_PREFILL_CHUNKED) return false;
+    if (c->verify_attn != KNNSSD_ATTN_MFMA && c->verify_attn != KNNSSD_ATTN_VALU) return false;
     return true;
 }
 
@@ -233,16 +235,11 @@ extern "C" int32_t knnssd_create(const knnssd_model_cfg *cfg, const knnssd_weigh
     c->prefilled = false; c->cache_len = 0;
     c->tuned = cfg->weights_packed != 0;     // stream-order weights <=> tuned kernels (checked above)
     c->tuned_verify = c->tuned;
-    c->tuned_prefill = c->tuned && prefill_tuned_ok(*cfg) && !getenv("KNNSSD_CHUNKED_PREFILL");
+    c->tuned_prefill = c->tuned && prefill_tuned_ok(*cfg) && cfg->prefill_mode == KNNSSD_PREFILL_AUTO;
     // Attention of the verification passes: the vector-ALU kernel walks a work item's (row, head) pairs one by one,
     // the matrix-core kernel takes 16 at a time. The latter is faster from two pairs on and 10 % slower at one; the
     // choice is per context (never per pass), so a row's result does not depend on how many rows share its pass.
-    // KNNSSD_VERIFY_ATTN = mfma | valu overrides it.
-    c->verify_attn_mfma = true;
-    if (const char *ev = getenv("KNNSSD_VERIFY_ATTN")) {
-        if (!strcmp(ev, "mfma")) c->verify_attn_mfma = true;
-        else if (!strcmp(ev, "valu")) c->verify_attn_mfma = false;
-    }
+    c->verify_attn_mfma = cfg->verify_attn == KNNSSD_ATTN_MFMA;
     if (c->tuned) {
         hipError_t ea = hipFuncSetAttribute((const void *)gemv_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, KS_MAX_DYN_LDS);
         if (ea == hipSuccess)

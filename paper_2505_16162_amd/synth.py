@@ -128,16 +128,63 @@ def _normal(shape, std, seed, device, dtype) -> torch.Tensor:
     return out
 
 
+def _s64(v: int) -> int:
+    """A 64-bit pattern as the signed integer torch's int64 holds."""
+    v &= (1 << 64) - 1
+    return v - (1 << 64) if v >= (1 << 63) else v
+
+
+def _mix64(x: torch.Tensor) -> torch.Tensor:
+    """The finaliser of the SplitMix64 generator on int64 tensors (wrapping products; the logical right shifts are
+    arithmetic shifts with the sign bits masked off). Integer work only: the same bits on every device."""
+    x = (x ^ ((x >> 30) & ((1 << 34) - 1))) * _s64(0xBF58476D1CE4E5B9)
+    x = (x ^ ((x >> 27) & ((1 << 37) - 1))) * _s64(0x94D049BB133111EB)
+    return x ^ ((x >> 31) & ((1 << 33) - 1))
+
+
+def _counter_normal(shape, std, seed, device, dtype) -> torch.Tensor:
+    """Approximately N(0, std^2), the SAME bytes whichever device draws them (torch's own generators differ between
+    host and GPU, so a tensor that both a host-side and a device-side consumer must regenerate independently comes
+    from here). Element i is a function of (seed, i) alone: two 64-bit hashes give eight 16-bit uniforms, whose sum
+    (Irwin-Hall, n = 8: Gaussian to within a kurtosis of -0.15, support +-4.9 sigma) is centred and scaled with one
+    fp32 multiplication, then rounded (nearest-even) to dtype. Every step is integer arithmetic or a single IEEE
+    operation, so host and device agree bit for bit."""
+    n = 1
+    for s in shape:
+        n *= s
+    out = torch.empty(shape, dtype=dtype, device=device)
+    flat = out.view(-1)
+    key = _s64((int(seed) * 0x9E3779B97F4A7C15) ^ 0xD1B54A32D192ED03)
+    scale = float(std) / (8.0 * (65536.0 ** 2 - 1.0) / 12.0) ** 0.5
+    chunk = 1 << 25
+    for lo in range(0, n, chunk):
+        hi = min(n, lo + chunk)
+        i = torch.arange(lo, hi, dtype=torch.int64, device=device)
+        total = torch.zeros(hi - lo, dtype=torch.int64, device=device)
+        for stream in (0, 1):
+            h = _mix64((2 * i + stream) * _s64(0x9E3779B97F4A7C15) + key)
+            for f in range(4):
+                total += (h >> (16 * f)) & 0xFFFF
+        flat[lo:hi] = ((total - 4 * 65535).to(torch.float32) * scale).to(dtype)
+    return out
+
+
 def make_weights(shape: ModelShape, seed: int = BASE_SEED, device="cpu",
-                 gains: str = "ones", std: float = 0.02) -> Dict:
+                 gains: str = "ones", std: float = 0.02, counter: bool = False) -> Dict:
     """Random-init decoder weights, all matrices row-major [out_features][in_features].
 
     gains="ones" gives unit RMSNorm gains (the benchmark recipe); gains="random"
     draws them from U(0.5, 1.5) so tests notice a missing or misplaced gain.
-    Norm gains are always fp32.
+    Norm gains are always fp32. counter=True draws the matrices from the counter-based
+    generator (_counter_normal): the same bytes on the host and on the GPU.
     """
     dt = _TORCH_DT[shape.weight_dtype]
     d, f = shape.d_model, shape.d_ffn
+    if counter:
+        assert gains == "ones", "the device-independent recipe uses unit gains"
+        _normal = _counter_normal       # noqa: F811 (same signature)
+    else:
+        _normal = globals()["_normal"]
 
     def gain(tid):
         if gains == "ones":
@@ -211,7 +258,7 @@ def make_sublayer_masks(n_blocks: int, n_domains: int, p_skip_attn: float, p_ski
 
 
 def make_anchors(dim: int, n_anchors: int, n_domains: int, sigma: float,
-                 seed: int = BASE_SEED + 3, device="cpu", clustered: bool = True):
+                 seed: int = BASE_SEED + 3, device="cpu", clustered: bool = True, counter: bool = False):
     """Anchor table (fp32 [N][D]), labels (int32 [N]) and domain centres (fp32 [n_domains][D]).
 
     clustered=True: centres ~ N(0, I); anchor n belongs to domain n % n_domains and
@@ -219,9 +266,13 @@ def make_anchors(dim: int, n_anchors: int, n_domains: int, sigma: float,
     clustered=False: anchors ~ N(0, I) and label n = n % n_domains (the tiny config:
     eight unrelated anchors, eight labels).
     """
-    g = _gen(seed, device)
-    centres = torch.randn((n_domains, dim), generator=g, device=device, dtype=torch.float32)
-    noise = torch.randn((n_anchors, dim), generator=g, device=device, dtype=torch.float32)
+    if counter:     # the same bytes on the host and on the GPU (see _counter_normal)
+        centres = _counter_normal((n_domains, dim), 1.0, seed * 7 + 1, device, torch.float32)
+        noise = _counter_normal((n_anchors, dim), 1.0, seed * 7 + 2, device, torch.float32)
+    else:
+        g = _gen(seed, device)
+        centres = torch.randn((n_domains, dim), generator=g, device=device, dtype=torch.float32)
+        noise = torch.randn((n_anchors, dim), generator=g, device=device, dtype=torch.float32)
     labels = (torch.arange(n_anchors, device=device) % n_domains).to(torch.int32)
     if clustered:
         anchors = centres[labels.long()] + sigma * noise

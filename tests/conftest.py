@@ -16,3 +16,18 @@ def pytest_configure(config):
 def has_gpu():
     import torch
     return torch.cuda.is_available()
+
+
+def pytest_terminal_summary(terminalreporter):
+    """GPU runs: the largest logit error each shape reached against the oracle (relative to the row's largest logit
+    on the bf16 path, absolute on the fp32 path), next to the bounds the tests enforce."""
+    try:
+        import gpu_common
+    except Exception:
+        return
+    if not gpu_common.ACHIEVED:
+        return
+    terminalreporter.write_line("achieved logit error per shape (bounds: fp32 abs %g, bf16 rel %g):" %
+                                (gpu_common.FP32_ABS_TIGHT, gpu_common.BF16_REL_TIGHT))
+    for name, err in sorted(gpu_common.ACHIEVED.items()):
+        terminalreporter.write_line("  %-24s %.3e" % (name, err))

@@ -129,6 +129,40 @@ def test_13b_properties_at_benchmark_size(llama13b):
 
 
 @pytest.mark.timeout(600)
+def test_13b_many_row_prefill_equals_16_row_passes(llama13b):
+    """The prompt prefill the benchmark runs (many-row kernels over 1008 of the 1024 rows) against the same prompt
+    sent through 16-row verification passes (cfg.prefill_mode = KNNSSD_PREFILL_CHUNKED), on the full 40-block model:
+    the two paths sum in different orders, so cached values may sit on neighbouring bf16 values and the divergence
+    grows with depth; keys, values, the last hidden vector and the first token's logits must stay within the
+    tolerances of the bf16 path. (The 16-row passes are the kernels every oracle comparison covers.)"""
+    wl, w, gpu, anchors, labels, masks = llama13b
+    shape = wl.shape
+    prompt = synth.make_prompt(shape.vocab, wl.prompt_len).tolist()
+    first_t, hidden_t = gpu.knnssd_prefill(prompt)
+    where = [(b, pos) for b in (0, 1, 20, 39) for pos in (0, 15, 16, 511, 1007, 1008, 1023)]
+    kv_t = {bp: gpu.knnssd_read_kv(*bp) for bp in where}
+    logits_t = gpu.knnssd_get_logits(15).clone()
+    print("second context: 16-row passes", flush=True)
+    gpu2 = binding.KnnSsd(shape, w, chunked_prefill=True)
+    first_c, hidden_c = gpu2.knnssd_prefill(prompt)
+    worst = 0.0
+    for bp in where:
+        for got, want in zip(kv_t[bp], gpu2.knnssd_read_kv(*bp)):
+            g, r = got.numpy().astype(np.float64), want.numpy().astype(np.float64)
+            # neighbouring bf16 values (2^-7 of the value), plus what the divergence of the inputs adds at depth
+            tol = np.abs(r) * 2.0 ** -7 + (2e-3 if bp[0] == 0 else 2e-2) * np.abs(r).max()
+            worst = max(worst, float((np.abs(g - r) / tol).max()))
+    print("largest cache difference / tolerance: %.3f" % worst, flush=True)
+    assert worst <= 1.0
+    ht, hc = hidden_t.cpu().numpy(), hidden_c.cpu().numpy()
+    assert np.abs(ht - hc).max() <= 2e-2 * np.abs(hc).max()
+    ok, err = logits_close(logits_t.numpy(), gpu2.knnssd_get_logits(15).numpy(), shape)
+    assert ok, err
+    assert first_t == first_c
+    gpu2.close()
+
+
+@pytest.mark.timeout(600)
 def test_qwen_widths_gqa_big_vocab_matches_oracle():
     """Qwen-2.5-14B-shaped widths (GQA 40/8, vocab 152064, FFN 13824) at reduced depth so that the oracle
     finishes in seconds; exercises the tile shapes of the 14B-shaped configuration, 9-row verification

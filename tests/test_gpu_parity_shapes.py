@@ -184,16 +184,15 @@ def test_fewer_rows_than_workgroups():
 @pytest.mark.parametrize("plen", [283, 250])
 @pytest.mark.parametrize("kernel", ["mfma", "valu"])
 @pytest.mark.parametrize("gqa", [False, True])
-def test_verification_attention_kernels(kernel, gqa, plen, monkeypatch):
+def test_verification_attention_kernels(kernel, gqa, plen):
     """Both split-KV attention kernels of the verification pass (matrix cores / vector ALUs; the library uses the first
-    unless KNNSSD_VERIFY_ATTN names the other) on a multi-head and a grouped-query shape: 1, 3, 9 and 16 rows behind
+    unless cfg.verify_attn names the other) on a multi-head and a grouped-query shape: 1, 3, 9 and 16 rows behind
     a prompt that spans two 256-position chunks (283 positions), or that ends just before the chunk boundary (250: the
     first rows of the pass see one chunk, the later ones two), logits against the oracle, and rows independent of the
     row count."""
-    monkeypatch.setenv("KNNSSD_VERIFY_ATTN", kernel)
     shape = synth.small_shape("va_gqa" if gqa else "va_mha", n_blocks=2, d_model=512, n_heads=8, n_kv_heads=2 if gqa else 8,
                               head_dim=64, d_ffn=1408, vocab=900, max_seq=320)
-    w, orc, gpu = make_pair(shape, seed=31, std=0.04)
+    w, orc, gpu = make_pair(shape, seed=31, std=0.04, verify_attn=kernel)
     prompt = synth.make_prompt(shape.vocab, plen, seed=2).tolist()
     first_o, _, _ = O.prefill(orc, prompt)
     first_g, _ = gpu.knnssd_prefill(prompt)
