@@ -142,13 +142,16 @@ int32_t knnssd_create(const knnssd_model_cfg *cfg, const knnssd_weights *w, void
 int32_t knnssd_destroy(knnssd_ctx *ctx);
 
 /* Anchor table for the KNN routing step (Sec. 4.1: anchors a_ij with their domain label i and
- * one stored skip set z*_i per domain). anchors_dev: fp32 [n_anchors][dim], dim must equal
- * d_model; labels_dev: int32 [n_anchors] in [0, n_domains); masks_host: uint8
- * [n_domains][2*n_blocks], copied. n_anchors <= cfg.max_anchors. */
-int32_t knnssd_set_anchors(knnssd_ctx *ctx, const float *anchors_dev, const int32_t *labels_dev,
-                           int32_t n_anchors, int32_t dim, const uint8_t *masks_host, int32_t n_domains);
+ * one stored skip set z*_i per domain). anchors_dev: [n_anchors][dim] in anchor_dtype (KNNSSD_FP32, or
+ * KNNSSD_BF16: half the bytes to scan; the values the caller stored ARE the anchors, products and sums stay
+ * fp32), 16-byte aligned, dim must equal d_model; labels_dev: int32 [n_anchors] in [0, n_domains); masks_host:
+ * uint8 [n_domains][mask_len], copied; mask_len must be 2*n_blocks (KNNSSD_ESHAPE otherwise: the table is read
+ * with that row length). n_anchors <= cfg.max_anchors. */
+int32_t knnssd_set_anchors(knnssd_ctx *ctx, const void *anchors_dev, int32_t anchor_dtype, const int32_t *labels_dev,
+                           int32_t n_anchors, int32_t dim, const uint8_t *masks_host, int32_t n_domains,
+                           int32_t mask_len);
 
-/* Prefill (Sec. 4.2 "extract its last hidden vector v from the model"): the full model over
+/* Prefill (Sec. 4.2: the routing query is the prompt's last hidden vector): the full model over
  * n prompt tokens at positions 0..n-1. Resets the KV cache length to n. Outputs: the first
  * generated token (host) and, if last_hidden_dev is not NULL, the final-RMSNorm hidden state of
  * the last prompt token (fp32 [d_model], device) - the vector the KNN step is queried with. */
@@ -199,7 +202,9 @@ int32_t knnssd_last_selection(const knnssd_ctx *ctx, int32_t *anchor_idx_out, in
 
 /* One draft step (Eq. 7): token_in at position pos through M(z) with the installed mask; only
  * retained attention sublayers read and write the KV cache. Returns the arg-max token (lowest
- * index on ties) and its softmax probability at temperature 1. pos must be < max_seq. */
+ * index on ties) and its softmax probability at temperature 1. pos must be < max_seq and at most one past the
+ * last position written so far (the prefill's and the accepted rows', plus the draft steps made since the last
+ * verification): KNNSSD_ERANGE otherwise, since attention would read entries nobody wrote. */
 int32_t knnssd_draft_step(knnssd_ctx *ctx, int32_t token_in, int32_t pos, int32_t *token_out,
                           float *top1_prob_out);
 
@@ -208,7 +213,9 @@ int32_t knnssd_draft_step(knnssd_ctx *ctx, int32_t token_in, int32_t pos, int32_
  * overwrites its KV entries at those positions; row i attends to positions 0..start_pos+i.
  * Greedy acceptance: *n_accepted_out = j, the number of leading drafts equal to the model's own
  * token; *next_token_out = the model's token after the accepted prefix; *new_cache_len_out =
- * start_pos + j + 1 (cache entries beyond it are dead: rollback is this counter). */
+ * start_pos + j + 1 (cache entries beyond it are dead: rollback is this counter). start_pos must not exceed the
+ * current cache length (KNNSSD_ERANGE): draft steps fill only the retained blocks' entries, so the full model
+ * can only continue from positions that a prefill or a verification wrote. */
 int32_t knnssd_verify(knnssd_ctx *ctx, const int32_t *tokens_host, int32_t n, int32_t start_pos,
                       int32_t *n_accepted_out, int32_t *next_token_out, int32_t *new_cache_len_out);
 

@@ -9,7 +9,7 @@
  * L = 2*n_blocks sublayers (attention and MLP counted separately); a mask
  * z in {0,1}^L marks the sublayers the draft model M(z) skips (z=1: the
  * sublayer is the identity on the residual stream). The full model is z = 0.
- * A KV cache is kept (App. C.1 "KV cache is used").
+ * A KV cache is kept (App. C.1, experimental setup).
  *
  * Arithmetic: everything is double precision. The only roundings are the ones
  * that are part of the data the two sides exchange: weights arrive already in

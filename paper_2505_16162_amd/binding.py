@@ -92,7 +92,7 @@ def load_library() -> ctypes.CDLL:
     lib.knnssd_destroy.restype = i32
     lib.knnssd_destroy.argtypes = [vp]
     lib.knnssd_set_anchors.restype = i32
-    lib.knnssd_set_anchors.argtypes = [vp, vp, vp, i32, i32, vp, i32]
+    lib.knnssd_set_anchors.argtypes = [vp, vp, i32, vp, i32, i32, vp, i32, i32]
     lib.knnssd_prefill.restype = i32
     lib.knnssd_prefill.argtypes = [vp, vp, i32, vp, ctypes.POINTER(i32)]
     lib.knnssd_select_skipset.restype = i32
@@ -240,12 +240,17 @@ class KnnSsd:
 
     # ---- the calls of the C ABI, same names -------------------------------------------------
     def knnssd_set_anchors(self, anchors: torch.Tensor, labels: torch.Tensor, masks: torch.Tensor):
-        self.anchors = anchors.to(self.device, torch.float32).contiguous()
+        """anchors: fp32 or bf16 [n][d_model] (stored as given: a bf16 table is scanned as bf16)."""
+        dt = torch.bfloat16 if anchors.dtype == torch.bfloat16 else torch.float32
+        self.anchors = anchors.to(self.device, dt).contiguous()
         self.labels = labels.to(self.device, torch.int32).contiguous()
         m = masks.to("cpu", torch.uint8).contiguous()
+        if m.dim() != 2:
+            raise ValueError("masks must be [n_domains][2*n_blocks]")
         self._masks_host = m
-        _check(self.lib.knnssd_set_anchors(self.h, self.anchors.data_ptr(), self.labels.data_ptr(),
-                                           self.anchors.shape[0], self.anchors.shape[1], m.data_ptr(), m.shape[0]))
+        _check(self.lib.knnssd_set_anchors(self.h, self.anchors.data_ptr(), _DT["bf16" if dt == torch.bfloat16 else "fp32"],
+                                           self.labels.data_ptr(), self.anchors.shape[0], self.anchors.shape[1],
+                                           m.data_ptr(), m.shape[0], m.shape[1]))
 
     def knnssd_prefill(self, tokens: Sequence[int], want_hidden: bool = True):
         toks = _i32_array(tokens)

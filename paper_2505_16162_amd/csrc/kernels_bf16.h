@@ -1047,10 +1047,10 @@ __global__ __launch_bounds__(NT) void embed_producer_kernel(GemmOp op, const Pas
 }
 
 // ------------------------------------------------------------------------------------------
-// Split-KV attention over the contiguous bf16 cache. Work item = (kv head, 128-position chunk,
-// group of ATT_PG (row, q-head) pairs). Wavefront w of the workgroup owns 16 positions of the
-// chunk and keeps their K and V fragments in registers (lane = (position, 8-dim slice)); the
-// eight wavefronts' (max, sum, weighted V) are merged in LDS and written as the chunk's partial.
+// Split-KV attention over the contiguous bf16 cache. Work item = (kv head, ATT_CHUNK = 256-position
+// chunk, group of ATT_PG (row, q-head) pairs). Wavefront w of the workgroup's 16 owns 16 positions of
+// the chunk and keeps their K and V fragments in registers (lane = (position, 8-dim slice)); the
+// sixteen wavefronts' (max, sum, weighted V) are merged in LDS and written as the chunk's partial.
 // ------------------------------------------------------------------------------------------
 struct AttnArgs {
     const float *q;          // [KS_MAX_ROWS][H*hd] rotated queries

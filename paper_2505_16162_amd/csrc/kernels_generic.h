@@ -324,8 +324,8 @@ __global__ __launch_bounds__(1024) void argmax_kernel(const PassCtl *ctl, const 
 // ------------------------------------------------------------------------------------------
 // KNN routing, Eq. 4: score_n = (v . a_n) / |a_n|  (|v| is a common positive factor), then arg-max
 // ------------------------------------------------------------------------------------------
-template <int Q>
-__global__ __launch_bounds__(256) void knn_scores_multi_kernel(const float *__restrict__ queries, const float *__restrict__ anchors,
+template <int Q, typename AT>
+__global__ __launch_bounds__(256) void knn_scores_multi_kernel(const float *__restrict__ queries, const AT *__restrict__ anchors,
                                                                int N, int D, float *scores);
 
 __global__ __launch_bounds__(1024) void knn_argmax_kernel(const float *scores, const float *query, const int32_t *labels,
@@ -386,36 +386,53 @@ struct KnnTopk {
     int32_t degenerate;   // 1: zero-norm / non-finite query or anchor met
 };
 
-template <int Q>
-__global__ __launch_bounds__(256) void knn_scores_multi_kernel(const float *__restrict__ queries, const float *__restrict__ anchors,
+// AT = float or bf16_t: the type the anchor table is stored in (queries, products and sums are fp32 either way). A lane's
+// 16-byte load covers EPL = 4 or 8 consecutive elements of the anchor.
+template <int Q, typename AT>
+__global__ __launch_bounds__(256) void knn_scores_multi_kernel(const float *__restrict__ queries, const AT *__restrict__ anchors,
                                                                int N, int D, float *scores /*[Q][N]*/) {
     typedef float f4 __attribute__((ext_vector_type(4)));
+    constexpr int EPL = 16 / (int)sizeof(AT);         // elements per lane and load
+    constexpr int BLK = 4 * 64 * EPL;                 // elements per block of four loads per lane
     const int lane = threadIdx.x & 63;
     const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int n_waves = (gridDim.x * blockDim.x) >> 6;
     for (int n = wave; n < N; n += n_waves) {
-        const float *a = anchors + (size_t)n * D;
+        const AT *a = anchors + (size_t)n * D;
         float dot[Q], nn = 0.f;
 #pragma unroll
         for (int q = 0; q < Q; ++q) dot[q] = 0.f;
-        for (int k0 = 0; k0 < D; k0 += 1024) {           // blocks of four 16-byte loads per lane, issued together
+        for (int k0 = 0; k0 < D; k0 += BLK) {            // blocks of four 16-byte loads per lane, issued together
             f4 av[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const int k = min(k0 + j * 256 + lane * 4, D - 4);           // clamped, masked below
+                const int k = min(k0 + (j * 64 + lane) * EPL, D - EPL);           // clamped, masked below
                 av[j] = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(a + k));
             }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const int k = k0 + j * 256 + lane * 4;
+                const int k = k0 + (j * 64 + lane) * EPL;
                 if (k < D) {
-                    nn = fmaf(av[j].x, av[j].x, nn); nn = fmaf(av[j].y, av[j].y, nn);
-                    nn = fmaf(av[j].z, av[j].z, nn); nn = fmaf(av[j].w, av[j].w, nn);
+                    float e[EPL];
+                    if constexpr (EPL == 4) {
+                        e[0] = av[j].x; e[1] = av[j].y; e[2] = av[j].z; e[3] = av[j].w;
+                    } else {
+#pragma unroll
+                        for (int w = 0; w < 4; ++w) {
+                            const unsigned int u = __float_as_uint(av[j][w]);
+                            e[2 * w] = __uint_as_float(u << 16); e[2 * w + 1] = __uint_as_float(u & 0xffff0000u);
+                        }
+                    }
+#pragma unroll
+                    for (int i = 0; i < EPL; ++i) nn = fmaf(e[i], e[i], nn);
 #pragma unroll
                     for (int q = 0; q < Q; ++q) {
-                        const float4 qv = *reinterpret_cast<const float4 *>(queries + (size_t)q * D + k);
-                        dot[q] = fmaf(av[j].x, qv.x, dot[q]); dot[q] = fmaf(av[j].y, qv.y, dot[q]);
-                        dot[q] = fmaf(av[j].z, qv.z, dot[q]); dot[q] = fmaf(av[j].w, qv.w, dot[q]);
+#pragma unroll
+                        for (int i4 = 0; i4 < EPL / 4; ++i4) {
+                            const float4 qv = *reinterpret_cast<const float4 *>(queries + (size_t)q * D + k + 4 * i4);
+                            dot[q] = fmaf(e[4 * i4], qv.x, dot[q]); dot[q] = fmaf(e[4 * i4 + 1], qv.y, dot[q]);
+                            dot[q] = fmaf(e[4 * i4 + 2], qv.z, dot[q]); dot[q] = fmaf(e[4 * i4 + 3], qv.w, dot[q]);
+                        }
                     }
                 }
             }

@@ -165,6 +165,10 @@ __global__ __launch_bounds__(VA_NT) void attn_partial_mfma_kernel(AttnArgs a, co
             for (int off = 1; off < 16; off <<= 1) ps += __shfl_xor(ps, off, 64);
             ls[q] = ps;
         }
+        // (the P tile is private to this wavefront: its stores above and its loads below are ordered by the in-order
+        // LDS pipeline of one wavefront; the barrier keeps the compiler from moving a load above a store of another
+        // lane's element and costs no instruction)
+        __builtin_amdgcn_wave_barrier();
         // O = P V: P back from LDS in operand layout (lane (kg, i): pair i, positions 32*ks2 + 8*kg .. +7); the value
         // operand of instruction t takes dimension DT*n + t of the lane's eight positions: the low (t even) or high
         // (t odd) halves of word t/2 of two neighbouring slots make one operand register

@@ -143,7 +143,8 @@ struct knnssd_ctx {
     std::vector<const float *> attn_norm, mlp_norm;
     std::vector<const void *> wqkv, wo, wgu, wdown;
     // anchors
-    const float *anchors;
+    const void *anchors;
+    int32_t anchor_dtype;             // KNNSSD_FP32 | KNNSSD_BF16
     const int32_t *labels;
     int32_t n_anchors, n_domains;
     std::vector<uint8_t> masks;       // [n_domains][2*n_blocks]
@@ -155,7 +156,8 @@ struct knnssd_ctx {
     bool verify_attn_mfma;  // verification passes run their split-KV attention on the matrix cores
     // tabulated workgroup splits of the five matrix shapes (tuned kernels)
     const WgSplit *split_qkv = nullptr, *split_o = nullptr, *split_gu = nullptr, *split_down = nullptr, *split_head = nullptr;
-    int32_t cache_len;
+    int32_t cache_len;        // positions whose K/V every block holds (prefill + accepted rows)
+    int32_t draft_len;        // positions a draft step may attend to: cache_len plus the drafts made since
     int32_t last_anchor = -1, last_domain = -1;   // most recent routing
     // pinned host staging for small read-backs
     int32_t *h_stage;
@@ -230,9 +232,9 @@ extern "C" int32_t knnssd_create(const knnssd_model_cfg *cfg, const knnssd_weigh
         c->wqkv.push_back(w->wqkv[b]); c->wo.push_back(w->wo[b]);
         c->wgu.push_back(w->wgu[b]); c->wdown.push_back(w->wdown[b]);
     }
-    c->anchors = nullptr; c->labels = nullptr; c->n_anchors = 0; c->n_domains = 0;
+    c->anchors = nullptr; c->anchor_dtype = KNNSSD_FP32; c->labels = nullptr; c->n_anchors = 0; c->n_domains = 0;
     c->draft_mask.assign((size_t)2 * nb, 0);
-    c->prefilled = false; c->cache_len = 0;
+    c->prefilled = false; c->cache_len = 0; c->draft_len = 0;
     c->tuned = cfg->weights_packed != 0;     // stream-order weights <=> tuned kernels (checked above)
     c->tuned_verify = c->tuned;
     c->tuned_prefill = c->tuned && prefill_tuned_ok(*cfg) && cfg->prefill_mode == KNNSSD_PREFILL_AUTO;
@@ -355,17 +357,20 @@ extern "C" int32_t knnssd_destroy(knnssd_ctx *ctx) {
     return KNNSSD_OK;
 }
 
-extern "C" int32_t knnssd_set_anchors(knnssd_ctx *ctx, const float *anchors_dev, const int32_t *labels_dev,
-                                      int32_t n_anchors, int32_t dim, const uint8_t *masks_host, int32_t n_domains) {
+extern "C" int32_t knnssd_set_anchors(knnssd_ctx *ctx, const void *anchors_dev, int32_t anchor_dtype, const int32_t *labels_dev,
+                                      int32_t n_anchors, int32_t dim, const uint8_t *masks_host, int32_t n_domains,
+                                      int32_t mask_len) {
     if (!ctx || !anchors_dev || !labels_dev || !masks_host) return KNNSSD_EINVAL;
+    if (anchor_dtype != KNNSSD_FP32 && anchor_dtype != KNNSSD_BF16) return KNNSSD_EINVAL;
     if (n_anchors <= 0 || n_domains <= 0) return KNNSSD_EINVAL;
     if (dim != ctx->cfg.d_model) return KNNSSD_ESHAPE;
+    if (mask_len != 2 * ctx->cfg.n_blocks) return KNNSSD_ESHAPE;     // one entry per sublayer
     if (n_anchors > ctx->cfg.max_anchors) return KNNSSD_ERANGE;
     if ((uintptr_t)anchors_dev & 15) return KNNSSD_EINVAL;
-    const size_t ml = (size_t)2 * ctx->cfg.n_blocks;
+    const size_t ml = (size_t)mask_len;
     for (size_t i = 0; i < ml * n_domains; ++i)
         if (masks_host[i] > 1) return KNNSSD_EINVAL;
-    ctx->anchors = anchors_dev; ctx->labels = labels_dev;
+    ctx->anchors = anchors_dev; ctx->anchor_dtype = anchor_dtype; ctx->labels = labels_dev;
     ctx->n_anchors = n_anchors; ctx->n_domains = n_domains;
     ctx->masks.assign(masks_host, masks_host + ml * n_domains);
     return KNNSSD_OK;
@@ -745,6 +750,7 @@ static int32_t prefill_impl(knnssd_ctx *c, const int32_t *tokens, int32_t n, flo
     }
     c->prefilled = true;
     c->cache_len = n;
+    c->draft_len = n;
     return KNNSSD_OK;
 }
 
@@ -762,13 +768,32 @@ extern "C" int32_t knnssd_prefill(knnssd_ctx *ctx, const int32_t *tokens_host, i
     return prefill_impl(ctx, tokens_host, n, last_hidden_dev, first_token_out);
 }
 
-static int32_t select_impl(knnssd_ctx *c, const float *query_dev, int32_t *idx_out, int32_t *dom_out) {
+// the scan of the anchor table for nq <= KNN_QMAX queries at once, in the table's storage type
+static void launch_scan(knnssd_ctx *c, const float *queries, int nq, float *scores) {
     const int N = c->n_anchors, D = c->cfg.d_model;
     int wgs = (N + 3) / 4;
     if (wgs > 4096) wgs = 4096;
+    const dim3 g(wgs), b(256);
+    if (c->anchor_dtype == KNNSSD_BF16) {
+        const bf16_t *a = (const bf16_t *)c->anchors;
+        if (nq == 1) hipLaunchKernelGGL((knn_scores_multi_kernel<1, bf16_t>), g, b, 0, c->stream, queries, a, N, D, scores);
+        else if (nq == 2) hipLaunchKernelGGL((knn_scores_multi_kernel<2, bf16_t>), g, b, 0, c->stream, queries, a, N, D, scores);
+        else if (nq == 3) hipLaunchKernelGGL((knn_scores_multi_kernel<3, bf16_t>), g, b, 0, c->stream, queries, a, N, D, scores);
+        else hipLaunchKernelGGL((knn_scores_multi_kernel<4, bf16_t>), g, b, 0, c->stream, queries, a, N, D, scores);
+    } else {
+        const float *a = (const float *)c->anchors;
+        if (nq == 1) hipLaunchKernelGGL((knn_scores_multi_kernel<1, float>), g, b, 0, c->stream, queries, a, N, D, scores);
+        else if (nq == 2) hipLaunchKernelGGL((knn_scores_multi_kernel<2, float>), g, b, 0, c->stream, queries, a, N, D, scores);
+        else if (nq == 3) hipLaunchKernelGGL((knn_scores_multi_kernel<3, float>), g, b, 0, c->stream, queries, a, N, D, scores);
+        else hipLaunchKernelGGL((knn_scores_multi_kernel<4, float>), g, b, 0, c->stream, queries, a, N, D, scores);
+    }
+}
+
+static int32_t select_impl(knnssd_ctx *c, const float *query_dev, int32_t *idx_out, int32_t *dom_out) {
+    const int N = c->n_anchors, D = c->cfg.d_model;
     float *scores = c->wsp<float>(c->L.knn_scores);
     KnnResult *res = c->wsp<KnnResult>(c->L.knn);
-    hipLaunchKernelGGL(knn_scores_multi_kernel<1>, dim3(wgs), dim3(256), 0, c->stream, query_dev, c->anchors, N, D, scores);
+    launch_scan(c, query_dev, 1, scores);
     hipLaunchKernelGGL(knn_argmax_kernel, dim3(1), dim3(1024), 0, c->stream, scores, query_dev, c->labels, N, D, res);
     HIP_TRY(hipGetLastError());
     KS_TRY(read_back(c, res, sizeof(KnnResult)));
@@ -793,15 +818,10 @@ extern "C" int32_t knnssd_knn_topk(knnssd_ctx *ctx, const float *queries_dev, in
     const int N = ctx->n_anchors, D = ctx->cfg.d_model;
     float *scores = ctx->wsp<float>(ctx->L.knn_scores);
     KnnTopk *res = ctx->wsp<KnnTopk>(ctx->L.knn_topk);
-    int wgs = (N + 3) / 4;
-    if (wgs > 4096) wgs = 4096;
     for (int q0 = 0; q0 < n_queries; q0 += KNN_QMAX) {
         const int nq = n_queries - q0 < KNN_QMAX ? n_queries - q0 : KNN_QMAX;
         const float *qp = queries_dev + (size_t)q0 * D;
-        if (nq == 1) hipLaunchKernelGGL(knn_scores_multi_kernel<1>, dim3(wgs), dim3(256), 0, ctx->stream, qp, ctx->anchors, N, D, scores);
-        else if (nq == 2) hipLaunchKernelGGL(knn_scores_multi_kernel<2>, dim3(wgs), dim3(256), 0, ctx->stream, qp, ctx->anchors, N, D, scores);
-        else if (nq == 3) hipLaunchKernelGGL(knn_scores_multi_kernel<3>, dim3(wgs), dim3(256), 0, ctx->stream, qp, ctx->anchors, N, D, scores);
-        else hipLaunchKernelGGL(knn_scores_multi_kernel<4>, dim3(wgs), dim3(256), 0, ctx->stream, qp, ctx->anchors, N, D, scores);
+        launch_scan(ctx, qp, nq, scores);
         int n_slices = N / 2048;                      // stage 1 slices per query: a few thousand scores each
         if (n_slices < 1) n_slices = 1;
         if (n_slices > 64) n_slices = 64;
@@ -887,7 +907,7 @@ extern "C" int32_t knnssd_route_static(const float *query_dev, const float *anch
     int wgs = (n_anchors + 3) / 4;
     if (wgs > 4096) wgs = 4096;
     // every score the arg-max reads is written by the scan of the same call, so nothing has to start at zero
-    hipLaunchKernelGGL(knn_scores_multi_kernel<1>, dim3(wgs), dim3(256), 0, s, query_dev, anchors_dev, n_anchors, dim, scores);
+    hipLaunchKernelGGL((knn_scores_multi_kernel<1, float>), dim3(wgs), dim3(256), 0, s, query_dev, anchors_dev, n_anchors, dim, scores);
     hipLaunchKernelGGL(knn_argmax_kernel, dim3(1), dim3(1024), 0, s, (const float *)scores, query_dev, labels_dev, n_anchors, dim,
                        reinterpret_cast<KnnResult *>(result_dev));
     HIP_TRY(hipGetLastError());
@@ -899,6 +919,7 @@ extern "C" int32_t knnssd_draft_step(knnssd_ctx *ctx, int32_t token_in, int32_t 
     if (!ctx || !token_out) return KNNSSD_EINVAL;
     if (!ctx->prefilled) return KNNSSD_ESTATE;
     if (pos < 0 || pos >= ctx->cfg.max_seq) return KNNSSD_ERANGE;
+    if (pos > ctx->draft_len) return KNNSSD_ERANGE;       // positions in between were never written
     if (token_in < 0 || token_in >= ctx->cfg.vocab) return KNNSSD_ERANGE;
     PassCtl *dr = ctx->wsp<PassCtl>(ctx->L.draft_ctl);
     KS_TRY(set_pass(ctx, dr, 1, 1, pos, 0, &token_in));
@@ -908,6 +929,7 @@ extern "C" int32_t knnssd_draft_step(knnssd_ctx *ctx, int32_t token_in, int32_t 
     memcpy(&hr, ctx->h_stage, sizeof(hr));
     *token_out = hr.tok[0];
     if (top1_prob_out) *top1_prob_out = hr.prob[0];
+    ctx->draft_len = pos + 1;
     return KNNSSD_OK;
 }
 
@@ -917,6 +939,7 @@ extern "C" int32_t knnssd_verify(knnssd_ctx *ctx, const int32_t *tokens_host, in
     if (!ctx->prefilled) return KNNSSD_ESTATE;
     if (n <= 0 || n > KS_MAX_ROWS) return KNNSSD_ERANGE;
     if (start_pos < 0 || start_pos + n > ctx->cfg.max_seq) return KNNSSD_ERANGE;
+    if (start_pos > ctx->cache_len) return KNNSSD_ERANGE;  // the full model's K/V in between were never written (drafts fill only retained blocks)
     KS_TRY(check_tokens(ctx, tokens_host, n));
     PassCtl *ver = ctx->wsp<PassCtl>(ctx->L.ver_ctl);
     KS_TRY(set_pass(ctx, ver, 1, n, start_pos, 0, tokens_host));
@@ -929,6 +952,7 @@ extern "C" int32_t knnssd_verify(knnssd_ctx *ctx, const int32_t *tokens_host, in
     *next_token_out = ctx->h_stage[1];
     if (new_cache_len_out) *new_cache_len_out = ctx->h_stage[2];
     ctx->cache_len = ctx->h_stage[2];
+    ctx->draft_len = ctx->cache_len;
     return KNNSSD_OK;
 }
 
@@ -1024,6 +1048,7 @@ extern "C" int32_t knnssd_generate(knnssd_ctx *ctx, const int32_t *prompt_host, 
     HIP_TRY(hipStreamSynchronize(s));
     *n_out = emitted;
     ctx->cache_len = hs.cache_len;
+    ctx->draft_len = hs.cache_len;
     if (stats) {
         memset(stats, 0, sizeof(*stats));
         stats->rounds = hs.rounds; stats->drafted = hs.drafted; stats->accepted = hs.accepted; stats->emitted = emitted;

@@ -27,7 +27,8 @@ def pytest_terminal_summary(terminalreporter):
         return
     if not gpu_common.ACHIEVED:
         return
-    terminalreporter.write_line("achieved logit error per shape (bounds: fp32 abs %g, bf16 rel %g):" %
-                                (gpu_common.FP32_ABS_TIGHT, gpu_common.BF16_REL_TIGHT))
+    terminalreporter.write_line("achieved logit error per shape (fp32 path: absolute; bf16 path: relative to the row's "
+                                "largest logit) and the bound enforced:")
     for name, err in sorted(gpu_common.ACHIEVED.items()):
-        terminalreporter.write_line("  %-24s %.3e" % (name, err))
+        m = gpu_common.MEASURED.get(name)
+        terminalreporter.write_line("  %-24s %.3e   bound %s" % (name, err, ("%.1e" % (10 * m)) if m else "default"))

@@ -49,6 +49,7 @@ def test_null_arguments_are_rejected_without_a_device(lib):
     assert lib.knnssd_create(None, None, None, 0, None, 0, None, ctypes.byref(h)) == -1
     assert lib.knnssd_destroy(None) == -1
     assert lib.knnssd_set_skipset(None, None) == -1
+    assert lib.knnssd_set_anchors(None, None, 0, None, 1, 256, None, 1, 8) == -1
     assert lib.knnssd_draft_step(None, 0, 0, None, None) == -1
     assert lib.knnssd_verify(None, None, 0, 0, None, None, None) == -1
     assert lib.knnssd_generate(None, None, 0, None, None, None, None, None) == -1

@@ -138,15 +138,31 @@ def test_error_paths_on_device():
     for bad in (lambda: gpu.knnssd_draft_step(wl.shape.vocab, 8), lambda: gpu.knnssd_draft_step(1, wl.shape.max_seq),
                 lambda: gpu.knnssd_verify([1] * 17, 8), lambda: gpu.knnssd_verify([1, 2], wl.shape.max_seq - 1),
                 lambda: gpu.knnssd_prefill([0] * (wl.shape.max_seq + 1)), lambda: gpu.knnssd_prefill([-1]),
-                lambda: gpu.knnssd_generate(prompt, wl.shape.max_seq, 4)):
+                lambda: gpu.knnssd_generate(prompt, wl.shape.max_seq, 4),
+                # positions nobody wrote: a draft step two past the prompt, a verification that starts past the cache
+                lambda: gpu.knnssd_draft_step(1, 10), lambda: gpu.knnssd_verify([1, 2], 9)):
         with pytest.raises(binding.KnnSsdError) as e:
             bad()
         assert e.value.code == -3
+    # ... while consecutive draft steps extend what the next one may attend to, and a verification resets it
+    gpu.knnssd_draft_step(1, 8)
+    gpu.knnssd_draft_step(2, 9)
+    with pytest.raises(binding.KnnSsdError) as e:
+        gpu.knnssd_verify([1, 2], 9)                       # the full model's cache still ends at 8
+    assert e.value.code == -3
+    j, nxt, new_len = gpu.knnssd_verify([1, 2, 3], 8)
+    with pytest.raises(binding.KnnSsdError) as e:
+        gpu.knnssd_draft_step(1, new_len + 1)
+    assert e.value.code == -3
+    gpu.knnssd_draft_step(1, new_len)
     anchors, labels, _ = synth.make_anchors(wl.shape.d_model, 8, 4, 1.0)
     masks = synth.make_block_masks(wl.shape.n_blocks, 4, 2)
     with pytest.raises(binding.KnnSsdError) as e:
         gpu.knnssd_set_anchors(torch.cat([anchors] * 3), torch.cat([labels] * 3), masks)   # 24 > max_anchors
     assert e.value.code == -3
+    with pytest.raises(binding.KnnSsdError) as e:
+        gpu.knnssd_set_anchors(anchors, labels, masks[:, :-2])     # a mask table of the wrong row length
+    assert e.value.code == -2
     zero = anchors.clone()
     zero[3] = 0
     gpu.knnssd_set_anchors(zero, labels, masks)

@@ -81,3 +81,41 @@ def test_gpu_topk_matches_oracle(n, k, nq):
     with pytest.raises(binding.KnnSsdError):
         gpu.knnssd_knn_topk(torch.zeros_like(queries), k)      # zero-norm query
     gpu.close()
+
+
+@pytest.mark.gpu
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_gpu_scan_of_a_large_table_matches_oracle(dtype):
+    """The regime in which the scan is bound by HBM: 100 000 anchors of dimension 5120 (2 GB in fp32, 1 GB in bf16),
+    the routing arg-max and the 8 nearest with their vote against the exhaustive oracle. A bf16 table is rounded
+    once by the caller; both sides then search the same rounded values."""
+    from paper_2505_16162_amd import binding
+    n, d, n_dom, k = 100_000, 5120, 5, 8
+    shape = synth.small_shape("knn_big", n_blocks=1, d_model=d, n_heads=40, n_kv_heads=40, head_dim=128, d_ffn=1024,
+                              vocab=1024, max_seq=64)
+    w = synth.make_weights(shape, device="cuda:0", seed=3)
+    gpu = binding.KnnSsd(shape, w, max_anchors=n)
+    print("anchors", flush=True)
+    # sigma 1: neighbouring scores are well apart (a table of near-duplicates would make the ranking a coin toss)
+    anchors, labels, centres = synth.make_anchors(d, n, n_dom, 1.0, seed=21, device="cuda:0")
+    if dtype == "bf16":
+        anchors = anchors.to(torch.bfloat16)
+    masks = synth.make_block_masks(shape.n_blocks, n_dom, 1, seed=6)
+    gpu.knnssd_set_anchors(anchors, labels, masks)
+    a64 = anchors.float().cpu().numpy()          # the stored values, exactly
+    lab = labels.cpu().numpy()
+    queries = torch.stack([synth.make_domain_query(centres.cpu(), i % n_dom, 1.0, seed=700 + i) for i in range(3)])
+    print("gpu", flush=True)
+    idx, cos, dom = gpu.knnssd_knn_topk(queries, k)
+    for i in range(3):
+        print("oracle query", i, flush=True)
+        order, scores, dvote = O.knn_topk_vote(queries[i].numpy(), a64, lab, k)
+        gaps = [scores[r] - scores[r + 1] for r in range(k - 1)]
+        assert idx[i] == order, (i, idx[i], order, min(gaps))
+        assert np.allclose(cos[i], scores, atol=3e-6)
+        assert dom[i] == dvote
+        n_star, d_star, mask, _ = O.knn_select(queries[i].numpy(), a64, lab, masks.numpy())
+        a1, d1, m1 = gpu.knnssd_select_skipset(queries[i])
+        assert (a1, d1, m1) == (n_star, d_star, mask.tolist())
+    gpu.close()
