@@ -52,6 +52,8 @@ extern "C" {
 #define KNNSSD_PREFILL_CHUNKED 1
 #define KNNSSD_ATTN_MFMA 0
 #define KNNSSD_ATTN_VALU 1
+#define KNNSSD_MERGE_FUSED 0
+#define KNNSSD_MERGE_SEPARATE 1
 
 #define KNNSSD_MAX_ROWS 16  /* rows one verification pass can carry: max_draft + 1 <= 16 */
 
@@ -73,6 +75,10 @@ typedef struct knnssd_model_cfg {
                                KNNSSD_ATTN_VALU (vector ALUs). One kernel per context, never chosen per pass, so a
                                row's result does not depend on how many rows share its pass. Only read with
                                weights_packed = 1. Results stay within the stated tolerances either way. */
+    int32_t attn_merge;     /* where a draft step merges the chunks of its split-KV attention: KNNSSD_MERGE_FUSED (the
+                               default: inside the output projection's kernel while the row sees at most 1536
+                               positions, in a launch of its own beyond) or KNNSSD_MERGE_SEPARATE (always in a launch
+                               of its own). Same arithmetic, same bits. Only read with weights_packed = 1. */
 } knnssd_model_cfg;
 
 /* Device pointers to the model. The four per-block members are HOST arrays of

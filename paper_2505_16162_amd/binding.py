@@ -35,7 +35,7 @@ class ModelCfg(ctypes.Structure):
                 ("vocab", ctypes.c_int32), ("max_seq", ctypes.c_int32), ("max_anchors", ctypes.c_int32),
                 ("rope_base", ctypes.c_float), ("rms_eps", ctypes.c_float),
                 ("weight_dtype", ctypes.c_int32), ("kv_dtype", ctypes.c_int32), ("weights_packed", ctypes.c_int32),
-                ("prefill_mode", ctypes.c_int32), ("verify_attn", ctypes.c_int32)]
+                ("prefill_mode", ctypes.c_int32), ("verify_attn", ctypes.c_int32), ("attn_merge", ctypes.c_int32)]
 
 
 class Weights(ctypes.Structure):
@@ -131,7 +131,7 @@ def _check(rc: int):
 def make_cfg(shape, max_anchors: int = 0) -> ModelCfg:
     return ModelCfg(shape.n_blocks, shape.d_model, shape.n_heads, shape.n_kv_heads, shape.head_dim, shape.d_ffn,
                     shape.vocab, shape.max_seq, max_anchors, float(shape.rope_base), float(shape.rms_eps),
-                    _DT[shape.weight_dtype], _DT[shape.kv_dtype], 0, 0, 0)
+                    _DT[shape.weight_dtype], _DT[shape.kv_dtype], 0, 0, 0, 0)
 
 
 def _i32_array(values: Sequence[int]):
@@ -153,7 +153,8 @@ class KnnSsd:
     """A library context over torch-owned device memory. Method names follow the C ABI."""
 
     def __init__(self, shape, weights: Dict, max_anchors: int = 0, device="cuda:0", stream: Optional[torch.cuda.Stream] = None,
-                 generic_kernels: bool = False, chunked_prefill: bool = False, verify_attn: str = "mfma"):
+                 generic_kernels: bool = False, chunked_prefill: bool = False, verify_attn: str = "mfma",
+                 separate_merge: bool = False):
         """generic_kernels: keep the matrices row-major and run the any-shape kernels (cfg.weights_packed = 0);
         chunked_prefill: cfg.prefill_mode = KNNSSD_PREFILL_CHUNKED; verify_attn: "mfma" | "valu" (cfg.verify_attn)."""
         self.lib = load_library()
@@ -179,6 +180,7 @@ class KnnSsd:
         self.cfg.weights_packed = 1 if self.packed else 0
         self.cfg.prefill_mode = 1 if chunked_prefill else 0
         self.cfg.verify_attn = {"mfma": 0, "valu": 1}[verify_attn]
+        self.cfg.attn_merge = 1 if separate_merge else 0
         # sizes of the caller-owned buffers, asked for with the final cfg (they depend on weights_packed)
         ws_bytes = self.lib.knnssd_workspace_bytes(ctypes.byref(self.cfg))
         kv_bytes = self.lib.knnssd_kvcache_bytes(ctypes.byref(self.cfg))

@@ -23,6 +23,9 @@ constexpr int NWV = NT / 64;   // wavefronts per workgroup
 constexpr int MAX_LROWS = 640; // most rows of one matrix a workgroup may own
 constexpr int ATT_CHUNK = NWV * 16;  // positions per split-KV work item (fixed: results do not depend on context length)
 constexpr int ATT_PG = 4;      // (row, head) pairs per attention work item
+constexpr int ATT_PAD = 4;     // a chunk's partial is [head_dim] weighted values, its maximum, its sum, 2 spare floats (16-byte rows)
+constexpr int ATT_FUSE_CHUNKS = 6;   // most chunks the O projection of a draft step merges in its own prologue (context <= 1536)
+constexpr int ATT_FUSE_GROUPS = 2;   // 4-float groups of the attention output a thread of that prologue merges (K <= 8192)
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
@@ -52,6 +55,10 @@ struct GemmOp {
     bf16_t *kv_block;         // this block's cache: [2][Hkv][max_seq][hd]
     const float *cos_t, *sin_t;
     int H, Hkv, hd, max_seq;
+    // OP_RESID behind the split-KV attention, draft step only (gemv_kernel<true>): the chunks' partials, merged in
+    // this kernel's prologue instead of by attn_combine_kernel; act_in is then unused
+    const float *att_part;    // [H][att_max_chunks][hd + ATT_PAD] (row 0 of the partial buffer)
+    int att_max_chunks;
     // OP_HEAD
     float *logits;            // [KS_MAX_ROWS][N]
     HeadPartial *head_part;   // [KS_MAX_ROWS][gridDim]
@@ -97,6 +104,25 @@ __device__ __forceinline__ u32x4 stream_load_x4(const void *p) {
     u32x4 v;
     asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(v) : "v"(p) : "memory");
     return v;
+}
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ u32x2 stream_load_x2(const void *p) {
+    u32x2 v;
+    asm volatile("global_load_dwordx2 %0, %1, off" : "=v"(v) : "v"(p) : "memory");
+    return v;
+}
+template <int KEEP>
+__device__ __forceinline__ void stream_wait_x2(u32x2 &r) {
+    asm volatile("s_waitcnt vmcnt(%1)" : "+v"(r) : "n"(KEEP) : "memory");
+}
+// twelve 16-byte pieces at once (the chunk partials of the fused attention merge)
+template <int KEEP>
+__device__ __forceinline__ void stream_wait_12(u32x4 (*x)[ATT_FUSE_CHUNKS]) {
+    static_assert(ATT_FUSE_GROUPS == 2 && ATT_FUSE_CHUNKS == 6, "twelve registers are named below");
+    asm volatile("s_waitcnt vmcnt(%12)"
+                 : "+v"(x[0][0]), "+v"(x[0][1]), "+v"(x[0][2]), "+v"(x[0][3]), "+v"(x[0][4]), "+v"(x[0][5]),
+                   "+v"(x[1][0]), "+v"(x[1][1]), "+v"(x[1][2]), "+v"(x[1][3]), "+v"(x[1][4]), "+v"(x[1][5])
+                 : "n"(KEEP) : "memory");
 }
 __device__ __forceinline__ float stream_load_f32(const float *p) {
     float v;
@@ -459,6 +485,9 @@ __global__ __launch_bounds__(NT, 1) void pack_matrix_kernel(GemmOp op, const bf1
 // loads per lane in flight), lane (kg, r) multiplies its 8 weights with x[32*step + 8*kg ..] from
 // LDS and keeps a private sum for row r; a tile ends with a 4-lane reduction over kg.
 // ------------------------------------------------------------------------------------------
+// ATT: the input vector is the attention output of this step, still in pieces: the prologue merges the split-KV
+// chunks' partials itself (what attn_combine_kernel does as a launch of its own), with exactly that kernel's arithmetic
+template <bool ATT>
 __device__ __forceinline__ void gemv_device(const GemmOp &op, const PassCtl *ctl, int wg, int nwg, char *lds) {
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int K = op.K;
@@ -468,10 +497,12 @@ __device__ __forceinline__ void gemv_device(const GemmOp &op, const PassCtl *ctl
     float *vals = reinterpret_cast<float *>(rowidx + MAX_LROWS);     // [MAX_LROWS]
     float *scratch = vals + MAX_LROWS;                               // [4*NWV + KS_MAX_ROWS]
     float *rstd_s = scratch + 4 * NWV;
+    float *ftab = rstd_s + KS_MAX_ROWS;                              // ATT: [H][ATT_FUSE_CHUNKS] chunk weights, then [H] sums
 
     // read through the scalar cache while that is still possible: after the first hand-placed load (whose memory
     // clobber the compiler must honour) this would become a vector load queued behind the whole weight batch
     const int active = ctl->active;
+    const int start = ATT ? ctl->start : 0;
     const WgSplit s = op.split[wg];                // tabulated; the row table is filled below
     const int R = s.R;
     const int tlane = wave >> s.ksshift, kpart = wave & (s.ksplit - 1);
@@ -484,8 +515,33 @@ __device__ __forceinline__ void gemv_device(const GemmOp &op, const PassCtl *ctl
     // all the small ones: the compiler's own counting would charge the weight loads to them.
     constexpr int XQ = 4;
     u32x4 xr[XQ];
+    constexpr int AG = ATT_FUSE_GROUPS, AC = ATT_FUSE_CHUNKS;
+    u32x4 orr[AG][AC];
+    u32x2 ml;
+    // chunks the step's row sees (positions 0..start); the host sends a step here only if they fit AC
+    const int n_chunks = ATT ? max(1, min(min((start + ATT_CHUNK) / ATT_CHUNK, op.att_max_chunks), AC)) : 0;
+    const int hd_shift = 31 - __builtin_clz(op.hd);             // head_dim is 64 or 128
+    if constexpr (!ATT) {
 #pragma unroll
-    for (int q = 0; q < XQ; ++q) xr[q] = stream_load_x4(op.act_in + min((tid + q * NT) * 4, K - 4));
+        for (int q = 0; q < XQ; ++q) xr[q] = stream_load_x4(op.act_in + min((tid + q * NT) * 4, K - 4));
+    } else {
+        // (Requesting the partials between two halves of the first weight batch instead, so that the weight stream does
+        // not start behind these thirteen loads, needs 23 registers more than a wavefront has.)
+        const int pstr = op.hd + ATT_PAD;
+        {   // thread (h, c) = (tid >> 3, tid & 7): maximum and sum of chunk c of head h (clamped; masked below)
+            const int h = min(tid >> 3, op.H - 1), c = min(tid & 7, n_chunks - 1);
+            ml = stream_load_x2(op.att_part + ((size_t)h * op.att_max_chunks + c) * pstr + op.hd);
+        }
+#pragma unroll
+        for (int q = 0; q < AG; ++q) {
+            // four consecutive dimensions of one head, from every chunk (chunks past the last re-read it: weight zero)
+            const int e = min((tid + q * NT) * 4, K - 4);
+            const int h = e >> hd_shift, dim = e & (op.hd - 1);
+            const float *pp = op.att_part + (size_t)h * op.att_max_chunks * pstr + dim;
+#pragma unroll
+            for (int c = 0; c < AC; ++c) orr[q][c] = stream_load_x4(pp + min(c, n_chunks - 1) * pstr);
+        }
+    }
     float sh[4];
     {
         // KS_NWG = 4 x 64 shares per token row; without a norm in front of this GEMM the loads read the split table
@@ -526,12 +582,55 @@ __device__ __forceinline__ void gemv_device(const GemmOp &op, const PassCtl *ctl
             shape.H = pinned_here(op.H); shape.Hkv = pinned_here(op.Hkv); shape.hd = pinned_here(op.hd);
             int n_first_unused;
             build_row_table<true>(shape, pinned_here(wg), rowidx, &n_first_unused);
-            stream_wait_pieces<8 + 6, XQ>(xr);          // the six small loads and the eight weight loads stay in flight
-            // (stores clamped like the loads: a duplicate writes the same value to the same place)
+            if constexpr (!ATT) {
+                stream_wait_pieces<8 + 6, XQ>(xr);          // the six small loads and the eight weight loads stay in flight
+                // (stores clamped like the loads: a duplicate writes the same value to the same place)
 #pragma unroll
-            for (int q = 0; q < XQ; ++q) *reinterpret_cast<u32x4 *>(xs + min((tid + q * NT) * 4, K - 4)) = xr[q];
-            for (int i = (tid + XQ * NT) * 4; i < K; i += NT * 4) *reinterpret_cast<float4 *>(xs + i) = *reinterpret_cast<const float4 *>(op.act_in + i);
-            __syncthreads();
+                for (int q = 0; q < XQ; ++q) *reinterpret_cast<u32x4 *>(xs + min((tid + q * NT) * 4, K - 4)) = xr[q];
+                for (int i = (tid + XQ * NT) * 4; i < K; i += NT * 4) *reinterpret_cast<float4 *>(xs + i) = *reinterpret_cast<const float4 *>(op.act_in + i);
+                __syncthreads();
+            } else {
+                // Merge of the chunks (the arithmetic of attn_combine_device, operation for operation): per head the
+                // largest chunk maximum M, the chunks' weights f_c = exp(m_c - M), the sum L = sum_c l_c f_c in chunk
+                // order; per element O = sum_c o_c f_c in chunk order, then O / L.
+                stream_wait_x2<8 + 6 + AG * AC>(ml);
+                {
+                    const int c = tid & 7, h = tid >> 3;
+                    const float m = (c < n_chunks) ? __uint_as_float(ml.x) : -INFINITY;
+                    float M = m;
+                    M = fmaxf(M, __shfl_xor(M, 1, 64)); M = fmaxf(M, __shfl_xor(M, 2, 64)); M = fmaxf(M, __shfl_xor(M, 4, 64));
+                    const float f = (c < n_chunks && m > -INFINITY) ? expf(m - M) : 0.f;
+                    const float lc = __uint_as_float(ml.y);
+                    float L = 0.f;
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) {
+                        const float fk = __shfl(f, (lane & ~7) + k, 64), lk = __shfl(lc, (lane & ~7) + k, 64);
+                        L = fmaf(lk, fk, L);
+                    }
+                    if (h < op.H) {
+                        if (c < AC) ftab[h * AC + c] = f;
+                        if (c == 0) ftab[op.H * AC + h] = L;
+                    }
+                }
+                __syncthreads();
+                stream_wait_12<8 + 6>(orr);
+#pragma unroll
+                for (int q = 0; q < AG; ++q) {
+                    const int e = min((tid + q * NT) * 4, K - 4);
+                    const int h = e >> hd_shift;
+                    float o0 = 0.f, o1 = 0.f, o2 = 0.f, o3 = 0.f;
+#pragma unroll
+                    for (int c = 0; c < AC; ++c) {
+                        const float f = ftab[h * AC + c];
+                        o0 = fmaf(__uint_as_float(orr[q][c].x), f, o0); o1 = fmaf(__uint_as_float(orr[q][c].y), f, o1);
+                        o2 = fmaf(__uint_as_float(orr[q][c].z), f, o2); o3 = fmaf(__uint_as_float(orr[q][c].w), f, o3);
+                    }
+                    const float L = ftab[op.H * AC + h];
+                    // (stores clamped like the loads: a duplicate writes the same value to the same place)
+                    *reinterpret_cast<float4 *>(xs + e) = make_float4(o0 / L, o1 / L, o2 / L, o3 / L);
+                }
+                __syncthreads();
+            }
         }
         float acc = 0.f;
         int u0 = 0;
@@ -595,13 +694,16 @@ __device__ __forceinline__ void gemv_device(const GemmOp &op, const PassCtl *ctl
     gemm_epilogue<false>(op, ctl, wg, nwg, R, s.n_first, rowidx, vals, 1, rstd_s, ctl->head_from, 1, scratch, xpre, gpre);
 }
 
+constexpr int ATT_FUSE_MAX_HEADS = 128;     // heads the fused merge's table in LDS holds
 __host__ __device__ inline size_t gemv_lds_bytes(int K) {
-    return (size_t)K * 4 + (size_t)MAX_LROWS * NWV * 4 + MAX_LROWS * 4 + MAX_LROWS * 4 + (4 * NWV + KS_MAX_ROWS) * 4;
+    return (size_t)K * 4 + (size_t)MAX_LROWS * NWV * 4 + MAX_LROWS * 4 + MAX_LROWS * 4 + (4 * NWV + KS_MAX_ROWS) * 4 +
+           (size_t)ATT_FUSE_MAX_HEADS * (ATT_FUSE_CHUNKS + 1) * 4;
 }
 
+template <bool ATT>
 __global__ __launch_bounds__(NT, 1) void gemv_kernel(GemmOp op, const PassCtl *ctl) {
     extern __shared__ __align__(16) char lds[];
-    gemv_device(op, ctl, blockIdx.x, gridDim.x, lds);
+    gemv_device<ATT>(op, ctl, blockIdx.x, gridDim.x, lds);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1055,7 +1157,7 @@ __global__ __launch_bounds__(NT) void embed_producer_kernel(GemmOp op, const Pas
 struct AttnArgs {
     const float *q;          // [KS_MAX_ROWS][H*hd] rotated queries
     const bf16_t *kv_block;  // [2][Hkv][max_seq][hd]
-    float *partial;          // [KS_MAX_ROWS*H][max_chunks][hd + 2]
+    float *partial;          // [KS_MAX_ROWS*H][max_chunks][hd + ATT_PAD]
     int H, Hkv, hd, max_seq, max_chunks;
     int group;               // H / Hkv
     // combine
@@ -1175,7 +1277,7 @@ __device__ __forceinline__ void attn_partial_device(const AttnArgs &a, const Pas
                 L = fmaf(rp[HD + 1], f, L);
                 O = fmaf(rp[dim], f, O);
             }
-            float *out = a.partial + (((size_t)m * a.H + h) * a.max_chunks + chunk) * (HD + 2);
+            float *out = a.partial + (((size_t)m * a.H + h) * a.max_chunks + chunk) * (HD + ATT_PAD);
             out[dim] = O;
             if (dim == 0) { out[HD] = M; out[HD + 1] = L; }
         }
@@ -1207,7 +1309,8 @@ __device__ __forceinline__ void attn_combine_device(const AttnArgs &a, const Pas
     for (int i = wg * NT + threadIdx.x; i < total; i += nwg * NT) {
         const int m = div_small(i, qd, inv_qd), c = i - m * qd, h = c >> hd_shift, dim = c & (hd - 1);
         const int n_chunks = (start + m + 1 + ATT_CHUNK - 1) / ATT_CHUNK;   // chunks row m can see
-        const float *pp = a.partial + ((size_t)m * a.H + h) * a.max_chunks * (hd + 2);
+        const int pstr = hd + ATT_PAD;
+        const float *pp = a.partial + ((size_t)m * a.H + h) * a.max_chunks * pstr;
         // Two passes in chunk order (largest maximum, then the weighted sums) over partials fetched CB chunks at a
         // time with unconditional loads before any of them is used: a load per loop iteration would cost one memory
         // round trip per chunk. The first CB chunks (all of them up to 2048 positions) are fetched once, for both
@@ -1216,7 +1319,7 @@ __device__ __forceinline__ void attn_combine_device(const AttnArgs &a, const Pas
         float mv0[CB], lv0[CB], ov0[CB];
 #pragma unroll
         for (int k = 0; k < CB; ++k) {
-            const float *cp = pp + (size_t)min(k, n_chunks - 1) * (hd + 2);
+            const float *cp = pp + (size_t)min(k, n_chunks - 1) * pstr;
             mv0[k] = cp[hd]; lv0[k] = cp[hd + 1]; ov0[k] = cp[dim];
         }
         float M = -INFINITY;
@@ -1225,7 +1328,7 @@ __device__ __forceinline__ void attn_combine_device(const AttnArgs &a, const Pas
         for (int base = CB; base < n_chunks; base += CB) {
             float mv[CB];
 #pragma unroll
-            for (int k = 0; k < CB; ++k) mv[k] = pp[(size_t)min(base + k, n_chunks - 1) * (hd + 2) + hd];
+            for (int k = 0; k < CB; ++k) mv[k] = pp[(size_t)min(base + k, n_chunks - 1) * pstr + hd];
 #pragma unroll
             for (int k = 0; k < CB; ++k) M = fmaxf(M, mv[k]);
         }
@@ -1240,7 +1343,7 @@ __device__ __forceinline__ void attn_combine_device(const AttnArgs &a, const Pas
             float mv[CB], lv[CB], ov[CB];
 #pragma unroll
             for (int k = 0; k < CB; ++k) {
-                const float *cp = pp + (size_t)min(base + k, n_chunks - 1) * (hd + 2);
+                const float *cp = pp + (size_t)min(base + k, n_chunks - 1) * pstr;
                 mv[k] = cp[hd]; lv[k] = cp[hd + 1]; ov[k] = cp[dim];
             }
 #pragma unroll

@@ -569,23 +569,26 @@ __global__ void round_begin_kernel(GenState *st, PassCtl *draft) {
     draft->tok[0] = st->x_last;
 }
 
-// host_flag (may be null): pinned host word that receives the pass's new `active` value, so the host can decide on
-// the next draft step after a plain stream synchronisation, without a copy
+// host_flag (may be null): two pinned host words: [0] receives the pass's new `active` value, so the host can decide on
+// the next draft step after a plain stream synchronisation, without a copy; [2] the drafts made so far in the round
 __global__ void draft_end_kernel(GenState *st, PassCtl *draft, const HeadResult *res, int32_t *host_flag) {
-    if (!draft->active) { if (host_flag) *host_flag = 0; return; }
+    if (!draft->active) { if (host_flag) { host_flag[0] = 0; host_flag[2] = st->k; } return; }
     int k = st->k;
     int d = res->tok[0]; float p = res->prob[0];
     st->drafts[k] = d; st->draft_p[k] = p;
     k += 1; st->k = k; st->draft_passes += 1;
     bool stop = (k >= st->kmax) || (st->conf_thr > 0.f && p < st->conf_thr);
     draft->active = stop ? 0 : 1;
-    if (host_flag) *host_flag = stop ? 0 : 1;
+    if (host_flag) { host_flag[0] = stop ? 0 : 1; host_flag[2] = k; }
     draft->tok[0] = d;
     draft->start = st->cache_len + k;
 }
 
-__global__ void verify_begin_kernel(const GenState *st, PassCtl *ver) {
-    ver->active = st->done ? 0 : 1;
+// expect_k >= 0: the pass was enqueued ahead of the host's knowledge, for a round of exactly expect_k drafts (its
+// launch arguments and activation layout are those of expect_k + 1 rows); it runs only if the draft did stop there
+__global__ void verify_begin_kernel(const GenState *st, const PassCtl *draft, PassCtl *ver, int expect_k) {
+    const bool as_expected = expect_k < 0 || (draft->active == 0 && st->k == expect_k);
+    ver->active = (st->done || !as_expected) ? 0 : 1;
     ver->n_rows = st->k + 1; ver->start = st->cache_len; ver->head_from = 0;
     ver->tok[0] = st->x_last;
     for (int i = 0; i < st->k; ++i) ver->tok[i + 1] = st->drafts[i];
@@ -594,8 +597,10 @@ __global__ void verify_begin_kernel(const GenState *st, PassCtl *ver) {
 // Greedy acceptance and rollback: keep the leading drafts that equal the full model's own
 // token, emit the model's next token after them, move the cache length behind the last kept row.
 // host_emitted (may be null): pinned host word that receives the new count of emitted tokens
-__global__ void accept_kernel(GenState *st, const HeadResult *res, int32_t *out_tokens, int32_t *host_emitted) {
-    if (st->done) { if (host_emitted) *host_emitted = st->emitted; return; }
+// ver: the pass whose result this is; a pass that did not run (enqueued ahead for a draft count that did not come
+// true) leaves the state alone
+__global__ void accept_kernel(GenState *st, const PassCtl *ver, const HeadResult *res, int32_t *out_tokens, int32_t *host_emitted) {
+    if (st->done || !ver->active) { if (host_emitted) *host_emitted = st->emitted; return; }
     int k = st->k, j = 0;
     while (j < k && st->drafts[j] == res->tok[j]) ++j;
     int e = st->emitted;

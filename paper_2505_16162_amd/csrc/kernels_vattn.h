@@ -227,7 +227,7 @@ __global__ __launch_bounds__(VA_NT) void attn_partial_mfma_kernel(AttnArgs a, co
                 L = fmaf(rp[HD + 1], f, L);
                 O = fmaf(rp[dim], f, O);
             }
-            float *out = a.partial + (((size_t)m * a.H + h) * a.max_chunks + chunk) * (HD + 2);
+            float *out = a.partial + (((size_t)m * a.H + h) * a.max_chunks + chunk) * (HD + ATT_PAD);
             out[dim] = O;
             if (dim == 0) { out[HD] = M; out[HD + 1] = L; }
         }

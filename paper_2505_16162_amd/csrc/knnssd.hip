@@ -61,6 +61,7 @@ static bool cfg_valid(const knnssd_model_cfg *c) {
     if (!(c->rope_base > 0.f) || !(c->rms_eps >= 0.f)) return false;
     if (c->prefill_mode != KNNSSD_PREFILL_AUTO && c->prefill_mode != KNNSSD_PREFILL_CHUNKED) return false;
     if (c->verify_attn != KNNSSD_ATTN_MFMA && c->verify_attn != KNNSSD_ATTN_VALU) return false;
+    if (c->attn_merge != KNNSSD_MERGE_FUSED && c->attn_merge != KNNSSD_MERGE_SEPARATE) return false;
     return true;
 }
 
@@ -109,7 +110,7 @@ static WsLayout ws_layout(const knnssd_model_cfg *c) {
         L.planes_u = take(plane_image_elems((size_t)c->d_ffn) * 2);
         L.ss = take((size_t)KS_NWG * R * 4);
         L.head_part = take(R * (size_t)KS_NWG * sizeof(HeadPartial));
-        L.attn_part = take(R * c->n_heads * max_chunks * (c->head_dim + 2) * 4);
+        L.attn_part = take(R * c->n_heads * max_chunks * (c->head_dim + ATT_PAD) * 4);
         L.split_tab = take((size_t)5 * KS_NWG * sizeof(WgSplit));
         if (c->weights_packed) {
             const size_t tt = (((size_t)c->max_seq + 15) / 16 + 15) / 16 * 16, rows = tt * 16;
@@ -243,7 +244,9 @@ extern "C" int32_t knnssd_create(const knnssd_model_cfg *cfg, const knnssd_weigh
     // choice is per context (never per pass), so a row's result does not depend on how many rows share its pass.
     c->verify_attn_mfma = cfg->verify_attn == KNNSSD_ATTN_MFMA;
     if (c->tuned) {
-        hipError_t ea = hipFuncSetAttribute((const void *)gemv_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, KS_MAX_DYN_LDS);
+        hipError_t ea = hipFuncSetAttribute((const void *)gemv_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, KS_MAX_DYN_LDS);
+        if (ea == hipSuccess)
+            ea = hipFuncSetAttribute((const void *)gemv_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, KS_MAX_DYN_LDS);
         if (ea == hipSuccess)
             ea = hipFuncSetAttribute((const void *)gemm_mfma_kernel<false, false>, hipFuncAttributeMaxDynamicSharedMemorySize, KS_MAX_DYN_LDS);
         if (ea == hipSuccess)
@@ -473,7 +476,8 @@ static const float *next_gain(const knnssd_ctx *c, const uint8_t *mask, int afte
 // One pass with the tuned bf16 kernels. rows1 = true: a draft step (one row, vector-ALU GEMV, fp32
 // activations); false: verification / prefill (up to 16 rows on the matrix cores, activations as
 // three bf16 planes). want_head = false skips the LM head (prefill chunks before the last).
-static int32_t run_pass_bf16(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, bool rows1, bool want_head, int n_rows) {
+// start: the position of the pass's first row as the host knows it (the control block will hold the same number).
+static int32_t run_pass_bf16(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, bool rows1, bool want_head, int n_rows, int start) {
     const knnssd_model_cfg &g = c->cfg;
     const int d = g.d_model, H = g.n_heads, Hkv = g.n_kv_heads, hd = g.head_dim, F = g.d_ffn;
     const int qd = H * hd, qkvd = (H + 2 * Hkv) * hd;
@@ -502,7 +506,8 @@ static int32_t run_pass_bf16(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, b
         return kc_of(OP_HEAD, g.vocab, d);
     };
     auto launch = [&](const GemmOp &op) {
-        if (rows1) hipLaunchKernelGGL(gemv_kernel, dim3(KS_NWG), dim3(NT), gemv_lds_bytes(op.K), s, op, ctl);
+        if (rows1 && op.att_part) hipLaunchKernelGGL(gemv_kernel<true>, dim3(KS_NWG), dim3(NT), gemv_lds_bytes(op.K), s, op, ctl);
+        else if (rows1) hipLaunchKernelGGL(gemv_kernel<false>, dim3(KS_NWG), dim3(NT), gemv_lds_bytes(op.K), s, op, ctl);
         else {
             GemmOp v = op;
             v.max_rows = max_rows_of(v.type, v.N);
@@ -549,6 +554,11 @@ static int32_t run_pass_bf16(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, b
     aa.q = qrot; aa.partial = c->wsp<float>(c->L.attn_part); aa.H = H; aa.Hkv = Hkv; aa.hd = hd; aa.max_seq = g.max_seq; aa.group = H / Hkv;
     aa.max_chunks = (g.max_seq + ATT_CHUNK - 1) / ATT_CHUNK; aa.act_out = att; aa.planes_out = planes_att;
     aa.n_rows = n_rows; aa.out_kc = kc_of(OP_RESID, d, qd);
+    // Draft steps whose row sees at most ATT_FUSE_CHUNKS chunks: the O projection merges the chunks' partials in its own
+    // prologue (gemv_kernel<true>) and the merge launch is dropped. Longer contexts, wider models and verification
+    // passes keep attn_combine_kernel.
+    const bool fuse_merge = rows1 && c->cfg.attn_merge == KNNSSD_MERGE_FUSED && start + 1 <= ATT_FUSE_CHUNKS * ATT_CHUNK &&
+                            qd <= ATT_FUSE_GROUPS * NT * 4 && H <= ATT_FUSE_MAX_HEADS;
     for (int b = 0; b < g.n_blocks; ++b) {
         bf16_t *kvb = (bf16_t *)(c->kv + (size_t)b * c->kv_block_bytes);
         if (!(mask && mask[2 * b])) {
@@ -565,13 +575,14 @@ static int32_t run_pass_bf16(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, b
                 else hipLaunchKernelGGL((attn_partial_mfma_kernel<64>), dim3(2 * KS_NWG), dim3(VA_NT), vattn_lds_bytes<64>(), s, aa, ctl);
             } else if (hd == 128) hipLaunchKernelGGL((attn_partial_kernel<128>), dim3(KS_NWG), dim3(NT), attn_lds_bytes(128), s, aa, ctl);
             else hipLaunchKernelGGL((attn_partial_kernel<64>), dim3(KS_NWG), dim3(NT), attn_lds_bytes(64), s, aa, ctl);
-            if (!others) {
+            if (!others || fuse_merge) {
             } else if (rows1) hipLaunchKernelGGL((attn_combine_kernel<false>), dim3(16), dim3(NT), 0, s, aa, ctl);
             else hipLaunchKernelGGL((attn_combine_kernel<true>), dim3(64), dim3(NT), 0, s, aa, ctl);
             GemmOp r = base;
             r.type = OP_RESID; r.W = (const bf16_t *)c->wo[b]; r.N = d; r.K = qd; r.act_in = att; r.planes_in = planes_att;
             r.ss_in = nullptr; r.x = x; r.gain_next = next_gain(c, mask, 2 * b); r.act_out = act_d; r.planes_out = planes_d;
             r.ss_out = ss; r.split = c->split_o; r.out_kc = kc_next(2 * b);
+            if (fuse_merge) { r.att_part = aa.partial; r.att_max_chunks = aa.max_chunks; }
             launch(r);
         }
         if (!(mask && mask[2 * b + 1])) {
@@ -601,11 +612,11 @@ static int32_t run_pass_bf16(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, b
 
 // mr: 1 for a draft step, KS_MAX_ROWS for verification / prefill; n_rows: the rows the control block will hold when
 // the pass runs (the host always knows the count, the device fills in the contents)
-static int32_t run_pass(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, int mr, int n_rows, bool want_head = true) {
+static int32_t run_pass(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, int mr, int n_rows, int start, bool want_head = true) {
     const bool wb = c->cfg.weight_dtype == KNNSSD_BF16, kb = c->cfg.kv_dtype == KNNSSD_BF16;
     if (n_rows < 1 || n_rows > mr) return KNNSSD_ERANGE;
-    if (mr == 1 && c->tuned) return run_pass_bf16(c, ctl, mask, true, true, 1);
-    if (mr != 1 && c->tuned_verify) return run_pass_bf16(c, ctl, mask, false, want_head, n_rows);
+    if (mr == 1 && c->tuned) return run_pass_bf16(c, ctl, mask, true, true, 1, start);
+    if (mr != 1 && c->tuned_verify) return run_pass_bf16(c, ctl, mask, false, want_head, n_rows, start);
     if (mr == 1) {
         if (wb && kb) return run_pass_t<bf16_t, bf16_t, 1>(c, ctl, mask);
         if (wb && !kb) return run_pass_t<bf16_t, float, 1>(c, ctl, mask);
@@ -725,7 +736,7 @@ static int32_t prefill_impl(knnssd_ctx *c, const int32_t *tokens, int32_t n, flo
         bool last = s + rows >= n;
         KS_TRY(set_pass(c, ver, 1, rows, s, last ? rows - 1 : rows, tokens + s));
         c->in_prefill = true;
-        int32_t rc_pass = run_pass(c, ver, nullptr, KS_MAX_ROWS, rows, last);
+        int32_t rc_pass = run_pass(c, ver, nullptr, KS_MAX_ROWS, rows, s, last);
         c->in_prefill = false;
         KS_TRY(rc_pass);
         if (last) {
@@ -923,7 +934,7 @@ extern "C" int32_t knnssd_draft_step(knnssd_ctx *ctx, int32_t token_in, int32_t 
     if (token_in < 0 || token_in >= ctx->cfg.vocab) return KNNSSD_ERANGE;
     PassCtl *dr = ctx->wsp<PassCtl>(ctx->L.draft_ctl);
     KS_TRY(set_pass(ctx, dr, 1, 1, pos, 0, &token_in));
-    KS_TRY(run_pass(ctx, dr, ctx->draft_mask.data(), 1, 1));
+    KS_TRY(run_pass(ctx, dr, ctx->draft_mask.data(), 1, 1, pos));
     KS_TRY(read_back(ctx, ctx->wsp<HeadResult>(ctx->L.head), sizeof(HeadResult)));
     HeadResult hr;
     memcpy(&hr, ctx->h_stage, sizeof(hr));
@@ -943,7 +954,7 @@ extern "C" int32_t knnssd_verify(knnssd_ctx *ctx, const int32_t *tokens_host, in
     KS_TRY(check_tokens(ctx, tokens_host, n));
     PassCtl *ver = ctx->wsp<PassCtl>(ctx->L.ver_ctl);
     KS_TRY(set_pass(ctx, ver, 1, n, start_pos, 0, tokens_host));
-    KS_TRY(run_pass(ctx, ver, nullptr, KS_MAX_ROWS, n));
+    KS_TRY(run_pass(ctx, ver, nullptr, KS_MAX_ROWS, n, start_pos));
     int32_t *out3 = ctx->wsp<int32_t>(ctx->L.out3);
     hipLaunchKernelGGL(verify_accept_kernel, dim3(1), dim3(1), 0, ctx->stream, ver, ctx->wsp<HeadResult>(ctx->L.head), out3);
     HIP_TRY(hipGetLastError());
@@ -1010,32 +1021,62 @@ extern "C" int32_t knnssd_generate(knnssd_ctx *ctx, const int32_t *prompt_host, 
     std::vector<size_t> round_ev;  // triples of event indices
     bool done = gen->max_new <= 1;
     int32_t emitted_host = 1;     // the host mirrors the round control far enough to know each pass's row count
+    // Where the draft count of a round is decided on the device (confidence stop), the host would have to wait after
+    // every draft step before it can enqueue the next pass, and the GPU idles meanwhile. Instead it predicts that the
+    // round stops where the last one did and enqueues the verification pass for that count right behind the draft
+    // step; the pass runs only if the prediction came true (verify_begin_kernel), otherwise its kernels return at
+    // once and the host carries on step by step. Without a threshold the count is known and nothing is waited for.
+    int pred_k = 1;
+    volatile int32_t *flags = (volatile int32_t *)ctx->h_stage + 512;   // [0] draft goes on, [1] emitted, [2] drafts made
     while (!done) {
         hipLaunchKernelGGL(round_begin_kernel, dim3(1), dim3(1), 0, s, st, dr);
-        size_t ea = ev++;
+        size_t ea = ev++, eb = ev++, ec = ev++;
         KS_TRY(mark(ctx, ea));
         int kmax = gen->max_new - emitted_host - 1;
         if (kmax > gen->max_draft) kmax = gen->max_draft;
         int k_host = 0;
+        const int cache_len_host = n_prompt + emitted_host - 1;     // every emitted token but the last is in the cache
+        bool verified = false;        // the round's verification pass has been enqueued for the right draft count
+        bool stepwise = false;        // a prediction failed in this round: wait after every step from here on
+        auto enqueue_verify = [&](int k, int expect_k) -> int32_t {
+            hipLaunchKernelGGL(verify_begin_kernel, dim3(1), dim3(1), 0, s, st, dr, ver, expect_k);
+            KS_TRY(run_pass(ctx, ver, nullptr, KS_MAX_ROWS, k + 1, cache_len_host));
+            hipLaunchKernelGGL(accept_kernel, dim3(1), dim3(1), 0, s, st, ver, head, out_dev, ctx->d_flags + 1);
+            KS_TRY(mark(ctx, ec));
+            return KNNSSD_OK;
+        };
         for (int i = 0; i < kmax; ++i) {
-            KS_TRY(run_pass(ctx, dr, ctx->draft_mask.data(), 1, 1));
+            KS_TRY(run_pass(ctx, dr, ctx->draft_mask.data(), 1, 1, cache_len_host + i));
             hipLaunchKernelGGL(draft_end_kernel, dim3(1), dim3(1), 0, s, st, dr, head, ctx->d_flags);
             ++n_draft_passes; ++k_host;
-            // the host decides whether to enqueue another draft pass
+            const bool last = k_host == kmax;                  // the round ends here whatever the confidence is
+            if (!(gen->conf_threshold > 0.f)) continue;        // no stop rule: kmax drafts, nothing to wait for
+            if (stepwise && last) break;                       // every earlier step was seen to go on: the count is known
+            if (!stepwise && k_host < pred_k && !last) continue;   // predicted to go on; a pass enqueued in vain returns at once
+            const int expected = k_host;
+            if (!stepwise) {                                   // predicted (or bound) to stop here: verification goes out ahead
+                KS_TRY(mark(ctx, eb));
+                KS_TRY(enqueue_verify(expected, expected));
+            }
             HIP_TRY(hipStreamSynchronize(s));
-            if (!((volatile int32_t *)ctx->h_stage)[512]) break;
+            if (!flags[0]) {                                   // the draft has stopped, after flags[2] steps
+                const int made = flags[2];
+                n_draft_passes -= k_host - made;               // steps enqueued beyond the stop did not run
+                k_host = made;
+                verified = !stepwise && made == expected;
+                break;
+            }
+            stepwise = true;                                   // it goes on: the pass enqueued ahead did not run
         }
-        size_t eb = ev++;
-        KS_TRY(mark(ctx, eb));
-        hipLaunchKernelGGL(verify_begin_kernel, dim3(1), dim3(1), 0, s, st, ver);
-        KS_TRY(run_pass(ctx, ver, nullptr, KS_MAX_ROWS, k_host + 1));
-        hipLaunchKernelGGL(accept_kernel, dim3(1), dim3(1), 0, s, st, head, out_dev, ctx->d_flags + 1);
+        pred_k = k_host > 0 ? k_host : 1;
+        if (!verified) {
+            KS_TRY(mark(ctx, eb));
+            KS_TRY(enqueue_verify(k_host, -1));
+        }
         ++n_verify_passes;
-        size_t ec = ev++;
-        KS_TRY(mark(ctx, ec));
         round_ev.push_back(ea); round_ev.push_back(eb); round_ev.push_back(ec);
         HIP_TRY(hipStreamSynchronize(s));
-        emitted_host = ((volatile int32_t *)ctx->h_stage)[513];
+        emitted_host = flags[1];
         done = emitted_host >= gen->max_new;
     }
     size_t e_end = ev++;
@@ -1081,7 +1122,7 @@ extern "C" int32_t knnssd_profile_pass(knnssd_ctx *ctx, int32_t kind, const int3
     ctx->prof_launches = 0; ctx->prof_bytes = 0;
     ctx->gemm_only = true;
     (void)hipEventRecord(p0, ctx->stream);
-    int32_t rc = run_pass(ctx, ctl, kind == 0 ? ctx->draft_mask.data() : nullptr, kind == 0 ? 1 : KS_MAX_ROWS, n);
+    int32_t rc = run_pass(ctx, ctl, kind == 0 ? ctx->draft_mask.data() : nullptr, kind == 0 ? 1 : KS_MAX_ROWS, n, start_pos);
     (void)hipEventRecord(p1, ctx->stream);
     ctx->gemm_only = false;
     hipError_t es = hipStreamSynchronize(ctx->stream);

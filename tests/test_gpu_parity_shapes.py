@@ -252,3 +252,37 @@ def test_tile_counts_of_three_five_and_six_per_workgroup():
     toks_g, st_g = gpu.knnssd_generate(prompt, 12, 4, 0.0)
     assert toks_g == toks_o, [min(r.margins) for r in rounds if r.margins]
     gpu.close()
+
+
+@pytest.mark.parametrize("gqa", [False, True])
+def test_draft_step_merge_inside_the_output_projection(gqa):
+    """A draft step whose row sees at most six 256-position chunks merges the chunks of its split-KV attention in the
+    prologue of the output projection (cfg.attn_merge = KNNSSD_MERGE_FUSED, the default); the same step with the merge
+    as a launch of its own (KNNSSD_MERGE_SEPARATE) must give the same bits, at one, two and six chunks, and both are
+    checked against the oracle. Beyond six chunks both contexts take the separate launch."""
+    shape = synth.small_shape("fuse_gqa" if gqa else "fuse_mha", n_blocks=2, d_model=512, n_heads=8, n_kv_heads=2 if gqa else 8,
+                              head_dim=64, d_ffn=1408, vocab=900, max_seq=1700)
+    w, orc, gpu = make_pair(shape, seed=37, std=0.04)
+    gpu2 = binding.KnnSsd(shape, w, separate_merge=True)
+    mask = [0, 1, 0, 0]
+    for plen in (37, 283, 1300, 1600):
+        print("case", gqa, plen, flush=True)
+        prompt = synth.make_prompt(shape.vocab, plen, seed=2).tolist()
+        first_o, _, _ = O.prefill(orc, prompt)
+        for g in (gpu, gpu2):
+            assert g.knnssd_prefill(prompt)[0] == first_o
+            g.knnssd_set_skipset(mask)
+        tok, rows = first_o, []
+        for i in range(3):                                   # consecutive steps: each reads what the one before wrote
+            t1, p1 = gpu.knnssd_draft_step(tok, plen + i)
+            t2, p2 = gpu2.knnssd_draft_step(tok, plen + i)
+            l1, l2 = gpu.knnssd_get_logits(0).clone(), gpu2.knnssd_get_logits(0).clone()
+            assert torch.equal(l1, l2), (plen, i)
+            assert (t1, p1) == (t2, p2)
+            row = orc.forward([tok], plen + i, np.asarray(mask, np.uint8))[0]
+            ok, err = logits_close(l1.numpy(), row, shape)
+            assert ok, (plen, i, err)
+            assert t1 == O.argmax_lowest(row)
+            tok = t1
+    gpu.close()
+    gpu2.close()
