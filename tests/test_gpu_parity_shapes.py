@@ -286,3 +286,50 @@ def test_draft_step_merge_inside_the_output_projection(gqa):
             tok = t1
     gpu.close()
     gpu2.close()
+
+
+def test_two_identical_runs_give_identical_bits():
+    """Run-to-run determinism of the tuned kernels (no atomics, fixed reduction orders): the same prefill, draft
+    steps, verification passes and generation twice on one context, and once more on a second context built from
+    the same weights; logits, cached keys/values, tokens and counters must be identical bit for bit."""
+    shape = synth.small_shape("det", n_blocks=3, d_model=512, n_heads=8, n_kv_heads=2, head_dim=64, d_ffn=1408, vocab=1531,
+                              max_seq=400)
+    w = synth.make_weights(shape, seed=51, gains="random", std=0.05)
+    prompt = synth.make_prompt(shape.vocab, 283, seed=6).tolist()
+    mask = synth.make_block_masks(shape.n_blocks, 1, 1, seed=9).numpy()[0].tolist()
+
+    def run(gpu):
+        out = {}
+        first, hidden = gpu.knnssd_prefill(prompt)
+        out["first"], out["hidden"] = first, hidden.cpu().clone()
+        out["kv"] = [torch.cat(gpu.knnssd_read_kv(b, p)) for b in range(shape.n_blocks) for p in (0, 100, 271, 272, 282)]
+        gpu.knnssd_set_skipset(mask)
+        tok, drafts = first, []
+        for i in range(4):
+            tok, p = gpu.knnssd_draft_step(tok, len(prompt) + i)
+            drafts.append((tok, p, gpu.knnssd_get_logits(0).clone()))
+        out["drafts"] = drafts
+        out["verify"] = gpu.knnssd_verify([first] + [d[0] for d in drafts], len(prompt))
+        out["vlogits"] = [gpu.knnssd_get_logits(r).clone() for r in range(5)]
+        toks, st = gpu.knnssd_generate(prompt, 40, 6, 0.0, route=False)
+        out["gen"] = (toks, st["rounds"], st["drafted"], st["accepted"])
+        return out
+
+    def same(a, b):
+        assert a["first"] == b["first"] and torch.equal(a["hidden"], b["hidden"])
+        assert all(torch.equal(x, y) for x, y in zip(a["kv"], b["kv"]))
+        for (t1, p1, l1), (t2, p2, l2) in zip(a["drafts"], b["drafts"]):
+            assert t1 == t2 and p1 == p2 and torch.equal(l1, l2)
+        assert a["verify"] == b["verify"]
+        assert all(torch.equal(x, y) for x, y in zip(a["vlogits"], b["vlogits"]))
+        assert a["gen"] == b["gen"]
+
+    gpu = binding.KnnSsd(shape, w)
+    assert gpu.packed
+    r1 = run(gpu)
+    r2 = run(gpu)
+    same(r1, r2)
+    gpu2 = binding.KnnSsd(shape, w)
+    same(r1, run(gpu2))
+    gpu.close()
+    gpu2.close()
