@@ -39,16 +39,16 @@ struct GemmOp {
     int type;
     const bf16_t *W;  // [N][K] row-major; OP_SWIGLU: [2N][K], gate rows then up rows
     int N, K;
-    const float *act_in;      // draft: fp32 [K], the next norm's gain already applied
-    const bf16_t *planes_in;  // verify: bf16 split of the same values (three planes), stored as this GEMM's chunk images
+    const float *act_in;      // fp32, the next norm's gain already applied. Draft: [K]. Verify: the live rows as this GEMM's
+                              // chunk images (image_offset; with one row that is the plain vector again)
     const float *ss_in;       // [KS_MAX_ROWS][KS_NWG] the workgroups' shares of sum(x^2) per token row; nullptr: input is not normalised
     int n_ss;                 // = KS_NWG (the tuned kernels rely on it)
     float inv_dim, eps;
     // OP_RESID / OP_EMBED: residual stream and the operands of the next norm
     float *x;                 // [KS_MAX_ROWS][N]
     const float *gain_next;   // [N]
-    float *act_out;           // fp32 [KS_MAX_ROWS][N]  (also OP_SWIGLU's output)
-    bf16_t *planes_out;       // three planes as the chunk images of the GEMM that reads them (plane_image_offset)
+    float *act_out;           // fp32 (also OP_SWIGLU's output). Draft: [N]. Verify: the chunk images of the GEMM that reads
+                              // them (image_offset with out_kc and n_rows)
     float *ss_out;            // [KS_MAX_ROWS][KS_NWG] (a row's shares are contiguous: its reader fetches them with four loads)
     // OP_QKV
     float *q_out;             // [KS_MAX_ROWS][H*hd], rotated
@@ -68,7 +68,7 @@ struct GemmOp {
     int lds_bytes, max_rows;
     int kc, nc;               // activation chunk length in columns and chunk count (mfma_chunking, set by the host)
     int bbuf_bytes, fixed_lds, red_bufs;   // the rest of that kernel's LDS plan (mfma_bbuf_bytes, mfma_fixed_lds, mfma_red_bufs)
-    int out_kc;               // chunk length of the GEMM that reads planes_out (the same call for its shape and row count)
+    int out_kc;               // chunk length of the GEMM that reads act_out (the same call for its shape and row count)
     int n_rows;               // token rows of the pass as the host counts them (the same number the control block holds)
     // [KS_NWG] this matrix shape's workgroup splits, tabulated once (split_table_kernel): a kernel reads its entry
     // with one scalar load instead of recomputing it in every wavefront of every launch
@@ -133,8 +133,10 @@ __device__ __forceinline__ float stream_load_f32(const float *p) {
 // stay in flight): N 16-byte pieces, or four norm shares and two epilogue values
 template <int KEEP, int N>
 __device__ __forceinline__ void stream_wait_pieces(u32x4 *x) {
-    static_assert(N == 4 || N == 5, "piece count");
-    if constexpr (N == 4)
+    static_assert(N == 3 || N == 4 || N == 5, "piece count");
+    if constexpr (N == 3)
+        asm volatile("s_waitcnt vmcnt(%3)" : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]) : "n"(KEEP) : "memory");
+    else if constexpr (N == 4)
         asm volatile("s_waitcnt vmcnt(%4)" : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]) : "n"(KEEP) : "memory");
     else
         asm volatile("s_waitcnt vmcnt(%5)" : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]) : "n"(KEEP) : "memory");
@@ -232,38 +234,23 @@ __device__ __forceinline__ int div_small(int i, int n, float inv) {
 }
 
 // Where the verification GEMM's activations live ("chunk images"). The GEMM stages its token rows through LDS in
-// chunks of kc columns (mfma_chunking); the producer of those activations writes them in exactly the byte order of
-// the LDS stage, so staging a chunk is a straight copy of one contiguous range (no index arithmetic in front of the
-// consumer's first weight load). Chunk c holds columns [c*kc, c*kc + cols_c) of the n_rows live rows for the three
-// planes: 3*n_rows staged rows (plane-major) of cols_c + 8 elements each (8 = the 16 bytes that spread the rows over
-// the LDS banks; never read). All chunks before the last are full, so chunk c starts at c * 3*n_rows*(kc+8).
-// Returns the element offset of (plane 0, row m, column n) and the distance between planes.
-__device__ __forceinline__ int plane_image_offset(int m, int n, int ldn, int kc, int n_rows, float inv_kc, int *plane_step) {
+// chunks of kc columns (mfma_chunking); the producer of those activations writes them so that a chunk is one contiguous
+// range of fp32 values: chunk c holds columns [c*kc, c*kc + cols_c) of the n_rows live rows, row after row. All chunks
+// before the last are full, so chunk c starts at c * n_rows * kc. The consumer fetches a chunk as 16-byte pieces with
+// straight indexing (4 bytes per element cross the L2, not the 6 of ready-made bf16 planes) and splits every value into
+// its three bf16 planes on the way into LDS. With one live row the image is the plain vector.
+// Returns the element offset of (row m, column n).
+__device__ __forceinline__ int image_offset(int m, int n, int ldn, int kc, int n_rows, float inv_kc) {
     const int c = div_small(n, kc, inv_kc);
     const int cols_c = min(kc, ldn - c * kc);
-    *plane_step = n_rows * (cols_c + 8);
-    return c * (3 * n_rows * (kc + 8)) + m * (cols_c + 8) + (n - c * kc);
+    return c * (n_rows * kc) + m * cols_c + (n - c * kc);
 }
-// elements a chunk-image buffer needs for up to KS_MAX_ROWS rows of ldn columns (chunks are at least 512 columns)
-__host__ __device__ inline size_t plane_image_elems(size_t ldn) { return 3 * (size_t)KS_MAX_ROWS * (ldn + 8 * ((ldn + 511) / 512)); }
 
-template <bool PLANES>
+// IMAGE = false: the draft step's plain vector (row 0); true: the chunk image of the GEMM that reads the value
+template <bool IMAGE>
 __device__ __forceinline__ void store_act(const GemmOp &op, int m, int n, int ldn, float v, float inv_kc) {
-    if (!PLANES) {
-        op.act_out[(size_t)m * ldn + n] = v;
-    } else {
-        // exact three-way split: v = hi + mid + lo, each a bf16 (truncation keeps every step exact)
-        unsigned int u = __float_as_uint(v);
-        float hi = __uint_as_float(u & 0xffff0000u);
-        float r1 = v - hi;
-        float mid = __uint_as_float(__float_as_uint(r1) & 0xffff0000u);
-        float lo = r1 - mid;
-        int step;
-        const int o = plane_image_offset(m, n, ldn, op.out_kc, op.n_rows, inv_kc, &step);
-        op.planes_out[o] = (bf16_t)(u >> 16);
-        op.planes_out[o + step] = (bf16_t)(__float_as_uint(mid) >> 16);
-        op.planes_out[o + 2 * step] = (bf16_t)(__float_as_uint(lo) >> 16);
-    }
+    if (!IMAGE) op.act_out[(size_t)m * ldn + n] = v;
+    else op.act_out[image_offset(m, n, ldn, op.out_kc, op.n_rows, inv_kc)] = v;
 }
 
 template <bool PLANES>
@@ -717,7 +704,7 @@ __global__ __launch_bounds__(NT, 1) void gemv_kernel(GemmOp op, const PassCtl *c
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int MFMA_BQ = 5;          // 16-byte pieces of an activation chunk a thread may carry (chunk <= 80 KB)
+constexpr int MFMA_BQ = 3;          // 16-byte pieces (four fp32 values) of an activation chunk a thread may carry: 72 KB of planes in LDS
 
 // LDS plan of the verification GEMM: [vals: max_rows x 16 floats][red: 1 or 2 x NWV x 256 floats][row table][scratch]
 // and two activation staging buffers sharing what is left of the dynamic LDS the launch asked for. A staging buffer
@@ -735,7 +722,7 @@ __host__ __device__ inline size_t mfma_fixed_lds(size_t lds_total, int max_rows)
 }
 __host__ __device__ inline int mfma_bbuf_bytes(size_t lds_total, int max_rows) {
     long long b = ((long long)lds_total - (long long)mfma_fixed_lds(lds_total, max_rows)) / 2 / 256 * 256;
-    const long long cap = (long long)MFMA_BQ * NT * 16;
+    const long long cap = (long long)MFMA_BQ * NT * 24;     // a fetched piece becomes 3 x 8 bytes of planes
     return (int)(b > cap ? cap : b);
 }
 // The token rows (B operand) are staged through LDS in column chunks shared by all wavefronts: only the live rows
@@ -776,25 +763,44 @@ __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl
     const int KC = op.kc, NC = op.nc;                                    // see mfma_chunking
     const int brow = min(r16, n_rows - 1);                               // dead token lanes re-read the last live row
     u32x4 breg[MFMA_BQ];
-    // The activations arrive as chunk images (plane_image_offset): chunk c is one contiguous range, 3*n_rows staged
-    // rows of cols_c + 8 elements, already in the byte order of the LDS stage. Staging is a straight copy, piece i
-    // of the range to byte 16*i of the buffer.
-    auto chunk_pieces = [&](int c) { return 3 * n_rows * ((min(KC, K - c * KC) >> 3) + 1); };
+    // The activations arrive as chunk images (image_offset): chunk c is one contiguous range of n_rows * cols_c fp32
+    // values, row after row. Piece i of the range (four values of row i / (cols_c/4)) is split into its three exact
+    // bf16 planes (hi + mid + lo by truncation) and lands in the LDS stage, whose 3 * n_rows rows (plane-major) have
+    // cols_c + 8 elements each (the 16 spare bytes spread the rows over the banks and are never read).
+    auto chunk_pieces = [&](int c) { return n_rows * (min(KC, K - c * KC) >> 2); };
     // (t = the thread's index, passed in so that a caller inside the unit loop can hand over a copy the optimiser
     // cannot see through: the piece offsets are then recomputed on the spot instead of living in registers)
     auto bchunk_load = [&](int c, int t) {   // global -> registers (hand-placed loads)
-        const bf16_t *src = op.planes_in + c * (3 * n_rows * (KC + 8));
+        const float *src = op.act_in + c * (n_rows * KC);
         const int last = chunk_pieces(c) - 1;
 #pragma unroll
         for (int q = 0; q < MFMA_BQ; ++q)        // unconditional (clamped): the waits below count on exactly MFMA_BQ loads
-            breg[q] = stream_load_x4(src + min(t + q * NT, last) * 8);
+            breg[q] = stream_load_x4(src + min(t + q * NT, last) * 4);
     };
-    auto bchunk_store = [&](int c, int t) {  // registers -> LDS buffer c & 1
+    auto bchunk_store = [&](int c, int t) {  // registers -> planes in LDS buffer c & 1
         char *dst = bbuf + (c & 1) * BBUF;
-        const int last = chunk_pieces(c) - 1;
+        const int cols = min(KC, K - c * KC), ppr = cols >> 2;      // pieces per row
+        const int last = n_rows * ppr - 1, bstride = (cols + 8) * 2, pstep = n_rows * bstride;
+        const float inv_ppr = __builtin_amdgcn_rcpf((float)ppr);
 #pragma unroll
-        for (int q = 0; q < MFMA_BQ; ++q)        // clamped like the loads: a duplicate writes the same value to the same place
-            *reinterpret_cast<u32x4 *>(dst + min(t + q * NT, last) * 16) = breg[q];
+        for (int q = 0; q < MFMA_BQ; ++q) {      // clamped like the loads: a duplicate writes the same value to the same place
+            const int i = min(t + q * NT, last);
+            const int row = div_small(i, ppr, inv_ppr), c4 = i - row * ppr;
+            unsigned int hi[4], mid[4], lo[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const unsigned int u = breg[q][e];
+                const float r1 = __uint_as_float(u) - __uint_as_float(u & 0xffff0000u);
+                const unsigned int um = __float_as_uint(r1);
+                hi[e] = u; mid[e] = um;
+                lo[e] = __float_as_uint(r1 - __uint_as_float(um & 0xffff0000u));
+            }
+            char *d = dst + row * bstride + c4 * 8;
+            // the upper halves of two neighbouring values make one register of a plane
+            *reinterpret_cast<u32x2 *>(d) = u32x2{__builtin_amdgcn_perm(hi[1], hi[0], 0x07060302u), __builtin_amdgcn_perm(hi[3], hi[2], 0x07060302u)};
+            *reinterpret_cast<u32x2 *>(d + pstep) = u32x2{__builtin_amdgcn_perm(mid[1], mid[0], 0x07060302u), __builtin_amdgcn_perm(mid[3], mid[2], 0x07060302u)};
+            *reinterpret_cast<u32x2 *>(d + 2 * pstep) = u32x2{__builtin_amdgcn_perm(lo[1], lo[0], 0x07060302u), __builtin_amdgcn_perm(lo[3], lo[2], 0x07060302u)};
+        }
     };
 
     // units of chunk c this wavefront owns (they are consecutive in its stream)
@@ -821,7 +827,7 @@ __device__ __forceinline__ void gemm_mfma_device(const GemmOp &op, const PassCtl
     {
         const bool resid = op.type == OP_RESID;
         const int n = resid ? min(wg_share(op.N, wg) + (tid >> 4), op.N - 1) : 0;
-        const float *fallback = reinterpret_cast<const float *>(op.planes_in);
+        const float *fallback = op.act_in;
         xpre = stream_load_f32((resid ? op.x : fallback) + (resid ? (size_t)min(tid & 15, n_rows - 1) * op.N + n : 0));
         gpre = stream_load_f32((resid ? op.gain_next : fallback) + n);
     }
@@ -1097,10 +1103,10 @@ __global__ __launch_bounds__(NT, 1) void gemm_mfma_kernel(GemmOp op, const PassC
     gemm_mfma_device<RING>(op, ctl, blockIdx.x, gridDim.x, lds);
 }
 
-// final-RMSNorm hidden state of one row from the head's operands: gain (.) x (three planes) times rstd
-__global__ __launch_bounds__(NT) void hidden_from_planes_kernel(const bf16_t *planes, int kc, int n_rows, const float *ss, int n_ss,
-                                                                int d, float eps, const PassCtl *ctl, float *out0, float *out1) {
-    // planes: the LM head's chunk images (chunk length kc, n_rows live rows as the host counts them)
+// final-RMSNorm hidden state of one row from the head's operands: gain (.) x times rstd
+__global__ __launch_bounds__(NT) void hidden_from_image_kernel(const float *image, int kc, int n_rows, const float *ss, int n_ss,
+                                                               int d, float eps, const PassCtl *ctl, float *out0, float *out1) {
+    // image: the LM head's chunk images (chunk length kc, n_rows live rows as the host counts them)
     if (!ctl->active) return;
     __shared__ float rs;
     const int m = min(ctl->n_rows, n_rows) - 1;
@@ -1113,10 +1119,7 @@ __global__ __launch_bounds__(NT) void hidden_from_planes_kernel(const bf16_t *pl
     __syncthreads();
     const float inv_kc = __builtin_amdgcn_rcpf((float)kc);
     for (int i = blockIdx.x * NT + threadIdx.x; i < d; i += gridDim.x * NT) {
-        int step;
-        const int o = plane_image_offset(m, i, d, kc, n_rows, inv_kc, &step);
-        float v = (bf16_to_float(planes[o]) + bf16_to_float(planes[o + step])) + bf16_to_float(planes[o + 2 * step]);
-        v *= rs;
+        const float v = image[image_offset(m, i, d, kc, n_rows, inv_kc)] * rs;
         out0[i] = v;
         if (out1) out1[i] = v;
     }
@@ -1129,7 +1132,7 @@ template <bool PLANES>
 __global__ __launch_bounds__(NT) void embed_producer_kernel(GemmOp op, const PassCtl *ctl) {
     __shared__ float scratch[NWV];
     if (!ctl->active) return;
-    // the plane layout is the one the host computed for op.n_rows rows: never more rows than that
+    // the image layout is the one the host computed for op.n_rows rows: never more rows than that
     const int n_rows = min(min(ctl->n_rows, KS_MAX_ROWS), PLANES ? op.n_rows : KS_MAX_ROWS);
     const float inv_kc = PLANES ? __builtin_amdgcn_rcpf((float)op.out_kc) : 0.f;
     const int wg = blockIdx.x;         // launched with KS_NWG workgroups (wg_share)
@@ -1161,9 +1164,9 @@ struct AttnArgs {
     int H, Hkv, hd, max_seq, max_chunks;
     int group;               // H / Hkv
     // combine
-    float *act_out;          // fp32 [KS_MAX_ROWS][H*hd]
-    bf16_t *planes_out;      // three planes as the O projection's chunk images (plane_image_offset)
-    int out_kc, n_rows;      // that GEMM's chunk length and the pass's row count as the host counts them
+    float *act_out;          // fp32: draft [H*hd]; verify: chunk images
+    int out_kc, n_rows;      // PLANES: act_out holds the O projection's chunk images: that GEMM's chunk length and the pass's
+                             // row count as the host counts them
 };
 
 template <int HD>
@@ -1301,7 +1304,7 @@ __device__ __forceinline__ void attn_combine_device(const AttnArgs &a, const Pas
     const int hd = a.hd, qd = a.H * hd;
     const int total = n_rows * qd;
     GemmOp st{};   // only the fields store_act uses
-    st.act_out = a.act_out; st.planes_out = a.planes_out; st.out_kc = a.out_kc; st.n_rows = a.n_rows;
+    st.act_out = a.act_out; st.out_kc = a.out_kc; st.n_rows = a.n_rows;
     const float inv_kc = PLANES ? __builtin_amdgcn_rcpf((float)a.out_kc) : 0.f;
     const float inv_qd = __builtin_amdgcn_rcpf((float)qd);
     const int hd_shift = 31 - __builtin_clz(hd);                           // head_dim is 64 or 128

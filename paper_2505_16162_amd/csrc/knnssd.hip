@@ -44,7 +44,7 @@ struct WsLayout {
     size_t draft_ctl, ver_ctl, gen, head, knn, out3;
     size_t x, xn, qkv, att, u, logits, hidden_last, rope_cos, rope_sin, knn_scores, knn_topk, knn_cand_idx, knn_cand_val, knn_bad, out_tokens;
     // tuned bf16 path
-    size_t act_d, planes_d, qrot, planes_att, planes_u, ss, head_part, attn_part, split_tab;
+    size_t act_d, qrot, ss, head_part, attn_part, split_tab;
     // tuned prompt prefill (stream-order weights only): all prompt rows at once
     size_t pf_tokens, pf_x, pf_q, pf_frag_d, pf_frag_att, pf_frag_u, pf_ss, pf_rstd;
     int pf_tt;          // token tiles the fragment buffers are laid out for
@@ -104,10 +104,7 @@ static WsLayout ws_layout(const knnssd_model_cfg *c) {
         const size_t qd = (size_t)c->n_heads * c->head_dim;
         const size_t max_chunks = ((size_t)c->max_seq + ATT_CHUNK - 1) / ATT_CHUNK;
         L.act_d = take(R * c->d_model * 4);
-        L.planes_d = take(plane_image_elems((size_t)c->d_model) * 2);
         L.qrot = take(R * qd * 4);
-        L.planes_att = take(plane_image_elems(qd) * 2);
-        L.planes_u = take(plane_image_elems((size_t)c->d_ffn) * 2);
         L.ss = take((size_t)KS_NWG * R * 4);
         L.head_part = take(R * (size_t)KS_NWG * sizeof(HeadPartial));
         L.attn_part = take(R * c->n_heads * max_chunks * (c->head_dim + ATT_PAD) * 4);
@@ -483,8 +480,6 @@ static int32_t run_pass_bf16(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, b
     const int qd = H * hd, qkvd = (H + 2 * Hkv) * hd;
     float *x = c->wsp<float>(c->L.x), *act_d = c->wsp<float>(c->L.act_d), *qrot = c->wsp<float>(c->L.qrot);
     float *att = c->wsp<float>(c->L.att), *u = c->wsp<float>(c->L.u), *ss = c->wsp<float>(c->L.ss);
-    bf16_t *planes_d = c->wsp<bf16_t>(c->L.planes_d), *planes_att = c->wsp<bf16_t>(c->L.planes_att);
-    bf16_t *planes_u = c->wsp<bf16_t>(c->L.planes_u);
     hipStream_t s = c->stream;
     // most rows of one matrix a workgroup owns (fixes the verification GEMM's LDS plan), and the chunk length that
     // GEMM stages its activations in: the producer of those activations writes them as that GEMM's chunk images
@@ -545,14 +540,14 @@ static int32_t run_pass_bf16(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, b
 
     GemmOp e = base;
     e.type = OP_EMBED; e.N = d; e.embed = (const bf16_t *)c->embed; e.x = x; e.gain_next = next_gain(c, mask, -1);
-    e.act_out = act_d; e.planes_out = planes_d; e.ss_out = ss; e.n_rows = n_rows; e.out_kc = kc_next(-1);
+    e.act_out = act_d; e.ss_out = ss; e.n_rows = n_rows; e.out_kc = kc_next(-1);
     if (!others) {
     } else if (rows1) hipLaunchKernelGGL((embed_producer_kernel<false>), dim3(KS_NWG), dim3(NT), 0, s, e, ctl);
     else hipLaunchKernelGGL((embed_producer_kernel<true>), dim3(KS_NWG), dim3(NT), 0, s, e, ctl);
 
     AttnArgs aa{};
     aa.q = qrot; aa.partial = c->wsp<float>(c->L.attn_part); aa.H = H; aa.Hkv = Hkv; aa.hd = hd; aa.max_seq = g.max_seq; aa.group = H / Hkv;
-    aa.max_chunks = (g.max_seq + ATT_CHUNK - 1) / ATT_CHUNK; aa.act_out = att; aa.planes_out = planes_att;
+    aa.max_chunks = (g.max_seq + ATT_CHUNK - 1) / ATT_CHUNK; aa.act_out = att;
     aa.n_rows = n_rows; aa.out_kc = kc_of(OP_RESID, d, qd);
     // Draft steps whose row sees at most ATT_FUSE_CHUNKS chunks: the O projection merges the chunks' partials in its own
     // prologue (gemv_kernel<true>) and the merge launch is dropped. Longer contexts, wider models and verification
@@ -563,7 +558,7 @@ static int32_t run_pass_bf16(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, b
         bf16_t *kvb = (bf16_t *)(c->kv + (size_t)b * c->kv_block_bytes);
         if (!(mask && mask[2 * b])) {
             GemmOp o = base;
-            o.type = OP_QKV; o.W = (const bf16_t *)c->wqkv[b]; o.N = qkvd; o.K = d; o.act_in = act_d; o.planes_in = planes_d;
+            o.type = OP_QKV; o.W = (const bf16_t *)c->wqkv[b]; o.N = qkvd; o.K = d; o.act_in = act_d;
             o.ss_in = ss; o.q_out = qrot; o.kv_block = kvb; o.split = c->split_qkv;
             launch(o);
             aa.kv_block = kvb;
@@ -579,27 +574,27 @@ static int32_t run_pass_bf16(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, b
             } else if (rows1) hipLaunchKernelGGL((attn_combine_kernel<false>), dim3(16), dim3(NT), 0, s, aa, ctl);
             else hipLaunchKernelGGL((attn_combine_kernel<true>), dim3(64), dim3(NT), 0, s, aa, ctl);
             GemmOp r = base;
-            r.type = OP_RESID; r.W = (const bf16_t *)c->wo[b]; r.N = d; r.K = qd; r.act_in = att; r.planes_in = planes_att;
-            r.ss_in = nullptr; r.x = x; r.gain_next = next_gain(c, mask, 2 * b); r.act_out = act_d; r.planes_out = planes_d;
+            r.type = OP_RESID; r.W = (const bf16_t *)c->wo[b]; r.N = d; r.K = qd; r.act_in = att;
+            r.ss_in = nullptr; r.x = x; r.gain_next = next_gain(c, mask, 2 * b); r.act_out = act_d;
             r.ss_out = ss; r.split = c->split_o; r.out_kc = kc_next(2 * b);
             if (fuse_merge) { r.att_part = aa.partial; r.att_max_chunks = aa.max_chunks; }
             launch(r);
         }
         if (!(mask && mask[2 * b + 1])) {
             GemmOp o = base;
-            o.type = OP_SWIGLU; o.W = (const bf16_t *)c->wgu[b]; o.N = F; o.K = d; o.act_in = act_d; o.planes_in = planes_d;
-            o.ss_in = ss; o.act_out = u; o.planes_out = planes_u; o.split = c->split_gu; o.out_kc = kc_of(OP_RESID, d, F);
+            o.type = OP_SWIGLU; o.W = (const bf16_t *)c->wgu[b]; o.N = F; o.K = d; o.act_in = act_d;
+            o.ss_in = ss; o.act_out = u; o.split = c->split_gu; o.out_kc = kc_of(OP_RESID, d, F);
             launch(o);
             GemmOp r = base;
-            r.type = OP_RESID; r.W = (const bf16_t *)c->wdown[b]; r.N = d; r.K = F; r.act_in = u; r.planes_in = planes_u;
-            r.ss_in = nullptr; r.x = x; r.gain_next = next_gain(c, mask, 2 * b + 1); r.act_out = act_d; r.planes_out = planes_d;
+            r.type = OP_RESID; r.W = (const bf16_t *)c->wdown[b]; r.N = d; r.K = F; r.act_in = u;
+            r.ss_in = nullptr; r.x = x; r.gain_next = next_gain(c, mask, 2 * b + 1); r.act_out = act_d;
             r.ss_out = ss; r.split = c->split_down; r.out_kc = kc_next(2 * b + 1);
             launch(r);
         }
     }
     if (want_head) {
         GemmOp h = base;
-        h.type = OP_HEAD; h.W = (const bf16_t *)c->lm_head; h.N = g.vocab; h.K = d; h.act_in = act_d; h.planes_in = planes_d;
+        h.type = OP_HEAD; h.W = (const bf16_t *)c->lm_head; h.N = g.vocab; h.K = d; h.act_in = act_d;
         h.ss_in = ss; h.logits = c->wsp<float>(c->L.logits); h.head_part = c->wsp<HeadPartial>(c->L.head_part);
         h.split = c->split_head;
         launch(h);
@@ -744,7 +739,7 @@ static int32_t prefill_impl(knnssd_ctx *c, const int32_t *tokens, int32_t n, flo
                 // the last pass left the final norm's operands as the LM head's chunk images
                 int head_kc = 0, head_nc = 0;
                 mfma_chunking(KS_MAX_DYN_LDS, (c->cfg.vocab + KS_NWG - 1) / KS_NWG, rows, c->cfg.d_model, &head_kc, &head_nc);
-                hipLaunchKernelGGL(hidden_from_planes_kernel, dim3(8), dim3(NT), 0, c->stream, c->wsp<bf16_t>(c->L.planes_d),
+                hipLaunchKernelGGL(hidden_from_image_kernel, dim3(8), dim3(NT), 0, c->stream, c->wsp<float>(c->L.act_d),
                                    head_kc, rows, c->wsp<float>(c->L.ss), KS_NWG, c->cfg.d_model, c->cfg.rms_eps, ver,
                                    c->wsp<float>(c->L.hidden_last), last_hidden_dev);
                 HIP_TRY(hipGetLastError());
