@@ -75,10 +75,12 @@ typedef struct knnssd_model_cfg {
                                KNNSSD_ATTN_VALU (vector ALUs). One kernel per context, never chosen per pass, so a
                                row's result does not depend on how many rows share its pass. Only read with
                                weights_packed = 1. Results stay within the stated tolerances either way. */
-    int32_t attn_merge;     /* where a draft step merges the chunks of its split-KV attention: KNNSSD_MERGE_FUSED (the
-                               default: inside the output projection's kernel while the row sees at most 1536
-                               positions, in a launch of its own beyond) or KNNSSD_MERGE_SEPARATE (always in a launch
-                               of its own). Same arithmetic, same bits. Only read with weights_packed = 1. */
+    int32_t attn_merge;     /* where the chunks of the split-KV attention are merged: KNNSSD_MERGE_FUSED (the default:
+                               the matrix-core attention kernel merges them itself, in the workgroup that finishes a
+                               group's last chunk; a draft step on the vector-ALU attention kernel merges them inside
+                               the output projection's kernel while its row sees at most 1536 positions, in a launch
+                               of its own beyond) or KNNSSD_MERGE_SEPARATE (always in a launch of its own). Same
+                               arithmetic, same bits. Only read with weights_packed = 1. */
 } knnssd_model_cfg;
 
 /* Device pointers to the model. The four per-block members are HOST arrays of

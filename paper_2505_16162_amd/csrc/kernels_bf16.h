@@ -1167,6 +1167,8 @@ struct AttnArgs {
     float *act_out;          // fp32: draft [H*hd]; verify: chunk images
     int out_kc, n_rows;      // PLANES: act_out holds the O projection's chunk images: that GEMM's chunk length and the pass's
                              // row count as the host counts them
+    int *arrivals;           // attn_partial_mfma_kernel: [pair tiles][Hkv] arrival counters (zero between launches) when the
+                             // last workgroup of a group merges the chunks itself; nullptr: attn_combine_kernel follows
 };
 
 template <int HD>

@@ -44,7 +44,7 @@ struct WsLayout {
     size_t draft_ctl, ver_ctl, gen, head, knn, out3;
     size_t x, xn, qkv, att, u, logits, hidden_last, rope_cos, rope_sin, knn_scores, knn_topk, knn_cand_idx, knn_cand_val, knn_bad, out_tokens;
     // tuned bf16 path
-    size_t act_d, qrot, ss, head_part, attn_part, split_tab;
+    size_t act_d, qrot, ss, head_part, attn_part, attn_arrivals, split_tab;
     // tuned prompt prefill (stream-order weights only): all prompt rows at once
     size_t pf_tokens, pf_x, pf_q, pf_frag_d, pf_frag_att, pf_frag_u, pf_ss, pf_rstd;
     int pf_tt;          // token tiles the fragment buffers are laid out for
@@ -108,6 +108,7 @@ static WsLayout ws_layout(const knnssd_model_cfg *c) {
         L.ss = take((size_t)KS_NWG * R * 4);
         L.head_part = take(R * (size_t)KS_NWG * sizeof(HeadPartial));
         L.attn_part = take(R * c->n_heads * max_chunks * (c->head_dim + ATT_PAD) * 4);
+        L.attn_arrivals = take(R * (size_t)c->n_heads * 4);
         L.split_tab = take((size_t)5 * KS_NWG * sizeof(WgSplit));
         if (c->weights_packed) {
             const size_t tt = (((size_t)c->max_seq + 15) / 16 + 15) / 16 * 16, rows = tt * 16;
@@ -283,6 +284,8 @@ extern "C" int32_t knnssd_create(const knnssd_model_cfg *cfg, const knnssd_weigh
         c->split_gu = tabulate(2, OP_SWIGLU, cfg->d_ffn, d);
         c->split_down = tabulate(3, OP_RESID, d, cfg->d_ffn);
         c->split_head = tabulate(4, OP_HEAD, cfg->vocab, d);
+        // arrival counters of the attention kernel that merges its own chunks: zero between launches
+        hipLaunchKernelGGL(fill_zero_kernel, dim3(1), dim3(256), 0, c->stream, c->wsp<int>(c->L.attn_arrivals), KS_MAX_ROWS * cfg->n_heads);
         hipError_t et = hipGetLastError();
         if (et != hipSuccess) {
             snprintf(g_hip_err, sizeof(g_hip_err), "%s (split_table_kernel)", hipGetErrorString(et));
@@ -552,8 +555,15 @@ static int32_t run_pass_bf16(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, b
     // Draft steps whose row sees at most ATT_FUSE_CHUNKS chunks: the O projection merges the chunks' partials in its own
     // prologue (gemv_kernel<true>) and the merge launch is dropped. Longer contexts, wider models and verification
     // passes keep attn_combine_kernel.
-    const bool fuse_merge = rows1 && c->cfg.attn_merge == KNNSSD_MERGE_FUSED && start + 1 <= ATT_FUSE_CHUNKS * ATT_CHUNK &&
-                            qd <= ATT_FUSE_GROUPS * NT * 4 && H <= ATT_FUSE_MAX_HEADS;
+    // Where the chunks of the split-KV attention are merged (the arithmetic is the same everywhere, so a value does not
+    // depend on the choice). Few (row, head) pairs per kv head on the matrix-core kernel: the workgroup that finishes a
+    // group's last chunk merges the group (13B-shaped, 2 rows: -2.7 us per block against the merge launch; with 45 pairs
+    // per kv head, Qwen-shaped 9 rows, the one workgroup's serial merge costs 5 us per block MORE than the launch that
+    // spreads it over the chip). Draft steps otherwise: inside the O projection while the row sees few enough chunks.
+    const bool mfma_attn = (!rows1 || aa.group >= 2) && c->verify_attn_mfma;
+    const bool self_merge = mfma_attn && c->cfg.attn_merge == KNNSSD_MERGE_FUSED && n_rows * aa.group <= 4;
+    const bool fuse_merge = rows1 && !self_merge && c->cfg.attn_merge == KNNSSD_MERGE_FUSED &&
+                            start + 1 <= ATT_FUSE_CHUNKS * ATT_CHUNK && qd <= ATT_FUSE_GROUPS * NT * 4 && H <= ATT_FUSE_MAX_HEADS;
     for (int b = 0; b < g.n_blocks; ++b) {
         bf16_t *kvb = (bf16_t *)(c->kv + (size_t)b * c->kv_block_bytes);
         if (!(mask && mask[2 * b])) {
@@ -562,15 +572,16 @@ static int32_t run_pass_bf16(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, b
             o.ss_in = ss; o.q_out = qrot; o.kv_block = kvb; o.split = c->split_qkv;
             launch(o);
             aa.kv_block = kvb;
+            aa.arrivals = self_merge ? c->wsp<int>(c->L.attn_arrivals) : nullptr;
             if (!others) {
-            } else if ((!rows1 || aa.group >= 2) && c->verify_attn_mfma) {
+            } else if (mfma_attn) {
                 // verification, and draft steps of grouped-query models (one row still brings H / Hkv pairs per kv
                 // head): the pairs of a work item side by side on the matrix cores
                 if (hd == 128) hipLaunchKernelGGL((attn_partial_mfma_kernel<128>), dim3(2 * KS_NWG), dim3(VA_NT), vattn_lds_bytes<128>(), s, aa, ctl);
                 else hipLaunchKernelGGL((attn_partial_mfma_kernel<64>), dim3(2 * KS_NWG), dim3(VA_NT), vattn_lds_bytes<64>(), s, aa, ctl);
             } else if (hd == 128) hipLaunchKernelGGL((attn_partial_kernel<128>), dim3(KS_NWG), dim3(NT), attn_lds_bytes(128), s, aa, ctl);
             else hipLaunchKernelGGL((attn_partial_kernel<64>), dim3(KS_NWG), dim3(NT), attn_lds_bytes(64), s, aa, ctl);
-            if (!others || fuse_merge) {
+            if (!others || fuse_merge || self_merge) {
             } else if (rows1) hipLaunchKernelGGL((attn_combine_kernel<false>), dim3(16), dim3(NT), 0, s, aa, ctl);
             else hipLaunchKernelGGL((attn_combine_kernel<true>), dim3(64), dim3(NT), 0, s, aa, ctl);
             GemmOp r = base;
