@@ -76,11 +76,10 @@ typedef struct knnssd_model_cfg {
                                row's result does not depend on how many rows share its pass. Only read with
                                weights_packed = 1. Results stay within the stated tolerances either way. */
     int32_t attn_merge;     /* where the chunks of the split-KV attention are merged: KNNSSD_MERGE_FUSED (the default:
-                               the matrix-core attention kernel merges them itself, in the workgroup that finishes a
-                               group's last chunk; a draft step on the vector-ALU attention kernel merges them inside
-                               the output projection's kernel while its row sees at most 1536 positions, in a launch
-                               of its own beyond) or KNNSSD_MERGE_SEPARATE (always in a launch of its own). Same
-                               arithmetic, same bits. Only read with weights_packed = 1. */
+                               inside the attention launch, by the workgroup that finishes a group's last chunk, while
+                               a kv head has at most four (row, head) pairs; in a launch of its own beyond) or
+                               KNNSSD_MERGE_SEPARATE (always in a launch of its own). Same arithmetic, same bits.
+                               Only read with weights_packed = 1. */
 } knnssd_model_cfg;
 
 /* Device pointers to the model. The four per-block members are HOST arrays of

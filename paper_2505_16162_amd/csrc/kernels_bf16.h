@@ -23,9 +23,8 @@ constexpr int NWV = NT / 64;   // wavefronts per workgroup
 constexpr int MAX_LROWS = 640; // most rows of one matrix a workgroup may own
 constexpr int ATT_CHUNK = NWV * 16;  // positions per split-KV work item (fixed: results do not depend on context length)
 constexpr int ATT_PG = 4;      // (row, head) pairs per attention work item
+constexpr int ATT_SELF_MERGE_PAIRS = 4;   // most (row, head) pairs per kv head for which the attention launch merges its own chunks
 constexpr int ATT_PAD = 4;     // a chunk's partial is [head_dim] weighted values, its maximum, its sum, 2 spare floats (16-byte rows)
-constexpr int ATT_FUSE_CHUNKS = 6;   // most chunks the O projection of a draft step merges in its own prologue (context <= 1536)
-constexpr int ATT_FUSE_GROUPS = 2;   // 4-float groups of the attention output a thread of that prologue merges (K <= 8192)
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
@@ -55,10 +54,6 @@ struct GemmOp {
     bf16_t *kv_block;         // this block's cache: [2][Hkv][max_seq][hd]
     const float *cos_t, *sin_t;
     int H, Hkv, hd, max_seq;
-    // OP_RESID behind the split-KV attention, draft step only (gemv_kernel<true>): the chunks' partials, merged in
-    // this kernel's prologue instead of by attn_combine_kernel; act_in is then unused
-    const float *att_part;    // [H][att_max_chunks][hd + ATT_PAD] (row 0 of the partial buffer)
-    int att_max_chunks;
     // OP_HEAD
     float *logits;            // [KS_MAX_ROWS][N]
     HeadPartial *head_part;   // [KS_MAX_ROWS][gridDim]
@@ -106,24 +101,6 @@ __device__ __forceinline__ u32x4 stream_load_x4(const void *p) {
     return v;
 }
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
-__device__ __forceinline__ u32x2 stream_load_x2(const void *p) {
-    u32x2 v;
-    asm volatile("global_load_dwordx2 %0, %1, off" : "=v"(v) : "v"(p) : "memory");
-    return v;
-}
-template <int KEEP>
-__device__ __forceinline__ void stream_wait_x2(u32x2 &r) {
-    asm volatile("s_waitcnt vmcnt(%1)" : "+v"(r) : "n"(KEEP) : "memory");
-}
-// twelve 16-byte pieces at once (the chunk partials of the fused attention merge)
-template <int KEEP>
-__device__ __forceinline__ void stream_wait_12(u32x4 (*x)[ATT_FUSE_CHUNKS]) {
-    static_assert(ATT_FUSE_GROUPS == 2 && ATT_FUSE_CHUNKS == 6, "twelve registers are named below");
-    asm volatile("s_waitcnt vmcnt(%12)"
-                 : "+v"(x[0][0]), "+v"(x[0][1]), "+v"(x[0][2]), "+v"(x[0][3]), "+v"(x[0][4]), "+v"(x[0][5]),
-                   "+v"(x[1][0]), "+v"(x[1][1]), "+v"(x[1][2]), "+v"(x[1][3]), "+v"(x[1][4]), "+v"(x[1][5])
-                 : "n"(KEEP) : "memory");
-}
 __device__ __forceinline__ float stream_load_f32(const float *p) {
     float v;
     asm volatile("global_load_dword %0, %1, off" : "=v"(v) : "v"(p) : "memory");
@@ -472,9 +449,6 @@ __global__ __launch_bounds__(NT, 1) void pack_matrix_kernel(GemmOp op, const bf1
 // loads per lane in flight), lane (kg, r) multiplies its 8 weights with x[32*step + 8*kg ..] from
 // LDS and keeps a private sum for row r; a tile ends with a 4-lane reduction over kg.
 // ------------------------------------------------------------------------------------------
-// ATT: the input vector is the attention output of this step, still in pieces: the prologue merges the split-KV
-// chunks' partials itself (what attn_combine_kernel does as a launch of its own), with exactly that kernel's arithmetic
-template <bool ATT>
 __device__ __forceinline__ void gemv_device(const GemmOp &op, const PassCtl *ctl, int wg, int nwg, char *lds) {
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int K = op.K;
@@ -484,12 +458,10 @@ __device__ __forceinline__ void gemv_device(const GemmOp &op, const PassCtl *ctl
     float *vals = reinterpret_cast<float *>(rowidx + MAX_LROWS);     // [MAX_LROWS]
     float *scratch = vals + MAX_LROWS;                               // [4*NWV + KS_MAX_ROWS]
     float *rstd_s = scratch + 4 * NWV;
-    float *ftab = rstd_s + KS_MAX_ROWS;                              // ATT: [H][ATT_FUSE_CHUNKS] chunk weights, then [H] sums
 
     // read through the scalar cache while that is still possible: after the first hand-placed load (whose memory
     // clobber the compiler must honour) this would become a vector load queued behind the whole weight batch
     const int active = ctl->active;
-    const int start = ATT ? ctl->start : 0;
     const WgSplit s = op.split[wg];                // tabulated; the row table is filled below
     const int R = s.R;
     const int tlane = wave >> s.ksshift, kpart = wave & (s.ksplit - 1);
@@ -502,33 +474,8 @@ __device__ __forceinline__ void gemv_device(const GemmOp &op, const PassCtl *ctl
     // all the small ones: the compiler's own counting would charge the weight loads to them.
     constexpr int XQ = 4;
     u32x4 xr[XQ];
-    constexpr int AG = ATT_FUSE_GROUPS, AC = ATT_FUSE_CHUNKS;
-    u32x4 orr[AG][AC];
-    u32x2 ml;
-    // chunks the step's row sees (positions 0..start); the host sends a step here only if they fit AC
-    const int n_chunks = ATT ? max(1, min(min((start + ATT_CHUNK) / ATT_CHUNK, op.att_max_chunks), AC)) : 0;
-    const int hd_shift = 31 - __builtin_clz(op.hd);             // head_dim is 64 or 128
-    if constexpr (!ATT) {
 #pragma unroll
-        for (int q = 0; q < XQ; ++q) xr[q] = stream_load_x4(op.act_in + min((tid + q * NT) * 4, K - 4));
-    } else {
-        // (Requesting the partials between two halves of the first weight batch instead, so that the weight stream does
-        // not start behind these thirteen loads, needs 23 registers more than a wavefront has.)
-        const int pstr = op.hd + ATT_PAD;
-        {   // thread (h, c) = (tid >> 3, tid & 7): maximum and sum of chunk c of head h (clamped; masked below)
-            const int h = min(tid >> 3, op.H - 1), c = min(tid & 7, n_chunks - 1);
-            ml = stream_load_x2(op.att_part + ((size_t)h * op.att_max_chunks + c) * pstr + op.hd);
-        }
-#pragma unroll
-        for (int q = 0; q < AG; ++q) {
-            // four consecutive dimensions of one head, from every chunk (chunks past the last re-read it: weight zero)
-            const int e = min((tid + q * NT) * 4, K - 4);
-            const int h = e >> hd_shift, dim = e & (op.hd - 1);
-            const float *pp = op.att_part + (size_t)h * op.att_max_chunks * pstr + dim;
-#pragma unroll
-            for (int c = 0; c < AC; ++c) orr[q][c] = stream_load_x4(pp + min(c, n_chunks - 1) * pstr);
-        }
-    }
+    for (int q = 0; q < XQ; ++q) xr[q] = stream_load_x4(op.act_in + min((tid + q * NT) * 4, K - 4));
     float sh[4];
     {
         // KS_NWG = 4 x 64 shares per token row; without a norm in front of this GEMM the loads read the split table
@@ -569,55 +516,12 @@ __device__ __forceinline__ void gemv_device(const GemmOp &op, const PassCtl *ctl
             shape.H = pinned_here(op.H); shape.Hkv = pinned_here(op.Hkv); shape.hd = pinned_here(op.hd);
             int n_first_unused;
             build_row_table<true>(shape, pinned_here(wg), rowidx, &n_first_unused);
-            if constexpr (!ATT) {
-                stream_wait_pieces<8 + 6, XQ>(xr);          // the six small loads and the eight weight loads stay in flight
-                // (stores clamped like the loads: a duplicate writes the same value to the same place)
+            stream_wait_pieces<8 + 6, XQ>(xr);          // the six small loads and the eight weight loads stay in flight
+            // (stores clamped like the loads: a duplicate writes the same value to the same place)
 #pragma unroll
-                for (int q = 0; q < XQ; ++q) *reinterpret_cast<u32x4 *>(xs + min((tid + q * NT) * 4, K - 4)) = xr[q];
-                for (int i = (tid + XQ * NT) * 4; i < K; i += NT * 4) *reinterpret_cast<float4 *>(xs + i) = *reinterpret_cast<const float4 *>(op.act_in + i);
-                __syncthreads();
-            } else {
-                // Merge of the chunks (the arithmetic of attn_combine_device, operation for operation): per head the
-                // largest chunk maximum M, the chunks' weights f_c = exp(m_c - M), the sum L = sum_c l_c f_c in chunk
-                // order; per element O = sum_c o_c f_c in chunk order, then O / L.
-                stream_wait_x2<8 + 6 + AG * AC>(ml);
-                {
-                    const int c = tid & 7, h = tid >> 3;
-                    const float m = (c < n_chunks) ? __uint_as_float(ml.x) : -INFINITY;
-                    float M = m;
-                    M = fmaxf(M, __shfl_xor(M, 1, 64)); M = fmaxf(M, __shfl_xor(M, 2, 64)); M = fmaxf(M, __shfl_xor(M, 4, 64));
-                    const float f = (c < n_chunks && m > -INFINITY) ? expf(m - M) : 0.f;
-                    const float lc = __uint_as_float(ml.y);
-                    float L = 0.f;
-#pragma unroll
-                    for (int k = 0; k < 8; ++k) {
-                        const float fk = __shfl(f, (lane & ~7) + k, 64), lk = __shfl(lc, (lane & ~7) + k, 64);
-                        L = fmaf(lk, fk, L);
-                    }
-                    if (h < op.H) {
-                        if (c < AC) ftab[h * AC + c] = f;
-                        if (c == 0) ftab[op.H * AC + h] = L;
-                    }
-                }
-                __syncthreads();
-                stream_wait_12<8 + 6>(orr);
-#pragma unroll
-                for (int q = 0; q < AG; ++q) {
-                    const int e = min((tid + q * NT) * 4, K - 4);
-                    const int h = e >> hd_shift;
-                    float o0 = 0.f, o1 = 0.f, o2 = 0.f, o3 = 0.f;
-#pragma unroll
-                    for (int c = 0; c < AC; ++c) {
-                        const float f = ftab[h * AC + c];
-                        o0 = fmaf(__uint_as_float(orr[q][c].x), f, o0); o1 = fmaf(__uint_as_float(orr[q][c].y), f, o1);
-                        o2 = fmaf(__uint_as_float(orr[q][c].z), f, o2); o3 = fmaf(__uint_as_float(orr[q][c].w), f, o3);
-                    }
-                    const float L = ftab[op.H * AC + h];
-                    // (stores clamped like the loads: a duplicate writes the same value to the same place)
-                    *reinterpret_cast<float4 *>(xs + e) = make_float4(o0 / L, o1 / L, o2 / L, o3 / L);
-                }
-                __syncthreads();
-            }
+            for (int q = 0; q < XQ; ++q) *reinterpret_cast<u32x4 *>(xs + min((tid + q * NT) * 4, K - 4)) = xr[q];
+            for (int i = (tid + XQ * NT) * 4; i < K; i += NT * 4) *reinterpret_cast<float4 *>(xs + i) = *reinterpret_cast<const float4 *>(op.act_in + i);
+            __syncthreads();
         }
         float acc = 0.f;
         int u0 = 0;
@@ -681,16 +585,13 @@ __device__ __forceinline__ void gemv_device(const GemmOp &op, const PassCtl *ctl
     gemm_epilogue<false>(op, ctl, wg, nwg, R, s.n_first, rowidx, vals, 1, rstd_s, ctl->head_from, 1, scratch, xpre, gpre);
 }
 
-constexpr int ATT_FUSE_MAX_HEADS = 128;     // heads the fused merge's table in LDS holds
 __host__ __device__ inline size_t gemv_lds_bytes(int K) {
-    return (size_t)K * 4 + (size_t)MAX_LROWS * NWV * 4 + MAX_LROWS * 4 + MAX_LROWS * 4 + (4 * NWV + KS_MAX_ROWS) * 4 +
-           (size_t)ATT_FUSE_MAX_HEADS * (ATT_FUSE_CHUNKS + 1) * 4;
+    return (size_t)K * 4 + (size_t)MAX_LROWS * NWV * 4 + MAX_LROWS * 4 + MAX_LROWS * 4 + (4 * NWV + KS_MAX_ROWS) * 4;
 }
 
-template <bool ATT>
 __global__ __launch_bounds__(NT, 1) void gemv_kernel(GemmOp op, const PassCtl *ctl) {
     extern __shared__ __align__(16) char lds[];
-    gemv_device<ATT>(op, ctl, blockIdx.x, gridDim.x, lds);
+    gemv_device(op, ctl, blockIdx.x, gridDim.x, lds);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1171,6 +1072,39 @@ struct AttnArgs {
                              // last workgroup of a group merges the chunks itself; nullptr: attn_combine_kernel follows
 };
 
+// ------------------------------------------------------------------------------------------
+// Merging the chunks inside the attention launch. The workgroup that finishes the last chunk of a group of (row, head)
+// pairs merges the group's chunks and hands the result to the O projection, so no merge launch follows. Nobody waits:
+// every workgroup writes its partial through to memory (agent-scope stores), waits for the writes to be acknowledged
+// and counts itself in; the one that draws the last number reads the group's partials back from memory (agent-scope
+// loads: another compute die's L2 may hold older lines of the buffer) and runs the arithmetic of attn_combine_device,
+// operation for operation, so a value does not depend on where it was merged. The counter is left at zero.
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ void store_agent(float *p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void load2_agent(const float *p, float &a, float &b) {      // p 8-byte aligned
+    const unsigned long long v = __hip_atomic_load(reinterpret_cast<const unsigned long long *>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    a = __uint_as_float((unsigned int)v); b = __uint_as_float((unsigned int)(v >> 32));
+}
+
+// Called by every thread of the workgroup after its partial's stores: true in the workgroup that arrives last of the
+// group's n_expected (uniform). ticket: one int of LDS; the caller's next workgroup meeting orders its reuse.
+__device__ __forceinline__ bool last_arrival(int *counter, int n_expected, int *ticket) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // this thread's partial stores have been acknowledged
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const int t = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (t == n_expected - 1) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *ticket = t;
+    }
+    __syncthreads();
+    return *ticket == n_expected - 1;
+}
+
+struct AttnArgs;
+template <int HD>
+__device__ __forceinline__ void merge_pairs_device(const AttnArgs &a, int kvh, int p_base, int n_p, int group, float inv_group,
+                                                   int start, int tid, int nt);
+
 template <int HD>
 __device__ __forceinline__ void attn_partial_device(const AttnArgs &a, const PassCtl *ctl, int wg, int nwg, char *lds) {
     constexpr int LPP = HD / 8;        // lanes per position
@@ -1187,6 +1121,7 @@ __device__ __forceinline__ void attn_partial_device(const AttnArgs &a, const Pas
     const int n_items = a.Hkv * n_chunks * n_pg;
     float *qs = reinterpret_cast<float *>(lds);                         // [ATT_PG][HD]
     float *red = qs + ATT_PG * HD;                                      // [NWV][ATT_PG][HD + 2]
+    int *ticket = reinterpret_cast<int *>(red + NWV * ATT_PG * (HD + 2));
     const float scale = 1.0f / sqrtf((float)HD);
     const size_t kv_head_stride = (size_t)a.max_seq * HD;
 
@@ -1283,13 +1218,82 @@ __device__ __forceinline__ void attn_partial_device(const AttnArgs &a, const Pas
                 O = fmaf(rp[dim], f, O);
             }
             float *out = a.partial + (((size_t)m * a.H + h) * a.max_chunks + chunk) * (HD + ATT_PAD);
-            out[dim] = O;
-            if (dim == 0) { out[HD] = M; out[HD + 1] = L; }
+            if (a.arrivals) {
+                store_agent(out + dim, O);
+                if (dim == 0) { store_agent(out + HD, M); store_agent(out + HD + 1, L); }
+            } else {
+                out[dim] = O;
+                if (dim == 0) { out[HD] = M; out[HD + 1] = L; }
+            }
         }
+        if (a.arrivals && last_arrival(a.arrivals + pg * a.Hkv + kvh, n_chunks, ticket))
+            merge_pairs_device<HD>(a, kvh, p_base, n_p, group, inv_group, start, tid, NT);
     }
 }
 
-__host__ __device__ inline size_t attn_lds_bytes(int hd) { return (size_t)(ATT_PG * hd + NWV * ATT_PG * (hd + 2)) * 4; }
+// The merge itself, by the nt threads of the calling workgroup: pairs [p_base, p_base + n_p) of kv head kvh, two
+// neighbouring dimensions per thread and step (8-byte agent-scope loads).
+template <int HD>
+__device__ __forceinline__ void merge_pairs_device(const AttnArgs &a, int kvh, int p_base, int n_p, int group, float inv_group,
+                                                   int start, int tid, int nt) {
+    constexpr int CB = 8, PSTR = HD + ATT_PAD, H2 = HD / 2;
+    const int qd = a.H * HD;
+    const float inv_kc = __builtin_amdgcn_rcpf((float)a.out_kc);
+    GemmOp st{};   // only the fields store_act uses
+    st.act_out = a.act_out; st.out_kc = a.out_kc; st.n_rows = a.n_rows;
+    for (int i = tid; i < n_p * H2; i += nt) {
+        const int pl = i / H2, dim = (i - pl * H2) * 2, p = p_base + pl;
+        const int m = div_small(p, group, inv_group), h = kvh * group + (p - m * group);
+        const int nc_m = (start + m + 1 + ATT_CHUNK - 1) / ATT_CHUNK;   // chunks row m can see
+        const float *pp = a.partial + ((size_t)m * a.H + h) * a.max_chunks * PSTR;
+        float mv0[CB], lv0[CB], oa0[CB], ob0[CB];
+#pragma unroll
+        for (int k = 0; k < CB; ++k) {
+            const float *cp = pp + (size_t)min(k, nc_m - 1) * PSTR;
+            load2_agent(cp + HD, mv0[k], lv0[k]);
+            load2_agent(cp + dim, oa0[k], ob0[k]);
+        }
+        float M = -INFINITY;
+#pragma unroll
+        for (int k = 0; k < CB; ++k) M = fmaxf(M, mv0[k]);
+        for (int base = CB; base < nc_m; base += CB) {
+#pragma unroll
+            for (int k = 0; k < CB; ++k) {
+                float mk, lk;
+                load2_agent(pp + (size_t)min(base + k, nc_m - 1) * PSTR + HD, mk, lk);
+                M = fmaxf(M, mk);
+            }
+        }
+        float L = 0.f, Oa = 0.f, Ob = 0.f;
+#pragma unroll
+        for (int k = 0; k < CB; ++k) {
+            const float f = (k < nc_m && mv0[k] > -INFINITY) ? expf(mv0[k] - M) : 0.f;
+            L = fmaf(lv0[k], f, L);
+            Oa = fmaf(oa0[k], f, Oa);
+            Ob = fmaf(ob0[k], f, Ob);
+        }
+        for (int base = CB; base < nc_m; base += CB) {
+            float mv[CB], lv[CB], oa[CB], ob[CB];
+#pragma unroll
+            for (int k = 0; k < CB; ++k) {
+                const float *cp = pp + (size_t)min(base + k, nc_m - 1) * PSTR;
+                load2_agent(cp + HD, mv[k], lv[k]);
+                load2_agent(cp + dim, oa[k], ob[k]);
+            }
+#pragma unroll
+            for (int k = 0; k < CB; ++k) {
+                const float f = (base + k < nc_m && mv[k] > -INFINITY) ? expf(mv[k] - M) : 0.f;
+                L = fmaf(lv[k], f, L);
+                Oa = fmaf(oa[k], f, Oa);
+                Ob = fmaf(ob[k], f, Ob);
+            }
+        }
+        store_act<true>(st, m, h * HD + dim, qd, Oa / L, inv_kc);
+        store_act<true>(st, m, h * HD + dim + 1, qd, Ob / L, inv_kc);
+    }
+}
+
+__host__ __device__ inline size_t attn_lds_bytes(int hd) { return (size_t)(ATT_PG * hd + NWV * ATT_PG * (hd + 2) + 4) * 4; }
 
 template <int HD>
 __global__ __launch_bounds__(NT) void attn_partial_kernel(AttnArgs a, const PassCtl *ctl) {

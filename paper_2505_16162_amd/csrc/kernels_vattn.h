@@ -30,11 +30,6 @@ static_assert(VA_WP % 32 == 0 && VA_WP * VA_NW == ATT_CHUNK, "whole summation st
 
 typedef unsigned int va_u32x2 __attribute__((ext_vector_type(2)));
 
-// stores that are written through to memory and loads that do not trust a compute die's own L2: how workgroups on
-// different dies hand each other data inside one launch
-__device__ __forceinline__ void store_agent(float *p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
-__device__ __forceinline__ float load_agent(const float *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
-
 template <int HD>
 __host__ __device__ constexpr size_t vattn_lds_bytes() {
     // per wavefront: the P tile [16][positions + 4] fp32 and its share [16][HD + 4] fp32 of the merge buffer
@@ -244,65 +239,8 @@ __global__ __launch_bounds__(VA_NT) void attn_partial_mfma_kernel(AttnArgs a, co
             }
         }
         if (!last_merges) continue;
-        // The workgroup that finishes the last chunk of a (pair tile, kv head) group merges the group's chunks and
-        // hands the result to the O projection, so no merge launch follows. Nobody waits: every workgroup writes its
-        // partial through to memory (agent-scope stores), waits for the writes to be acknowledged, and counts itself in;
-        // the one that draws the last number reads the group's partials back from memory (agent-scope loads: another
-        // compute die's L2 may hold older lines of the buffer) and runs the arithmetic of attn_combine_device,
-        // operation for operation, so a value does not depend on where it was merged. The counter is left at zero.
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-        int *cnt = a.arrivals + pt * a.Hkv + kvh;
-        if (tid == 0) tickets[0] = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __syncthreads();
-        const int ticket = tickets[0];
-        if (ticket != n_chunks - 1) continue;                   // (the next item's first meeting orders the reuse of tickets[0])
-        if (tid == 0) __hip_atomic_store(cnt, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const float inv_kc = __builtin_amdgcn_rcpf((float)a.out_kc);
-        GemmOp st{};   // only the fields store_act uses
-        st.act_out = a.act_out; st.out_kc = a.out_kc; st.n_rows = a.n_rows;
-        constexpr int CB = 8;
-        for (int i = tid; i < n_p * HD; i += VA_NT) {
-            const int pl = i / HD, dim = i - pl * HD, p = pt * 16 + pl;
-            const int m = div_small(p, group, inv_group), h = kvh * group + (p - m * group);
-            const int nc_m = (start + m + 1 + ATT_CHUNK - 1) / ATT_CHUNK;   // chunks row m can see
-            const float *pp = a.partial + ((size_t)m * a.H + h) * a.max_chunks * (HD + ATT_PAD);
-            float mv0[CB], lv0[CB], ov0[CB];
-#pragma unroll
-            for (int k = 0; k < CB; ++k) {
-                const float *cp = pp + (size_t)min(k, nc_m - 1) * (HD + ATT_PAD);
-                mv0[k] = load_agent(cp + HD); lv0[k] = load_agent(cp + HD + 1); ov0[k] = load_agent(cp + dim);
-            }
-            float M = -INFINITY;
-#pragma unroll
-            for (int k = 0; k < CB; ++k) M = fmaxf(M, mv0[k]);
-            for (int base = CB; base < nc_m; base += CB) {
-#pragma unroll
-                for (int k = 0; k < CB; ++k) M = fmaxf(M, load_agent(pp + (size_t)min(base + k, nc_m - 1) * (HD + ATT_PAD) + HD));
-            }
-            float L = 0.f, O = 0.f;
-#pragma unroll
-            for (int k = 0; k < CB; ++k) {
-                const float f = (k < nc_m && mv0[k] > -INFINITY) ? expf(mv0[k] - M) : 0.f;
-                L = fmaf(lv0[k], f, L);
-                O = fmaf(ov0[k], f, O);
-            }
-            for (int base = CB; base < nc_m; base += CB) {
-                float mv[CB], lv[CB], ov[CB];
-#pragma unroll
-                for (int k = 0; k < CB; ++k) {
-                    const float *cp = pp + (size_t)min(base + k, nc_m - 1) * (HD + ATT_PAD);
-                    mv[k] = load_agent(cp + HD); lv[k] = load_agent(cp + HD + 1); ov[k] = load_agent(cp + dim);
-                }
-#pragma unroll
-                for (int k = 0; k < CB; ++k) {
-                    const float f = (base + k < nc_m && mv[k] > -INFINITY) ? expf(mv[k] - M) : 0.f;
-                    L = fmaf(lv[k], f, L);
-                    O = fmaf(ov[k], f, O);
-                }
-            }
-            store_act<true>(st, m, h * HD + dim, qd, O / L, inv_kc);
-        }
+        if (!last_arrival(a.arrivals + pt * a.Hkv + kvh, n_chunks, tickets)) continue;
+        merge_pairs_device<HD>(a, kvh, pt * 16, n_p, group, inv_group, start, tid, VA_NT);
     }
 }
 

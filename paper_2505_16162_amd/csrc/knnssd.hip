@@ -242,9 +242,7 @@ extern "C" int32_t knnssd_create(const knnssd_model_cfg *cfg, const knnssd_weigh
     // choice is per context (never per pass), so a row's result does not depend on how many rows share its pass.
     c->verify_attn_mfma = cfg->verify_attn == KNNSSD_ATTN_MFMA;
     if (c->tuned) {
-        hipError_t ea = hipFuncSetAttribute((const void *)gemv_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, KS_MAX_DYN_LDS);
-        if (ea == hipSuccess)
-            ea = hipFuncSetAttribute((const void *)gemv_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, KS_MAX_DYN_LDS);
+        hipError_t ea = hipFuncSetAttribute((const void *)gemv_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, KS_MAX_DYN_LDS);
         if (ea == hipSuccess)
             ea = hipFuncSetAttribute((const void *)gemm_mfma_kernel<false, false>, hipFuncAttributeMaxDynamicSharedMemorySize, KS_MAX_DYN_LDS);
         if (ea == hipSuccess)
@@ -504,8 +502,7 @@ static int32_t run_pass_bf16(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, b
         return kc_of(OP_HEAD, g.vocab, d);
     };
     auto launch = [&](const GemmOp &op) {
-        if (rows1 && op.att_part) hipLaunchKernelGGL(gemv_kernel<true>, dim3(KS_NWG), dim3(NT), gemv_lds_bytes(op.K), s, op, ctl);
-        else if (rows1) hipLaunchKernelGGL(gemv_kernel<false>, dim3(KS_NWG), dim3(NT), gemv_lds_bytes(op.K), s, op, ctl);
+        if (rows1) hipLaunchKernelGGL(gemv_kernel, dim3(KS_NWG), dim3(NT), gemv_lds_bytes(op.K), s, op, ctl);
         else {
             GemmOp v = op;
             v.max_rows = max_rows_of(v.type, v.N);
@@ -552,18 +549,13 @@ static int32_t run_pass_bf16(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, b
     aa.q = qrot; aa.partial = c->wsp<float>(c->L.attn_part); aa.H = H; aa.Hkv = Hkv; aa.hd = hd; aa.max_seq = g.max_seq; aa.group = H / Hkv;
     aa.max_chunks = (g.max_seq + ATT_CHUNK - 1) / ATT_CHUNK; aa.act_out = att;
     aa.n_rows = n_rows; aa.out_kc = kc_of(OP_RESID, d, qd);
-    // Draft steps whose row sees at most ATT_FUSE_CHUNKS chunks: the O projection merges the chunks' partials in its own
-    // prologue (gemv_kernel<true>) and the merge launch is dropped. Longer contexts, wider models and verification
-    // passes keep attn_combine_kernel.
     // Where the chunks of the split-KV attention are merged (the arithmetic is the same everywhere, so a value does not
-    // depend on the choice). Few (row, head) pairs per kv head on the matrix-core kernel: the workgroup that finishes a
-    // group's last chunk merges the group (13B-shaped, 2 rows: -2.7 us per block against the merge launch; with 45 pairs
-    // per kv head, Qwen-shaped 9 rows, the one workgroup's serial merge costs 5 us per block MORE than the launch that
-    // spreads it over the chip). Draft steps otherwise: inside the O projection while the row sees few enough chunks.
+    // depend on the choice). Few (row, head) pairs per kv head: the workgroup that finishes a group's last chunk merges
+    // the group inside the attention launch (13B-shaped: -2.7 us per block at 2 rows, -2.4 us per draft step, against
+    // the merge launch). Many pairs (Qwen-shaped 9 rows: 45 per kv head): the one workgroup's serial merge costs 5 us per
+    // block MORE than the launch that spreads it over the chip, so that launch stays.
     const bool mfma_attn = (!rows1 || aa.group >= 2) && c->verify_attn_mfma;
-    const bool self_merge = mfma_attn && c->cfg.attn_merge == KNNSSD_MERGE_FUSED && n_rows * aa.group <= 4;
-    const bool fuse_merge = rows1 && !self_merge && c->cfg.attn_merge == KNNSSD_MERGE_FUSED &&
-                            start + 1 <= ATT_FUSE_CHUNKS * ATT_CHUNK && qd <= ATT_FUSE_GROUPS * NT * 4 && H <= ATT_FUSE_MAX_HEADS;
+    const bool self_merge = c->cfg.attn_merge == KNNSSD_MERGE_FUSED && n_rows * aa.group <= ATT_SELF_MERGE_PAIRS;
     for (int b = 0; b < g.n_blocks; ++b) {
         bf16_t *kvb = (bf16_t *)(c->kv + (size_t)b * c->kv_block_bytes);
         if (!(mask && mask[2 * b])) {
@@ -581,14 +573,13 @@ static int32_t run_pass_bf16(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, b
                 else hipLaunchKernelGGL((attn_partial_mfma_kernel<64>), dim3(2 * KS_NWG), dim3(VA_NT), vattn_lds_bytes<64>(), s, aa, ctl);
             } else if (hd == 128) hipLaunchKernelGGL((attn_partial_kernel<128>), dim3(KS_NWG), dim3(NT), attn_lds_bytes(128), s, aa, ctl);
             else hipLaunchKernelGGL((attn_partial_kernel<64>), dim3(KS_NWG), dim3(NT), attn_lds_bytes(64), s, aa, ctl);
-            if (!others || fuse_merge || self_merge) {
+            if (!others || self_merge) {
             } else if (rows1) hipLaunchKernelGGL((attn_combine_kernel<false>), dim3(16), dim3(NT), 0, s, aa, ctl);
             else hipLaunchKernelGGL((attn_combine_kernel<true>), dim3(64), dim3(NT), 0, s, aa, ctl);
             GemmOp r = base;
             r.type = OP_RESID; r.W = (const bf16_t *)c->wo[b]; r.N = d; r.K = qd; r.act_in = att;
             r.ss_in = nullptr; r.x = x; r.gain_next = next_gain(c, mask, 2 * b); r.act_out = act_d;
             r.ss_out = ss; r.split = c->split_o; r.out_kc = kc_next(2 * b);
-            if (fuse_merge) { r.att_part = aa.partial; r.att_max_chunks = aa.max_chunks; }
             launch(r);
         }
         if (!(mask && mask[2 * b + 1])) {

@@ -255,11 +255,12 @@ def test_tile_counts_of_three_five_and_six_per_workgroup():
 
 
 @pytest.mark.parametrize("gqa", [False, True])
-def test_draft_step_merge_inside_the_output_projection(gqa):
-    """A draft step whose row sees at most six 256-position chunks merges the chunks of its split-KV attention in the
-    prologue of the output projection (cfg.attn_merge = KNNSSD_MERGE_FUSED, the default); the same step with the merge
-    as a launch of its own (KNNSSD_MERGE_SEPARATE) must give the same bits, at one, two and six chunks, and both are
-    checked against the oracle. Beyond six chunks both contexts take the separate launch."""
+def test_merge_inside_the_attention_launch(gqa):
+    """With few (row, head) pairs per kv head the attention launch merges its own chunks (cfg.attn_merge =
+    KNNSSD_MERGE_FUSED, the default: the workgroup that finishes a group's last chunk does it); the same steps with the
+    merge as a launch of its own (KNNSSD_MERGE_SEPARATE) must give the same bits, at one, two, six and seven chunks,
+    for draft steps (vector-ALU kernel, or the matrix-core one with grouped-query heads) and for verification passes of
+    1, 3 and 5 rows (more than four pairs per kv head keep the launch), and both are checked against the oracle."""
     shape = synth.small_shape("fuse_gqa" if gqa else "fuse_mha", n_blocks=2, d_model=512, n_heads=8, n_kv_heads=2 if gqa else 8,
                               head_dim=64, d_ffn=1408, vocab=900, max_seq=1700)
     w, orc, gpu = make_pair(shape, seed=37, std=0.04)
@@ -284,6 +285,17 @@ def test_draft_step_merge_inside_the_output_projection(gqa):
             assert ok, (plen, i, err)
             assert t1 == O.argmax_lowest(row)
             tok = t1
+    # verification rows on the three contexts (the matrix-core kernel merges one- and three-row passes itself unless
+    # the merge is a launch of its own)
+    rows_in = [first_o] + synth.make_prompt(shape.vocab, 4, seed=8).tolist()
+    for n in (1, 3, 5):
+        got = []
+        for g in (gpu, gpu2):
+            g.knnssd_prefill(prompt)
+            g.knnssd_verify(rows_in[:n], len(prompt))
+            got.append([g.knnssd_get_logits(r).clone() for r in range(n)])
+        for r in range(n):
+            assert torch.equal(got[0][r], got[1][r]), (n, r)
     gpu.close()
     gpu2.close()
 
