@@ -31,49 +31,72 @@ COPY_BYTES = 1 << 30          # size of the calibration copy of --traffic-probe
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "gemm_mfma_kernel_llama13b_hbm_traffic.md")
 
 
+FAMILIES = (("gemm_mfma_kernel<false", "verification GEMM"), ("gemv_kernel", "draft GEMV"),
+            ("attn_partial_mfma_kernel", "attention, matrix cores (verification)"),
+            ("attn_partial_kernel", "attention, vector ALUs (draft)"), ("attn_combine_kernel", "attention merge launch"))
+
+
 def traffic_parse(fetch_csv, write_csv):
-    """Per-launch HBM traffic of the verification GEMM from two `rocprofv3 --pmc` runs of
-    `bench.py --traffic-probe` (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch). Each counter is scaled by
-    what it reads for the plain copy of COPY_BYTES in the same run."""
+    """Per-launch HBM traffic of the path's kernels from two `rocprofv3 --pmc` runs of `bench.py --traffic-probe`
+    (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch). Each counter is scaled by what it reads for the plain copy of
+    COPY_BYTES in the same run."""
     import csv
 
     def per_kernel(path, counter):
         rows = [r for r in csv.DictReader(open(path)) if r["Counter_Name"] == counter]
         rows.sort(key=lambda r: int(r["Dispatch_Id"]))
-        copy, gemm = None, []
+        copy, fam, seen_ours = None, {}, False
         for r in rows:
             name = r["Kernel_Name"]
-            if "gemm_mfma_kernel<false" in name:      # the verification launches (first template argument: not prefill)
-                gemm.append(float(r["Counter_Value"]))
-            elif "MulFunctor" in name and not gemm:
+            hit = next((f for f, _ in FAMILIES if f in name), None)
+            if hit:
+                fam.setdefault(hit, []).append(float(r["Counter_Value"]))
+                seen_ours = seen_ours or hit.startswith(("gemm", "gemv"))
+            elif "MulFunctor" in name and not seen_ours:
                 copy = float(r["Counter_Value"])           # the last multiply before the passes is the calibration copy
-        return copy, gemm
+        return copy, fam
 
     out = {}
     for tag, path, counter in (("read", fetch_csv, "FETCH_SIZE"), ("write", write_csv, "WRITE_SIZE")):
-        copy, gemm = per_kernel(path, counter)
-        copy_v = copy
-        scale = COPY_BYTES / (copy_v * 1024.0)             # true bytes per counted byte
-        out[tag] = {"copy_counter_KiB": copy_v, "scale": scale, "launches": len(gemm),
-                    "gemm_avg_KiB": sum(gemm) / len(gemm), "bytes_per_launch": scale * 1024.0 * sum(gemm) / len(gemm)}
-    total = out["read"]["bytes_per_launch"] + out["write"]["bytes_per_launch"]
-    for tag in ("read", "write"):
-        o = out[tag]
-        print(f"{tag}: copy of {COPY_BYTES} B counted as {o['copy_counter_KiB']:.0f} KiB -> scale {o['scale']:.4f}; "
-              f"gemm_mfma_kernel<false, *>: {o['launches']} launches, avg counter {o['gemm_avg_KiB']:.0f} KiB "
-              f"-> {o['bytes_per_launch']:.0f} B per launch")
-    print(f"traffic_bytes_per_launch: {total:.0f}")
+        copy, fam = per_kernel(path, counter)
+        scale = COPY_BYTES / (copy * 1024.0)             # true bytes per counted byte
+        print(f"{tag}: copy of {COPY_BYTES} B counted as {copy:.0f} KiB -> scale {scale:.4f}")
+        out[tag] = {f: (len(v), scale * 1024.0 * sum(v) / len(v)) for f, v in fam.items()}
+    print("| kernel | launches | fetched B per launch | written B per launch | total B per launch |")
+    print("|---|---|---|---|---|")
+    for f, label in FAMILIES:
+        if f in out["read"]:
+            n, rd = out["read"][f]
+            wr = out["write"].get(f, (0, 0.0))[1]
+            print(f"| `{f}` ({label}) | {n} | {rd:.0f} | {wr:.0f} | {rd + wr:.0f} |")
+    g = "gemm_mfma_kernel<false"
+    print(f"traffic_bytes_per_launch: {out['read'][g][1] + out['write'][g][1]:.0f}")
+    print(f"kernel_source_sha16: {kernel_source_sha16()}")
+
+
+def kernel_source_sha16():
+    """Hash of the library's sources: a counter measurement belongs to the kernels it was taken on."""
+    import hashlib
+    h = hashlib.sha256()
+    src = os.path.join(ROOT, "paper_2505_16162_amd", "csrc")
+    for name in sorted(os.listdir(src)):
+        h.update(open(os.path.join(src, name), "rb").read())
+    return h.hexdigest()[:16]
 
 
 def recorded_traffic():
-    """HBM bytes per launch of the verification GEMM as last measured with the counters (None if never)."""
+    """HBM bytes per launch of the verification GEMM as measured with the counters (profiles/), or None when
+    there is no measurement or it was taken on other kernel sources than the ones this run uses."""
+    val, sha = None, None
     try:
         for line in open(TRAFFIC_FILE):
             if line.startswith("traffic_bytes_per_launch:"):
-                return float(line.split(":")[1])
+                val = float(line.split(":")[1])
+            if line.startswith("kernel_source_sha16:"):
+                sha = line.split(":")[1].strip()
     except OSError:
-        pass
-    return None
+        return None
+    return val if sha == kernel_source_sha16() else None
 
 
 def pass_bytes(shape, mask, ctx, rows):
@@ -102,6 +125,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="llama13b")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the planted-acceptance and routing-scan sub-records of the benchmark line")
     ap.add_argument("--cpu-tokens", type=int, default=6, help="tokens the CPU oracle decodes for its baseline")
     ap.add_argument("--max-new", type=int, default=0, help="override the workload's generation length")
     ap.add_argument("--prompt-len", type=int, default=0, help="override the workload's prompt length")
@@ -180,9 +205,9 @@ def main():
         torch.cuda.synchronize()
         torch.mul(src, 1.0, out=dst)         # the calibration kernel: a plain elementwise copy, reads and writes COPY_BYTES
         torch.cuda.synchronize()
-        gpu.knnssd_prefill(prompt)
-        for _ in range(3):
-            gpu.knnssd_profile_pass(1, prompt[:2], prompt_len)
+        # a few whole rounds of the benchmark's own generation: draft steps (GEMV, vector-ALU attention) and two-row
+        # verification passes (GEMM, matrix-core attention) at context 1024..., every kernel of the path included
+        gpu.knnssd_generate(prompt, 6, wl.max_draft, wl.conf_threshold)
         torch.cuda.synchronize()
         gpu.close()
         return
@@ -253,6 +278,8 @@ def main():
                 "rows": n_ver, "context": prompt_len}
         d = gpu.knnssd_profile_pass(0, rows[:1], prompt_len)
         roof["draft_gemv_kernel_GBps"] = round(d["gemm_bytes"] / (d["gemm_ns"] * 1e-9) / 1e9, 1)
+        if roof["traffic"] is None:
+            roof["traffic_note"] = "no counter measurement for these kernel sources under profiles/"
     except binding.KnnSsdError as e:       # shape runs on the generic kernels
         roof["note"] = f"per-kernel events unavailable: {e}"
 
@@ -286,13 +313,24 @@ def main():
         "draft_pass": {"ms": round(draft_ms, 4), "GB": round(db / 1e9, 3), "GBps": round(draft_gbs, 1),
                        "frac_of_peak": round(draft_gbs / HBM_PEAK_GBS, 4)},
         "roofline": roof,
+        # the target the path is built against: each pass as a whole (every kernel and gap) against the HBM peak
+        "pass_roofline": {"target_frac": 0.70, "verify_frac": round(verify_gbs / HBM_PEAK_GBS, 4),
+                          "draft_frac": round(draft_gbs / HBM_PEAK_GBS, 4),
+                          "met": bool(verify_gbs / HBM_PEAK_GBS >= 0.70 and draft_gbs / HBM_PEAK_GBS >= 0.70)},
         "setup_s": round(t_setup, 1),
     }
+    gpu.close()
+    gpu = None
+    if not args.no_extras and args.workload == "llama13b":
+        # what the rounds are worth when drafts are accepted (random weights accept none), and the routing scan where
+        # it is bound by HBM: sub-records of the same line
+        out["planted_acceptance"] = planted_acceptance_record(wl, shape, w, prompt, max_new)
+        out["knn_scan"] = {k: v for k, v in knn_probe(200000, dev).items() if k not in ("mode",)}
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(shape, w, wl, mask, args.cpu_tokens)
+        out["cpu_baseline_tiny_config"] = cpu_baseline_tiny()
     print(json.dumps(out))
-    gpu.close()
 
 
 def stream_mode(args, gpu, wl, shape, centres, prompt_len, max_new, dev):
@@ -326,20 +364,100 @@ def knn_probe(n_anchors, dev):
     gpu = binding.KnnSsd(shape, synth.make_weights(shape, device=dev), max_anchors=n_anchors)
     anchors, labels, centres = synth.make_anchors(d, n_anchors, n_dom, 0.1, device=dev)
     gpu.knnssd_set_anchors(anchors, labels, synth.make_block_masks(1, n_dom, 1))
-    out = {"mode": "knn-probe", "anchors": n_anchors, "dim": d, "k": k, "table_GB": round(n_anchors * d * 4 / 1e9, 3)}
-    for nq in (1, 4):
-        queries = torch.stack([synth.make_domain_query(centres, i % n_dom, 0.1, seed=i) for i in range(nq)])
-        idx, _, dom = gpu.knnssd_knn_topk(queries, k)
-        assert dom == [i % n_dom for i in range(nq)]
-        torch.cuda.synchronize()
-        reps = 5
-        t0 = time.time()
-        for _ in range(reps):
-            gpu.knnssd_knn_topk(queries, k)
-        dt = (time.time() - t0) / reps
-        out[f"q{nq}"] = {"ms": round(dt * 1e3, 3), "scan_GBps": round(n_anchors * d * 4 / dt / 1e9, 1),
-                         "frac_of_peak": round(n_anchors * d * 4 / dt / 1e9 / HBM_PEAK_GBS, 4)}
+    out = {"mode": "knn-probe", "anchors": n_anchors, "dim": d, "k": k, "table_GB_fp32": round(n_anchors * d * 4 / 1e9, 3)}
+    for tag, table, eb in (("fp32", anchors, 4), ("bf16", anchors.to(torch.bfloat16), 2)):
+        gpu.knnssd_set_anchors(table, labels, synth.make_block_masks(1, n_dom, 1))
+        for nq in (1, 4):
+            queries = torch.stack([synth.make_domain_query(centres, i % n_dom, 0.1, seed=i) for i in range(nq)])
+            idx, _, dom = gpu.knnssd_knn_topk(queries, k)
+            assert dom == [i % n_dom for i in range(nq)]
+            torch.cuda.synchronize()
+            reps = 5
+            t0 = time.time()
+            for _ in range(reps):
+                gpu.knnssd_knn_topk(queries, k)
+            dt = (time.time() - t0) / reps
+            out[f"{tag}_q{nq}"] = {"ms": round(dt * 1e3, 3), "scan_GBps": round(n_anchors * d * eb / dt / 1e9, 1),
+                                   "frac_of_peak": round(n_anchors * d * eb / dt / 1e9 / HBM_PEAK_GBS, 4)}
+    out["note"] = "K = 8 nearest anchors per query, whole call (scan, two-stage selection, read-back), host-timed"
     gpu.close()
+    return out
+
+
+def planted_acceptance_record(wl, shape, w, prompt, max_new):
+    """Sub-record of the benchmark line: acceptance 1 planted as in full_acceptance_probe (the skipped blocks'
+    output projections zeroed, which makes them identities), rounds of max_draft drafts and max_draft + 1 verified
+    rows, no confidence stop. Reports tokens/s against AR on the same weights and the many-row verification pass."""
+    import torch
+    from paper_2505_16162_amd import binding, synth
+    mask = synth.make_block_masks(shape.n_blocks, 1, wl.skipped_blocks)[0].tolist()
+    saved = {}
+    for b, blk in enumerate(w["blocks"]):
+        for key, bit in (("wo", 2 * b), ("wd", 2 * b + 1)):
+            if mask[bit]:
+                saved[(b, key)] = blk[key].clone()
+                blk[key].zero_()
+    gpu = binding.KnnSsd(shape, w)
+    for (b, key), t in saved.items():
+        w["blocks"][b][key].copy_(t)           # the caller's weights are left as they were
+    gpu.knnssd_set_skipset(mask)
+    gpu.knnssd_generate(prompt, max_new, 0)
+    ar_toks, ar_st = gpu.knnssd_generate(prompt, max_new, 0)
+    ar_tps = (ar_st["emitted"] - 1) / (ar_st["ns_verify"] * 1e-9)
+    k = wl.max_draft
+    gpu.knnssd_generate(prompt, max_new, k, 0.0, route=False)
+    toks, st = gpu.knnssd_generate(prompt, max_new, k, 0.0, route=False)
+    dec = st["ns_draft"] + st["ns_verify"]
+    tps = (st["emitted"] - 1) / (dec * 1e-9)
+    rows = st["drafted"] / max(st["rounds"], 1) + 1
+    v_ms = st["ns_verify"] * 1e-6 / max(st["verify_passes"], 1)
+    d_ms = st["ns_draft"] * 1e-6 / max(st["draft_passes"], 1)
+    ctx_mean = len(prompt) + max_new // 2
+    vb = pass_bytes(shape, [0] * (2 * shape.n_blocks), ctx_mean, rows)
+    gpu.close()
+    return {"what": "acceptance 1 planted (skipped blocks made identities), no confidence stop", "max_draft": k,
+            "tokens_per_s": round(tps, 2), "ar_tokens_per_s_same_weights": round(ar_tps, 2),
+            "speedup_over_ar": round(tps / ar_tps, 3), "equals_ar_tokens": toks == ar_toks,
+            "mean_generated_length_M": round((st["emitted"] - 1) / max(st["rounds"], 1), 3),
+            "acceptance_rate_alpha": round(st["accepted"] / max(st["drafted"], 1), 4),
+            "verify_pass": {"rows": round(rows, 2), "ms": round(v_ms, 4), "GBps": round(vb / (v_ms * 1e-3) / 1e9, 1),
+                            "frac_of_peak": round(vb / (v_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
+            "draft_pass_ms": round(d_ms, 4), "ms_per_round": round(dec * 1e-6 / max(st["rounds"], 1), 3)}
+
+
+def cpu_baseline_tiny():
+    """The oracle on the tiny configuration in full (prompt 32, 32 greedy tokens, 4 drafts per round, routing over
+    8 anchors), plain autoregressive and KNN-SSD, with one thread and with every core of this box."""
+    import ctypes
+    import numpy as np
+    from oracle import knnssd_oracle as O
+    from paper_2505_16162_amd import synth
+    wl = synth.workload("tiny")
+    w = synth.make_weights(wl.shape)
+    prompt = synth.make_prompt(wl.shape.vocab, wl.prompt_len).tolist()
+    anchors, labels, _ = synth.make_anchors(wl.shape.d_model, wl.n_anchors, wl.n_domains, 1.0, clustered=False)
+    masks = synth.make_block_masks(wl.shape.n_blocks, wl.n_domains, wl.skipped_blocks)
+    model = O.OracleModel(wl.shape, w)
+    all_cores = int(os.environ.get("OMP_NUM_THREADS", "0")) or len(os.sched_getaffinity(0))
+    try:
+        omp = ctypes.CDLL("libgomp.so.1")
+    except OSError:
+        omp = None
+    out = {"config": "tiny: 4 blocks d=256 fp32, prompt 32, 32 tokens, 4 drafts per round, 8 anchors"}
+    for threads in ((1, all_cores) if omp is not None else (all_cores,)):
+        if omp is not None:
+            omp.omp_set_num_threads(int(threads))
+        t0 = time.time()
+        O.greedy_ar(model, prompt, wl.max_new)
+        t_ar = time.time() - t0
+        t0 = time.time()
+        O.knnssd_generate(model, prompt, anchors.numpy(), labels.numpy(), masks.numpy(), wl.max_new, wl.max_draft,
+                          wl.conf_threshold)
+        t_ssd = time.time() - t0
+        out["threads_%d" % threads] = {"ar_tokens_per_s": round(wl.max_new / t_ar, 2),
+                                       "knnssd_tokens_per_s": round(wl.max_new / t_ssd, 2)}
+    if omp is not None:
+        omp.omp_set_num_threads(int(all_cores))
     return out
 
 
