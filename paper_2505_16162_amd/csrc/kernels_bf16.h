@@ -24,6 +24,7 @@ constexpr int MAX_LROWS = 640; // most rows of one matrix a workgroup may own
 constexpr int ATT_CHUNK = NWV * 16;  // positions per split-KV work item (fixed: results do not depend on context length)
 constexpr int ATT_PG = 4;      // (row, head) pairs per attention work item
 constexpr int ATT_SELF_MERGE_PAIRS = 4;   // most (row, head) pairs per kv head for which the attention launch merges its own chunks
+constexpr int ATT_SELF_MERGE_CHUNKS = 8;  // ... and most chunks (one batch of the merge's loads: context <= 2048)
 constexpr int ATT_PAD = 4;     // a chunk's partial is [head_dim] weighted values, its maximum, its sum, 2 spare floats (16-byte rows)
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));

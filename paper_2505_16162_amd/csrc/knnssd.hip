@@ -555,7 +555,10 @@ static int32_t run_pass_bf16(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, b
     // the merge launch). Many pairs (Qwen-shaped 9 rows: 45 per kv head): the one workgroup's serial merge costs 5 us per
     // block MORE than the launch that spreads it over the chip, so that launch stays.
     const bool mfma_attn = (!rows1 || aa.group >= 2) && c->verify_attn_mfma;
-    const bool self_merge = c->cfg.attn_merge == KNNSSD_MERGE_FUSED && n_rows * aa.group <= ATT_SELF_MERGE_PAIRS;
+    // Long contexts keep the launch as well: the last workgroup fetches the chunks in serial batches of eight, and at
+    // 17 chunks (context 4096) that costs what the launch costs (verification) or 3 us more (draft steps).
+    const bool self_merge = c->cfg.attn_merge == KNNSSD_MERGE_FUSED && n_rows * aa.group <= ATT_SELF_MERGE_PAIRS &&
+                            start + n_rows <= ATT_SELF_MERGE_CHUNKS * ATT_CHUNK;
     for (int b = 0; b < g.n_blocks; ++b) {
         bf16_t *kvb = (bf16_t *)(c->kv + (size_t)b * c->kv_block_bytes);
         if (!(mask && mask[2 * b])) {

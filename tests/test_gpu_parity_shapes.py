@@ -258,15 +258,15 @@ def test_tile_counts_of_three_five_and_six_per_workgroup():
 def test_merge_inside_the_attention_launch(gqa):
     """With few (row, head) pairs per kv head the attention launch merges its own chunks (cfg.attn_merge =
     KNNSSD_MERGE_FUSED, the default: the workgroup that finishes a group's last chunk does it); the same steps with the
-    merge as a launch of its own (KNNSSD_MERGE_SEPARATE) must give the same bits, at one, two, six and seven chunks,
+    merge as a launch of its own (KNNSSD_MERGE_SEPARATE) must give the same bits, at one, two, six, seven and nine chunks,
     for draft steps (vector-ALU kernel, or the matrix-core one with grouped-query heads) and for verification passes of
     1, 3 and 5 rows (more than four pairs per kv head keep the launch), and both are checked against the oracle."""
     shape = synth.small_shape("fuse_gqa" if gqa else "fuse_mha", n_blocks=2, d_model=512, n_heads=8, n_kv_heads=2 if gqa else 8,
-                              head_dim=64, d_ffn=1408, vocab=900, max_seq=1700)
+                              head_dim=64, d_ffn=1408, vocab=900, max_seq=2200)
     w, orc, gpu = make_pair(shape, seed=37, std=0.04)
     gpu2 = binding.KnnSsd(shape, w, separate_merge=True)
     mask = [0, 1, 0, 0]
-    for plen in (37, 283, 1300, 1600):
+    for plen in (37, 283, 1300, 1600, 2100):         # 2100: past the context up to which the launch merges itself
         print("case", gqa, plen, flush=True)
         prompt = synth.make_prompt(shape.vocab, plen, seed=2).tolist()
         first_o, _, _ = O.prefill(orc, prompt)
