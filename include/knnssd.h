@@ -255,6 +255,13 @@ int32_t knnssd_get_logits(knnssd_ctx *ctx, int32_t row, float *logits_host);
  * each [n_kv_heads*head_dim] on the host. */
 int32_t knnssd_read_kv(knnssd_ctx *ctx, int32_t block, int32_t pos, float *k_host, float *v_host);
 
+/* One transition of the task stream of Sec. 4.2, Eq. 8 (host only, no device work): the next sample stays in domain
+ * `current` unless u_switch < mix_ratio; on a switch it lands on one of the other n_domains - 1 domains, taken in
+ * increasing order, chosen by u_pick. u_switch and u_pick are uniform draws on [0, 1) the caller supplies (the library
+ * draws no random numbers). Returns the next domain, or KNNSSD_EINVAL / KNNSSD_ERANGE (negative) for n_domains < 1, a
+ * current domain outside [0, n_domains), a mix ratio outside [0, 1] or a draw outside [0, 1). */
+int32_t knnssd_stream_next_domain(int32_t current, int32_t n_domains, double mix_ratio, double u_switch, double u_pick);
+
 /* Message for an error code; for KNNSSD_EHIP the text of the last HIP error of this thread. */
 const char *knnssd_strerror(int32_t code);
 

@@ -25,7 +25,7 @@ EXPORTS = [
     "knnssd_pack_supported", "knnssd_pack_matrix",
     "knnssd_set_anchors", "knnssd_prefill", "knnssd_select_skipset", "knnssd_set_skipset", "knnssd_last_selection", "knnssd_knn_topk", "knnssd_route_static",
     "knnssd_draft_step", "knnssd_verify", "knnssd_generate", "knnssd_profile_pass", "knnssd_get_logits", "knnssd_read_kv",
-    "knnssd_strerror",
+    "knnssd_strerror", "knnssd_stream_next_domain",
 ]
 
 
@@ -117,6 +117,8 @@ def load_library() -> ctypes.CDLL:
     lib.knnssd_get_logits.argtypes = [vp, i32, vp]
     lib.knnssd_read_kv.restype = i32
     lib.knnssd_read_kv.argtypes = [vp, i32, i32, vp, vp]
+    lib.knnssd_stream_next_domain.restype = i32
+    lib.knnssd_stream_next_domain.argtypes = [i32, i32, ctypes.c_double, ctypes.c_double, ctypes.c_double]
     lib.knnssd_strerror.restype = ctypes.c_char_p
     lib.knnssd_strerror.argtypes = [i32]
     _lib = lib
@@ -147,6 +149,14 @@ def knnssd_route_static(query: torch.Tensor, anchors: torch.Tensor, labels: torc
     s = stream if stream is not None else torch.cuda.current_stream(query.device)
     _check(lib.knnssd_route_static(query.data_ptr(), anchors.data_ptr(), labels.data_ptr(), anchors.shape[0], anchors.shape[1],
                                    ctypes.c_void_p(s.cuda_stream), result.data_ptr()))
+
+
+def knnssd_stream_next_domain(current: int, n_domains: int, mix_ratio: float, u_switch: float, u_pick: float) -> int:
+    """Eq. 8 transition (host-only call of the library; argument marshalling only)."""
+    rc = load_library().knnssd_stream_next_domain(int(current), int(n_domains), float(mix_ratio), float(u_switch), float(u_pick))
+    if rc < 0:
+        _check(rc)
+    return int(rc)
 
 
 class KnnSsd:

@@ -1137,6 +1137,17 @@ extern "C" int32_t knnssd_profile_pass(knnssd_ctx *ctx, int32_t kind, const int3
     return KNNSSD_OK;
 }
 
+extern "C" int32_t knnssd_stream_next_domain(int32_t current, int32_t n_domains, double mix_ratio, double u_switch, double u_pick) {
+    if (n_domains < 1) return KNNSSD_EINVAL;
+    if (current < 0 || current >= n_domains) return KNNSSD_ERANGE;
+    if (!(mix_ratio >= 0.0 && mix_ratio <= 1.0) || !(u_switch >= 0.0 && u_switch < 1.0) || !(u_pick >= 0.0 && u_pick < 1.0))
+        return KNNSSD_ERANGE;
+    if (n_domains == 1 || !(u_switch < mix_ratio)) return current;
+    int32_t slot = (int32_t)(u_pick * (double)(n_domains - 1));       // one of the other N-1 domains, equally likely
+    if (slot > n_domains - 2) slot = n_domains - 2;
+    return slot < current ? slot : slot + 1;
+}
+
 extern "C" int32_t knnssd_get_logits(knnssd_ctx *ctx, int32_t row, float *logits_host) {
     if (!ctx || !logits_host) return KNNSSD_EINVAL;
     if (row < 0 || row >= KS_MAX_ROWS) return KNNSSD_ERANGE;

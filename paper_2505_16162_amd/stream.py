@@ -7,26 +7,21 @@ the whole per-sample path (`knnssd_generate`: prefill, 1-NN routing of the sampl
 rounds with the routed mask). With `reselect=False` the mask routed for the FIRST sample is kept for the
 whole stream, which is the fixed-configuration Self-SD baseline of Sec. 5.1.
 
-Host code only: every step of the path runs in the library's kernels. The uniform draws that drive the
-chain and the synthetic prompts / queries come from the seeded generators in `synth`.
+Host code only, and bookkeeping only: every step of the path runs in the library's kernels and the chain's
+transition rule is the library's `knnssd_stream_next_domain`. The uniform draws that drive the chain and the
+synthetic prompts / queries come from the seeded generators in `synth`.
 """
 from dataclasses import dataclass, field
 from typing import Callable, Dict, List, Optional, Sequence
 
 import torch
 
-from . import synth
+from . import binding, synth
 
 
 def domain_after(current: int, n_domains: int, r: float, u_switch: float, u_pick: float) -> int:
-    """One transition of the Eq. 8 chain from two uniforms on [0, 1): keep the domain unless u_switch < r;
-    on a switch, u_pick selects among the N-1 other domains, taken in increasing order."""
-    if n_domains <= 1 or not (u_switch < r):
-        return current
-    slot = int(u_pick * (n_domains - 1))
-    if slot > n_domains - 2:
-        slot = n_domains - 2
-    return slot if slot < current else slot + 1
+    """One transition of the Eq. 8 chain from two uniforms on [0, 1): the library's knnssd_stream_next_domain."""
+    return binding.knnssd_stream_next_domain(current, n_domains, r, u_switch, u_pick)
 
 
 def domain_sequence(n_domains: int, n_samples: int, r: float, seed: int, first: int = 0) -> List[int]:

@@ -93,3 +93,13 @@ def test_route_static_checks_its_arguments_before_touching_the_device(lib):
     assert f(fake, fake, fake, 65537, 256, None, fake) == -3     # beyond KNNSSD_ROUTE_MAX_ANCHORS
     header = open(os.path.join(ROOT, "include", "knnssd.h")).read()
     assert "#define KNNSSD_ROUTE_MAX_ANCHORS 65536" in header
+
+
+def test_stream_transition_is_a_host_call_with_argument_checks(lib):
+    f = lib.knnssd_stream_next_domain
+    assert f(2, 5, 0.0, 0.5, 0.5) == 2                  # r = 0: task by task
+    assert f(2, 5, 1.0, 0.0, 0.0) == 0 and f(2, 5, 1.0, 0.0, 0.999999) == 4 and f(2, 5, 1.0, 0.0, 0.5) == 3   # never itself
+    assert f(0, 1, 1.0, 0.0, 0.0) == 0
+    assert f(5, 5, 0.5, 0.1, 0.1) == -3 and f(-1, 5, 0.5, 0.1, 0.1) == -3
+    assert f(0, 0, 0.5, 0.1, 0.1) == -1
+    assert f(0, 5, 1.5, 0.1, 0.1) == -3 and f(0, 5, 0.5, 1.0, 0.1) == -3 and f(0, 5, 0.5, 0.1, -0.1) == -3
