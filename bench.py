@@ -28,7 +28,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 COPY_BYTES = 1 << 30          # size of the calibration copy of --traffic-probe
-TRAFFIC_FILE = os.path.join(ROOT, "profiles", "gemm_mfma_kernel_llama13b_hbm_traffic.md")
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "knnssd_kernels_llama13b_hbm_traffic.md")
 
 
 FAMILIES = (("gemm_mfma_kernel<false", "verification GEMM"), ("gemv_kernel", "draft GEMV"),

@@ -300,6 +300,33 @@ def test_merge_inside_the_attention_launch(gqa):
     gpu2.close()
 
 
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("hd,heads,kv_heads,plen,row_counts", [(64, 32, 32, 4101, (2, 9)), (128, 32, 8, 6200, (9, 2))])
+def test_attention_with_more_work_items_than_workgroups(hd, heads, kv_heads, plen, row_counts):
+    """Many heads on a long context: a verification pass brings more (pair tile, kv head, 256-position chunk) items
+    than the matrix-core attention launch has workgroups (32 kv heads x 17 chunks; 3 pair tiles x 8 kv heads x 25
+    chunks), so workgroups run several items one after the other, with the padding slots of the item order in
+    between; the 2-row pass of the grouped-query shape has fewer items than workgroups. Logits against the oracle."""
+    shape = synth.small_shape("items%d" % hd, n_blocks=1, d_model=256, n_heads=heads, n_kv_heads=kv_heads, head_dim=hd,
+                              d_ffn=704, vocab=1200, max_seq=plen + 40)
+    w, orc, gpu = make_pair(shape, seed=8, std=0.05)
+    prompt = synth.make_prompt(shape.vocab, plen, seed=6).tolist()
+    print("oracle prefill of", plen, "rows,", heads, "heads", flush=True)
+    first_o, _, _ = O.prefill(orc, prompt)
+    assert gpu.knnssd_prefill(prompt)[0] == first_o
+    rows_in = [first_o] + synth.make_prompt(shape.vocab, 8, seed=12).tolist()
+    for n in row_counts:
+        print("case", hd, plen, n, flush=True)
+        j, nxt, new_len = gpu.knnssd_verify(rows_in[:n], plen)
+        rows_o = orc.forward(rows_in[:n], plen, None)
+        for r in range(n):
+            ok, err = logits_close(gpu.knnssd_get_logits(r).numpy(), rows_o[r], shape)
+            assert ok, (n, r, err)
+        targets = [O.argmax_lowest(rows_o[r]) for r in range(n)]
+        assert j == O.accept_length(rows_in[1:n], targets) and nxt == targets[j] and new_len == plen + j + 1
+    gpu.close()
+
+
 def test_two_identical_runs_give_identical_bits():
     """Run-to-run determinism of the tuned kernels (no atomics, fixed reduction orders): the same prefill, draft
     steps, verification passes and generation twice on one context, and once more on a second context built from
