@@ -181,7 +181,8 @@ int32_t knnssd_set_skipset(knnssd_ctx *ctx, const uint8_t *mask_host);
  * Batched: up to 4 queries share one pass over the table. queries_dev: fp32 [n_queries][d_model], 16-byte aligned
  * (device). anchor_idx_out: int32 [n_queries][k] (host). cosine_out: fp32 [n_queries][k] (host, may be NULL).
  * domain_out: int32 [n_queries] (host). 1 <= k <= 16 and k <= number of anchors. Installs no mask.
- * KNNSSD_EDEGENERATE for a zero-norm or non-finite query or anchor, KNNSSD_ESTATE without an anchor table. */
+ * KNNSSD_EDEGENERATE for a zero-norm or non-finite query or anchor, KNNSSD_ESTATE without an anchor table,
+ * KNNSSD_ERANGE for k or n_queries out of range or a table of more than 2^24 anchors. */
 #define KNNSSD_KNN_KMAX 16
 int32_t knnssd_knn_topk(knnssd_ctx *ctx, const float *queries_dev, int32_t n_queries, int32_t k,
                         int32_t *anchor_idx_out, float *cosine_out, int32_t *domain_out);

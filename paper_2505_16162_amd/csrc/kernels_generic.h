@@ -387,112 +387,198 @@ struct KnnTopk {
 };
 
 // AT = float or bf16_t: the type the anchor table is stored in (queries, products and sums are fp32 either way). A lane's
-// 16-byte load covers EPL = 4 or 8 consecutive elements of the anchor.
+// 16-byte load covers EPL = 4 or 8 consecutive elements of an anchor. A wavefront takes A consecutive anchors at a
+// time and L loads per lane of each, so 8 loads per lane are in flight whatever the storage type and query count, a
+// query value fetched from the cache serves A anchors (with four queries the query reads would otherwise be four
+// times the table's bytes), and 5120 elements are whole blocks in every variant. An anchor's sums are formed in the
+// same order whatever A is: a lane adds its elements in column order, then the 64 lanes are summed.
+template <int Q, typename AT>
+struct KnnTile {
+    static constexpr int EPL = 16 / (int)sizeof(AT);
+    static constexpr int A = (Q >= 3 || EPL == 8) ? 4 : 2;
+    static constexpr int L = 8 / A;
+};
+
 template <int Q, typename AT>
 __global__ __launch_bounds__(256) void knn_scores_multi_kernel(const float *__restrict__ queries, const AT *__restrict__ anchors,
                                                                int N, int D, float *scores /*[Q][N]*/) {
     typedef float f4 __attribute__((ext_vector_type(4)));
-    constexpr int EPL = 16 / (int)sizeof(AT);         // elements per lane and load
-    constexpr int BLK = 4 * 64 * EPL;                 // elements per block of four loads per lane
+    constexpr int EPL = KnnTile<Q, AT>::EPL;          // elements per lane and load
+    constexpr int A = KnnTile<Q, AT>::A, L = KnnTile<Q, AT>::L;
+    constexpr int BLK = L * 64 * EPL;                 // elements of an anchor per block of L loads per lane
     const int lane = threadIdx.x & 63;
     const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int n_waves = (gridDim.x * blockDim.x) >> 6;
-    for (int n = wave; n < N; n += n_waves) {
-        const AT *a = anchors + (size_t)n * D;
-        float dot[Q], nn = 0.f;
+    for (int n0 = wave * A; n0 < N; n0 += n_waves * A) {
+        const AT *a[A];
 #pragma unroll
-        for (int q = 0; q < Q; ++q) dot[q] = 0.f;
-        for (int k0 = 0; k0 < D; k0 += BLK) {            // blocks of four 16-byte loads per lane, issued together
-            f4 av[4];
+        for (int t = 0; t < A; ++t) a[t] = anchors + (size_t)min(n0 + t, N - 1) * D;      // past the table: the last anchor again, not stored
+        float dot[A][Q], nn[A];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
+        for (int t = 0; t < A; ++t) {
+            nn[t] = 0.f;
+#pragma unroll
+            for (int q = 0; q < Q; ++q) dot[t][q] = 0.f;
+        }
+        for (int k0 = 0; k0 < D; k0 += BLK) {            // blocks of A x L 16-byte loads per lane, issued together
+            f4 av[A][L];
+#pragma unroll
+            for (int j = 0; j < L; ++j) {
                 const int k = min(k0 + (j * 64 + lane) * EPL, D - EPL);           // clamped, masked below
-                av[j] = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(a + k));
+#pragma unroll
+                for (int t = 0; t < A; ++t) av[t][j] = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(a[t] + k));
             }
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
+            for (int j = 0; j < L; ++j) {
                 const int k = k0 + (j * 64 + lane) * EPL;
                 if (k < D) {
-                    float e[EPL];
-                    if constexpr (EPL == 4) {
-                        e[0] = av[j].x; e[1] = av[j].y; e[2] = av[j].z; e[3] = av[j].w;
-                    } else {
+                    float4 qv[Q][EPL / 4];
 #pragma unroll
-                        for (int w = 0; w < 4; ++w) {
-                            const unsigned int u = __float_as_uint(av[j][w]);
-                            e[2 * w] = __uint_as_float(u << 16); e[2 * w + 1] = __uint_as_float(u & 0xffff0000u);
+                    for (int q = 0; q < Q; ++q)
+#pragma unroll
+                        for (int i4 = 0; i4 < EPL / 4; ++i4)
+                            qv[q][i4] = *reinterpret_cast<const float4 *>(queries + (size_t)q * D + k + 4 * i4);
+#pragma unroll
+                    for (int t = 0; t < A; ++t) {
+                        float e[EPL];
+                        if constexpr (EPL == 4) {
+                            e[0] = av[t][j].x; e[1] = av[t][j].y; e[2] = av[t][j].z; e[3] = av[t][j].w;
+                        } else {
+#pragma unroll
+                            for (int w = 0; w < 4; ++w) {
+                                const unsigned int u = __float_as_uint(av[t][j][w]);
+                                e[2 * w] = __uint_as_float(u << 16); e[2 * w + 1] = __uint_as_float(u & 0xffff0000u);
+                            }
                         }
-                    }
 #pragma unroll
-                    for (int i = 0; i < EPL; ++i) nn = fmaf(e[i], e[i], nn);
+                        for (int i = 0; i < EPL; ++i) nn[t] = fmaf(e[i], e[i], nn[t]);
 #pragma unroll
-                    for (int q = 0; q < Q; ++q) {
+                        for (int q = 0; q < Q; ++q) {
 #pragma unroll
-                        for (int i4 = 0; i4 < EPL / 4; ++i4) {
-                            const float4 qv = *reinterpret_cast<const float4 *>(queries + (size_t)q * D + k + 4 * i4);
-                            dot[q] = fmaf(e[4 * i4], qv.x, dot[q]); dot[q] = fmaf(e[4 * i4 + 1], qv.y, dot[q]);
-                            dot[q] = fmaf(e[4 * i4 + 2], qv.z, dot[q]); dot[q] = fmaf(e[4 * i4 + 3], qv.w, dot[q]);
+                            for (int i4 = 0; i4 < EPL / 4; ++i4) {
+                                dot[t][q] = fmaf(e[4 * i4], qv[q][i4].x, dot[t][q]); dot[t][q] = fmaf(e[4 * i4 + 1], qv[q][i4].y, dot[t][q]);
+                                dot[t][q] = fmaf(e[4 * i4 + 2], qv[q][i4].z, dot[t][q]); dot[t][q] = fmaf(e[4 * i4 + 3], qv[q][i4].w, dot[t][q]);
+                            }
                         }
                     }
                 }
             }
         }
-        nn = wave_sum(nn);
-        const bool ok = nn > 0.f && isfinite(nn);
-        const float inv = ok ? 1.0f / sqrtf(nn) : 0.f;
 #pragma unroll
-        for (int q = 0; q < Q; ++q) {
-            const float d = wave_sum(dot[q]);
-            if (lane == 0) scores[(size_t)q * N + n] = ok ? d * inv : NAN;
+        for (int t = 0; t < A; ++t) {
+            const float nt = wave_sum(nn[t]);
+            const bool ok = nt > 0.f && isfinite(nt);
+            const float inv = ok ? 1.0f / sqrtf(nt) : 0.f;
+#pragma unroll
+            for (int q = 0; q < Q; ++q) {
+                const float d = wave_sum(dot[t][q]);
+                if (lane == 0 && n0 + t < N) scores[(size_t)q * N + n0 + t] = ok ? d * inv : NAN;
+            }
         }
     }
 }
 
-// K rounds of arg-max (lowest anchor index on ties) over values not yet taken. Entry i has value val[i] and anchor
-// index (map ? map[i] : first + i). Runs on one workgroup of 1024 threads; the winners land in taken_idx / taken_val.
-__device__ __forceinline__ int knn_rounds(const float *val, const int32_t *map, int first, int n, int K, int *taken_pos,
-                                          int *taken_idx, float *taken_val, float *sv, int *si, int *sp) {
+// The K best (largest value, lowest anchor index on ties) of n entries, in rank order, by one workgroup of 1024
+// threads. Entry i has value val[i] and anchor index (map ? map[i] : first + i); entries with a negative index are
+// dead. Two levels of K rounds of arg-max, both inside single wavefronts (registers and cross-lane moves, no
+// meeting per round): every wavefront ranks the K best of its sixteenth of the entries (a lane looks at entries 64
+// apart and marks the ones it has given away in a 64-bit mask, hence n <= KNN_ROUNDS_MAX_N), the workgroup meets once,
+// and the first wavefront ranks the K best of the 16 x K survivors. taken_idx / taken_val receive the winners
+// (0x7fffffff / -inf once the entries run out); returns nonzero in the threads that met a non-finite value.
+#define KNN_ROUNDS_MAX_N (16 * 64 * 64)
+#define KNN_SLICES_MAX 256       // stage-1 slices per query: 256 x KNN_ROUNDS_MAX_N anchors at most
+struct KnnRoundsLds {
+    float val[16][KNN_KMAX];
+    int idx[16][KNN_KMAX];
+};
+
+__device__ __forceinline__ void knn_wave_best(float &bv, int &bi, int &bp) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const float ov = __shfl_xor(bv, off, 64); const int oi = __shfl_xor(bi, off, 64), op = __shfl_xor(bp, off, 64);
+        if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; bp = op; }
+    }
+}
+
+__device__ __forceinline__ int knn_rounds(const float *val, const int32_t *map, int first, int n, int K, int *taken_idx,
+                                          float *taken_val, KnnRoundsLds *wl) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int anybad = 0;
-    for (int r = 0; r < K; ++r) {
-        float bv = -INFINITY; int bi = 0x7fffffff, bp = -1;
-        for (int i = threadIdx.x; i < n; i += 1024) {
-            const float v = val[i];
-            if (!isfinite(v)) { anybad = 1; continue; }
-            bool free_ = true;
-            for (int t = 0; t < r; ++t) free_ = free_ && (taken_pos[t] != i);
-            const int gi = map ? map[i] : first + i;
-            if (free_ && gi >= 0 && better(v, gi, bv, bi)) { bv = v; bi = gi; bp = i; }
-        }
+    {
+        const int w0 = (int)((long long)n * wave / 16), w1 = (int)((long long)n * (wave + 1) / 16);
+        const int M = (w1 - w0 + 63) >> 6;                 // <= 64
+        unsigned long long given = 0;                       // bit m: this lane's entry w0 + 64 m + lane is among the winners
+        // the lane's first MR entries stay in registers over the rounds (slices of a few thousand scores and the
+        // candidate lists have no more); entries beyond are read again in every round
+        constexpr int MR = 4;
+        float rv[MR]; int rg[MR];
 #pragma unroll
-        for (int off = 32; off > 0; off >>= 1) {
-            const float ov = __shfl_xor(bv, off, 64); const int oi = __shfl_xor(bi, off, 64), op = __shfl_xor(bp, off, 64);
-            if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; bp = op; }
+        for (int m = 0; m < MR; ++m) {
+            const int i = w0 + (m << 6) + lane;
+            rv[m] = -INFINITY; rg[m] = -1;                  // a dead entry
+            if (i < w1) {
+                const float v = val[i];
+                if (!isfinite(v)) anybad = 1;
+                else { rv[m] = v; rg[m] = map ? map[i] : first + i; }
+            }
         }
-        if (lane == 0) { sv[wave] = bv; si[wave] = bi; sp[wave] = bp; }
-        __syncthreads();
-        if (threadIdx.x == 0) {
-            bv = sv[0]; bi = si[0]; bp = sp[0];
-            for (int w = 1; w < 16; ++w) if (better(sv[w], si[w], bv, bi)) { bv = sv[w]; bi = si[w]; bp = sp[w]; }
-            taken_pos[r] = bp; taken_idx[r] = bi; taken_val[r] = bv;
+        for (int r = 0; r < K; ++r) {
+            float bv = -INFINITY; int bi = 0x7fffffff, bp = -1;
+#pragma unroll
+            for (int m = 0; m < MR; ++m)
+                if (!((given >> m) & 1ull) && rg[m] >= 0 && better(rv[m], rg[m], bv, bi)) { bv = rv[m]; bi = rg[m]; bp = w0 + (m << 6) + lane; }
+            for (int m = MR; m < M; ++m) {
+                const int i = w0 + (m << 6) + lane;
+                if (i >= w1 || ((given >> m) & 1ull)) continue;
+                const float v = val[i];
+                if (!isfinite(v)) { anybad = 1; continue; }
+                const int gi = map ? map[i] : first + i;
+                if (gi >= 0 && better(v, gi, bv, bi)) { bv = v; bi = gi; bp = i; }
+            }
+            knn_wave_best(bv, bi, bp);                      // every lane holds the winner
+            if (bp >= 0 && ((bp - w0) & 63) == lane) given |= 1ull << ((bp - w0) >> 6);
+            if (lane == 0) { wl->val[wave][r] = bv; wl->idx[wave][r] = bi; }
         }
-        __syncthreads();
     }
+    __syncthreads();
+    if (wave == 0) {
+        // 16 x KNN_KMAX slots, four per lane; slots of rounds that were not played are dead
+        float cv[4]; int ci[4];
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            const int c = (m << 6) + lane, w = c / KNN_KMAX, r = c % KNN_KMAX;
+            const bool live = r < K;
+            cv[m] = live ? wl->val[w][r] : -INFINITY;
+            ci[m] = live ? wl->idx[w][r] : 0x7fffffff;
+        }
+        unsigned int given = 0;
+        for (int r = 0; r < K; ++r) {
+            float bv = -INFINITY; int bi = 0x7fffffff, bp = -1;
+#pragma unroll
+            for (int m = 0; m < 4; ++m)
+                if (!((given >> m) & 1u) && ci[m] != 0x7fffffff && better(cv[m], ci[m], bv, bi)) { bv = cv[m]; bi = ci[m]; bp = (m << 6) + lane; }
+            knn_wave_best(bv, bi, bp);
+            if (bp >= 0 && (bp & 63) == lane) given |= 1u << (bp >> 6);
+            if (lane == 0) { taken_idx[r] = bi; taken_val[r] = bv; }
+        }
+    }
+    __syncthreads();
     return anybad;
 }
 
 // Stage 1 of the top-K: workgroup (query q, slice b) leaves the K best of its slice of the scores as candidates.
 __global__ __launch_bounds__(1024) void knn_topk_part_kernel(const float *scores /*[Q][N]*/, int N, int K, int n_slices,
                                                              int32_t *cand_idx /*[Q][n_slices][KNN_KMAX]*/, float *cand_val,
-                                                             int *bad_flag /*[Q]*/) {
-    __shared__ float sv[16];
-    __shared__ int si[16], sp[16], tpos[KNN_KMAX], tidx[KNN_KMAX];
+                                                             int *bad_flag /*[Q][n_slices]*/) {
+    __shared__ KnnRoundsLds wl;
+    __shared__ int tidx[KNN_KMAX];
     __shared__ float tval[KNN_KMAX];
     const int q = blockIdx.x, b = blockIdx.y;
     const int i0 = (int)((long long)N * b / n_slices), i1 = (int)((long long)N * (b + 1) / n_slices);
     const int kk = min(K, i1 - i0);
-    const int anybad = knn_rounds(scores + (size_t)q * N + i0, nullptr, i0, i1 - i0, kk, tpos, tidx, tval, sv, si, sp);
-    if (anybad) atomicOr(&bad_flag[q], 1);
+    const int anybad = knn_rounds(scores + (size_t)q * N + i0, nullptr, i0, i1 - i0, kk, tidx, tval, &wl);
+    const int slice_bad = __syncthreads_or(anybad);           // every slice writes its own flag: nothing to clear beforehand
+    if (threadIdx.x == 0) bad_flag[q * n_slices + b] = slice_bad ? 1 : 0;
     if (threadIdx.x < KNN_KMAX) {
         const size_t o = ((size_t)q * n_slices + b) * KNN_KMAX + threadIdx.x;
         const bool live = (int)threadIdx.x < kk && tidx[threadIdx.x] != 0x7fffffff;
@@ -504,8 +590,7 @@ __global__ __launch_bounds__(1024) void knn_topk_part_kernel(const float *scores
 // Stage 2: one workgroup per query merges the slices' candidates (K rounds again), then the vote.
 __global__ __launch_bounds__(1024) void knn_topk_kernel(const int32_t *cand_idx, const float *cand_val, int n_slices, const int *bad_flag,
                                                         const float *queries, const int32_t *labels, int D, int K, KnnTopk *res) {
-    __shared__ float sv[16];
-    __shared__ int si[16], sp[16], tpos[KNN_KMAX];
+    __shared__ KnnRoundsLds wl;
     __shared__ int taken[KNN_KMAX];
     __shared__ float tval[KNN_KMAX];
     __shared__ float qn[16];
@@ -517,35 +602,47 @@ __global__ __launch_bounds__(1024) void knn_topk_kernel(const int32_t *cand_idx,
     if (lane == 0) qn[wave] = q2;
     __syncthreads();
     const size_t o = (size_t)q * n_slices * KNN_KMAX;
-    knn_rounds(cand_val + o, cand_idx + o, 0, n_slices * KNN_KMAX, K, tpos, taken, tval, sv, si, sp);
-    const int bad = bad_flag[q];
+    knn_rounds(cand_val + o, cand_idx + o, 0, n_slices * KNN_KMAX, K, taken, tval, &wl);
+    int mybad = 0;
+    for (int b = threadIdx.x; b < n_slices; b += 1024) mybad |= bad_flag[q * n_slices + b];
+    const int bad = __syncthreads_or(mybad);
+    // the winners' labels, fetched side by side (the vote below walks them many times)
+    __shared__ int lab_of[KNN_KMAX];
+    if (threadIdx.x < KNN_KMAX) {
+        const int t = taken[threadIdx.x];
+        lab_of[threadIdx.x] = ((int)threadIdx.x < K && t != 0x7fffffff && t >= 0) ? labels[t] : -1;
+    }
+    __syncthreads();
+    // (no per-thread arrays below: they would live in scratch memory, one memory round trip per access)
+    float qtot = 0.f;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) qtot += qn[w];
+    const bool degenerate = bad || !(qtot > 0.f) || !isfinite(qtot) || taken[0] == 0x7fffffff;
+    const float invq = degenerate ? 0.f : 1.0f / sqrtf(qtot);
+    if (threadIdx.x < KNN_KMAX) {
+        const int r = threadIdx.x;
+        const bool live = r < K && !degenerate && taken[r] != 0x7fffffff;
+        res[q].idx[r] = live ? taken[r] : -1;
+        res[q].cosine[r] = live ? tval[r] * invq : 0.f;
+        if (!live) lab_of[r] = -1;                    // only this thread touches entry r here
+    }
+    __syncthreads();
     if (threadIdx.x == 0) {
-        float qtot = 0.f;
-        for (int w = 0; w < 16; ++w) qtot += qn[w];
-        KnnTopk out;
-        const bool degenerate = bad || !(qtot > 0.f) || !isfinite(qtot) || taken[0] == 0x7fffffff;
-        const float invq = degenerate ? 0.f : 1.0f / sqrtf(qtot);
-        int best_label = -1, best_count = 0;
-        for (int r = 0; r < KNN_KMAX; ++r) {
-            const bool live = r < K && !degenerate && taken[r] != 0x7fffffff;
-            out.idx[r] = live ? taken[r] : -1;
-            out.cosine[r] = live ? tval[r] * invq : 0.f;
-        }
         // ranked order: the first label to reach the highest count wins a tie only if its best anchor ranks first,
         // i.e. count every label, then take the best-ranked label among those with the highest count
+        int best_label = -1, best_count = 0;
         for (int r = 0; r < K && !degenerate; ++r) {
-            if (out.idx[r] < 0) break;
-            const int lab = labels[out.idx[r]];
+            const int lab = lab_of[r];
+            if (lab < 0) break;                       // the winners ran out
             bool seen = false;
-            for (int t = 0; t < r; ++t) seen = seen || (labels[out.idx[t]] == lab);
+            for (int t = 0; t < r; ++t) seen = seen || (lab_of[t] == lab);
             if (seen) continue;                       // counted when first met
             int cnt = 0;
-            for (int t = r; t < K; ++t) if (out.idx[t] >= 0 && labels[out.idx[t]] == lab) ++cnt;
+            for (int t = r; t < K; ++t) if (lab_of[t] == lab) ++cnt;
             if (cnt > best_count) { best_count = cnt; best_label = lab; }
         }
-        out.domain = degenerate ? -1 : best_label;
-        out.degenerate = degenerate ? 1 : 0;
-        res[q] = out;
+        res[q].domain = degenerate ? -1 : best_label;
+        res[q].degenerate = degenerate ? 1 : 0;
     }
 }
 

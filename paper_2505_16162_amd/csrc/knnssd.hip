@@ -96,9 +96,9 @@ static WsLayout ws_layout(const knnssd_model_cfg *c) {
     L.rope_sin = take((size_t)c->max_seq * (c->head_dim / 2) * 4);
     L.knn_scores = take((size_t)(c->max_anchors > 0 ? c->max_anchors : 1) * 4 * KNN_QMAX);
     L.knn_topk = take(sizeof(KnnTopk) * KNN_QMAX);
-    L.knn_cand_idx = take((size_t)KNN_QMAX * 64 * KNN_KMAX * 4);
-    L.knn_cand_val = take((size_t)KNN_QMAX * 64 * KNN_KMAX * 4);
-    L.knn_bad = take(KNN_QMAX * 4);
+    L.knn_cand_idx = take((size_t)KNN_QMAX * KNN_SLICES_MAX * KNN_KMAX * 4);
+    L.knn_cand_val = take((size_t)KNN_QMAX * KNN_SLICES_MAX * KNN_KMAX * 4);
+    L.knn_bad = take((size_t)KNN_QMAX * KNN_SLICES_MAX * 4);
     L.out_tokens = take((size_t)c->max_seq * 4);
     {
         const size_t qd = (size_t)c->n_heads * c->head_dim;
@@ -835,11 +835,13 @@ extern "C" int32_t knnssd_knn_topk(knnssd_ctx *ctx, const float *queries_dev, in
         launch_scan(ctx, qp, nq, scores);
         int n_slices = N / 2048;                      // stage 1 slices per query: a few thousand scores each
         if (n_slices < 1) n_slices = 1;
-        if (n_slices > 64) n_slices = 64;
+        if (n_slices > KNN_SLICES_MAX) n_slices = KNN_SLICES_MAX;
+        // a slice is ranked by one workgroup, whose lanes keep one mask bit per entry they look at
+        if ((N + n_slices - 1) / n_slices > KNN_ROUNDS_MAX_N) n_slices = (N + KNN_ROUNDS_MAX_N - 1) / KNN_ROUNDS_MAX_N;
+        if (n_slices > KNN_SLICES_MAX) return KNNSSD_ERANGE;       // more than 16.7 million anchors
         int32_t *cand_idx = ctx->wsp<int32_t>(ctx->L.knn_cand_idx);
         float *cand_val = ctx->wsp<float>(ctx->L.knn_cand_val);
         int *bad = ctx->wsp<int>(ctx->L.knn_bad);
-        hipLaunchKernelGGL(fill_zero_kernel, dim3(1), dim3(64), 0, ctx->stream, bad, KNN_QMAX);
         hipLaunchKernelGGL(knn_topk_part_kernel, dim3(nq, n_slices), dim3(1024), 0, ctx->stream, scores, N, k, n_slices, cand_idx, cand_val, bad);
         hipLaunchKernelGGL(knn_topk_kernel, dim3(nq), dim3(1024), 0, ctx->stream, cand_idx, cand_val, n_slices, bad, qp, ctx->labels, D, k, res);
         HIP_TRY(hipGetLastError());

@@ -84,6 +84,43 @@ def test_gpu_topk_matches_oracle(n, k, nq):
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("n,k", [(16, 16), (20, 16), (70, 5), (3000, 16), (9000, 7)])
+def test_gpu_topk_ties_short_tables_and_bad_anchors(n, k):
+    """The selection's own edges: exact ties (every anchor stored several times, so equal scores must come out lowest
+    index first, across the lanes, wavefronts and slices that rank parts of the table), tables shorter than a
+    wavefront's share or than K allows to be dropped, and a non-finite anchor anywhere in the table."""
+    from paper_2505_16162_amd import binding
+    from gpu_common import make_pair
+    shape = synth.small_shape("knnties", d_ffn=704, max_seq=64)
+    n_dom = 4
+    w, orc, gpu = make_pair(shape, seed=2, max_anchors=n)
+    base, _, centres = _table((n + 3) // 4, shape.d_model, n_dom, seed=11)
+    # copies of one anchor sit a quarter of the table apart (different lanes, wavefronts, slices); scaled copies have
+    # the same cosine up to rounding only, so the copies are exact
+    anchors = torch.cat([base, base, base, base])[:n].contiguous()
+    labels = (torch.arange(n) % n_dom).to(torch.int32)
+    masks = synth.make_block_masks(shape.n_blocks, n_dom, 1, seed=6)
+    gpu.knnssd_set_anchors(anchors, labels, masks)
+    queries = torch.stack([synth.make_domain_query(centres, i % n_dom, 0.3, seed=40 + i) for i in range(4)])
+    idx, cos, dom = gpu.knnssd_knn_topk(queries, k)
+    for i in range(4):
+        order, scores, d = O.knn_topk_vote(queries[i].numpy(), anchors.numpy(), labels.numpy(), k)
+        assert idx[i] == order, (i, idx[i], order)
+        assert np.allclose(cos[i], scores, atol=2e-6)
+        assert dom[i] == d
+    a1, d1, _ = gpu.knnssd_select_skipset(queries[1])
+    assert a1 == idx[1][0]
+    bad = anchors.clone()
+    bad[n - 1, 3] = float("nan")
+    gpu.knnssd_set_anchors(bad, labels, masks)
+    with pytest.raises(binding.KnnSsdError):
+        gpu.knnssd_knn_topk(queries, min(k, 2))
+    with pytest.raises(binding.KnnSsdError):
+        gpu.knnssd_select_skipset(queries[0])
+    gpu.close()
+
+
+@pytest.mark.gpu
 @pytest.mark.timeout(600)
 @pytest.mark.parametrize("dtype", ["fp32", "bf16"])
 def test_gpu_scan_of_a_large_table_matches_oracle(dtype):
