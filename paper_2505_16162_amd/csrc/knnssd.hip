@@ -1120,7 +1120,10 @@ extern "C" int32_t knnssd_profile_pass(knnssd_ctx *ctx, int32_t kind, const int3
     KS_TRY(set_pass(ctx, ctl, 1, n, start_pos, 0, tokens_host));
     hipEvent_t p0, p1;
     HIP_TRY(hipEventCreate(&p0));
-    HIP_TRY(hipEventCreate(&p1));
+    {
+        const hipError_t e1 = hipEventCreate(&p1);
+        if (e1 != hipSuccess) { (void)hipEventDestroy(p0); HIP_TRY(e1); }
+    }
     ctx->prof_launches = 0; ctx->prof_bytes = 0;
     ctx->gemm_only = true;
     (void)hipEventRecord(p0, ctx->stream);

@@ -129,6 +129,51 @@ def test_13b_properties_at_benchmark_size(llama13b):
 
 
 @pytest.mark.timeout(600)
+def test_13b_stream_configuration_properties(llama13b):
+    """The domain-shift stream's configuration on the full 13B-shaped model: a 4096-token prompt (17 split-KV chunks
+    of 40 heads x 128: more attention work items than workgroups on both kernels) and routing over 5000 anchors.
+    The oracle cannot prefill that, so: the routing of the GPU's own hidden vector is compared with the exhaustive
+    oracle (index, domain, mask), and the properties that hold at any size are asserted at that context."""
+    _, w, _, _, _, _ = llama13b
+    wl = synth.workload("llama13b_stream")
+    shape = wl.shape
+    gpu = binding.KnnSsd(shape, w, max_anchors=wl.n_anchors)
+    anchors, labels, centres = synth.make_anchors(shape.d_model, wl.n_anchors, wl.n_domains, wl.anchor_sigma, device="cuda:0")
+    masks = synth.make_block_masks(shape.n_blocks, wl.n_domains, wl.skipped_blocks)
+    gpu.knnssd_set_anchors(anchors, labels, masks)
+    prompt = synth.make_prompt(shape.vocab, wl.prompt_len, seed=31).tolist()
+    print("prefill of", len(prompt), "rows", flush=True)
+    first, hidden = gpu.knnssd_prefill(prompt)
+    a_np, l_np = anchors.cpu().numpy(), labels.cpu().numpy()
+    for dom in range(wl.n_domains):
+        # the model's own hidden vector, then a query near each domain's centre (what the stream hands over)
+        q = hidden if dom == 0 else synth.make_domain_query(centres.cpu(), dom, wl.anchor_sigma, seed=60 + dom).to("cuda:0")
+        n_star, d_star, mask, _ = O.knn_select(q.cpu().numpy(), a_np, l_np, masks.numpy())
+        assert gpu.knnssd_select_skipset(q) == (n_star, d_star, mask.tolist()), dom
+        if dom > 0:
+            assert d_star == dom
+    max_new = 24
+    print("AR", flush=True)
+    ar, st_ar = gpu.knnssd_generate(prompt, max_new, 0)
+    assert len(ar) == max_new and ar[0] == first
+    print("SSD", flush=True)
+    for thr in (wl.conf_threshold, 0.0):
+        toks, st = gpu.knnssd_generate(prompt, max_new, wl.max_draft, thr)
+        assert toks == ar, thr
+        assert st["emitted"] == max_new and st["accepted"] <= st["drafted"]
+    print("row independence", flush=True)
+    gpu.knnssd_prefill(prompt)
+    rows_in = [ar[0]] + ar[1:9]
+    gpu.knnssd_verify(rows_in, len(prompt))
+    many = [gpu.knnssd_get_logits(r).clone() for r in range(9)]
+    gpu.knnssd_prefill(prompt)
+    for r in range(3):
+        gpu.knnssd_verify(rows_in[r:r + 1], len(prompt) + r)
+        assert torch.equal(gpu.knnssd_get_logits(0), many[r]), r
+    gpu.close()
+
+
+@pytest.mark.timeout(600)
 def test_13b_many_row_prefill_equals_16_row_passes(llama13b):
     """The prompt prefill the benchmark runs (many-row kernels over 1008 of the 1024 rows) against the same prompt
     sent through 16-row verification passes (cfg.prefill_mode = KNNSSD_PREFILL_CHUNKED), on the full 40-block model:
