@@ -71,7 +71,8 @@ typedef struct knnssd_model_cfg {
                                fits them; KNNSSD_PREFILL_CHUNKED: through 16-row passes of the verification kernels.
                                Only read with weights_packed = 1. */
     int32_t verify_attn;    /* which split-KV attention kernel verification passes (and the draft steps of
-                               grouped-query models) use: KNNSSD_ATTN_MFMA (matrix cores, the default) or
+                               grouped-query models, and of any model once the context brings more (kv head,
+                               256-position chunk) items than 512) use: KNNSSD_ATTN_MFMA (matrix cores, the default) or
                                KNNSSD_ATTN_VALU (vector ALUs). One kernel per context, never chosen per pass, so a
                                row's result does not depend on how many rows share its pass. Only read with
                                weights_packed = 1. Results stay within the stated tolerances either way. */

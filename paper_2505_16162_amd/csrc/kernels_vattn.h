@@ -36,8 +36,10 @@ __host__ __device__ constexpr size_t vattn_lds_bytes() {
     return (size_t)VA_NW * 16 * (VA_WP + 4) * 4 + (size_t)VA_NW * 16 * (HD + 4) * 4;
 }
 
-template <int HD>
-__global__ __launch_bounds__(VA_NT) void attn_partial_mfma_kernel(AttnArgs a, const PassCtl *ctl) {
+// OCC = workgroups the register budget allows on a compute unit: 2 (180 registers per lane at HD = 128), or 3 for
+// launches with more work items than 2 x 256 workgroups (long contexts), which then run in one round instead of two
+template <int HD, int OCC>
+__global__ __launch_bounds__(VA_NT, OCC) void attn_partial_mfma_kernel(AttnArgs a, const PassCtl *ctl) {
     constexpr int QS = HD / 32, DT = HD / 16;
     constexpr int PSTR = VA_WP + 4;            // floats per row of the P tile
     constexpr int MSTR = HD + 4;               // floats per row of the merge buffer (16-byte aligned rows)

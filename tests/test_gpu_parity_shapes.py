@@ -324,6 +324,15 @@ def test_attention_with_more_work_items_than_workgroups(hd, heads, kv_heads, ple
             assert ok, (n, r, err)
         targets = [O.argmax_lowest(rows_o[r]) for r in range(n)]
         assert j == O.accept_length(rows_in[1:n], targets) and nxt == targets[j] and new_len == plen + j + 1
+    # a draft step at that context: with one pair per kv head and that many items it runs on the matrix-core kernel too
+    mask = [0, 1]
+    gpu.knnssd_prefill(prompt)
+    gpu.knnssd_set_skipset(mask)
+    tok, p = gpu.knnssd_draft_step(first_o, plen)
+    row = orc.forward([first_o], plen, np.asarray(mask, np.uint8))[0]
+    ok, err = logits_close(gpu.knnssd_get_logits(0).numpy(), row, shape)
+    assert ok, err
+    assert tok == O.argmax_lowest(row) and abs(p - O.top1_prob(row)) <= 1e-2 * O.top1_prob(row)
     gpu.close()
 
 
