@@ -78,8 +78,8 @@ typedef struct knnssd_model_cfg {
                                weights_packed = 1. Results stay within the stated tolerances either way. */
     int32_t attn_merge;     /* where the chunks of the split-KV attention are merged: KNNSSD_MERGE_FUSED (the default:
                                inside the attention launch, by the workgroup that finishes a group's last chunk, while
-                               a kv head has at most four (row, head) pairs and the context at most 2048 positions; in a launch of its own
-                               beyond) or
+                               a kv head has at most four (row, head) pairs and the context at most 2048 positions
+                               (6144 on the matrix-core kernel); in a launch of its own beyond) or
                                KNNSSD_MERGE_SEPARATE (always in a launch of its own). Same arithmetic, same bits.
                                Only read with weights_packed = 1. */
 } knnssd_model_cfg;

@@ -25,6 +25,7 @@ constexpr int ATT_CHUNK = NWV * 16;  // positions per split-KV work item (fixed:
 constexpr int ATT_PG = 4;      // (row, head) pairs per attention work item
 constexpr int ATT_SELF_MERGE_PAIRS = 4;   // most (row, head) pairs per kv head for which the attention launch merges its own chunks
 constexpr int ATT_SELF_MERGE_CHUNKS = 8;  // ... and most chunks (one batch of the merge's loads: context <= 2048)
+constexpr int ATT_SELF_MERGE_CHUNKS_MFMA = 24;  // the matrix-core kernel's 256-thread workgroups can hold a batch of 24 (context <= 6144)
 constexpr int ATT_PAD = 4;     // a chunk's partial is [head_dim] weighted values, its maximum, its sum, 2 spare floats (16-byte rows)
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
@@ -1102,7 +1103,7 @@ __device__ __forceinline__ bool last_arrival(int *counter, int n_expected, int *
 }
 
 struct AttnArgs;
-template <int HD>
+template <int HD, int CB>
 __device__ __forceinline__ void merge_pairs_device(const AttnArgs &a, int kvh, int p_base, int n_p, int group, float inv_group,
                                                    int start, int tid, int nt);
 
@@ -1228,16 +1229,16 @@ __device__ __forceinline__ void attn_partial_device(const AttnArgs &a, const Pas
             }
         }
         if (a.arrivals && last_arrival(a.arrivals + pg * a.Hkv + kvh, n_chunks, ticket))
-            merge_pairs_device<HD>(a, kvh, p_base, n_p, group, inv_group, start, tid, NT);
+            merge_pairs_device<HD, ATT_SELF_MERGE_CHUNKS>(a, kvh, p_base, n_p, group, inv_group, start, tid, NT);
     }
 }
 
 // The merge itself, by the nt threads of the calling workgroup: pairs [p_base, p_base + n_p) of kv head kvh, two
-// neighbouring dimensions per thread and step (8-byte agent-scope loads).
-template <int HD>
+// neighbouring dimensions per thread and step (8-byte agent-scope loads), the partials of CB chunks fetched together.
+template <int HD, int CB>
 __device__ __forceinline__ void merge_pairs_device(const AttnArgs &a, int kvh, int p_base, int n_p, int group, float inv_group,
                                                    int start, int tid, int nt) {
-    constexpr int CB = 8, PSTR = HD + ATT_PAD, H2 = HD / 2;
+    constexpr int PSTR = HD + ATT_PAD, H2 = HD / 2;
     const int qd = a.H * HD;
     const float inv_kc = __builtin_amdgcn_rcpf((float)a.out_kc);
     GemmOp st{};   // only the fields store_act uses

@@ -36,10 +36,11 @@ __host__ __device__ constexpr size_t vattn_lds_bytes() {
     return (size_t)VA_NW * 16 * (VA_WP + 4) * 4 + (size_t)VA_NW * 16 * (HD + 4) * 4;
 }
 
-// OCC = workgroups the register budget allows on a compute unit: 2 (180 registers per lane at HD = 128), or 3 for
-// launches with more work items than 2 x 256 workgroups (long contexts), which then run in one round instead of two
-template <int HD, int OCC>
-__global__ __launch_bounds__(VA_NT, OCC) void attn_partial_mfma_kernel(AttnArgs a, const PassCtl *ctl) {
+// LONG = false: contexts of up to eight chunks. LONG = true: compiled for three workgroups per compute unit (168
+// registers per lane), so that a launch with more work items than 2 x 256 workgroups runs in one round instead of
+// two, and with a merge that fetches the partials of up to 24 chunks together.
+template <int HD, bool LONG>
+__global__ __launch_bounds__(VA_NT, LONG ? 3 : 1) void attn_partial_mfma_kernel(AttnArgs a, const PassCtl *ctl) {
     constexpr int QS = HD / 32, DT = HD / 16;
     constexpr int PSTR = VA_WP + 4;            // floats per row of the P tile
     constexpr int MSTR = HD + 4;               // floats per row of the merge buffer (16-byte aligned rows)
@@ -242,7 +243,7 @@ __global__ __launch_bounds__(VA_NT, OCC) void attn_partial_mfma_kernel(AttnArgs 
         }
         if (!last_merges) continue;
         if (!last_arrival(a.arrivals + pt * a.Hkv + kvh, n_chunks, tickets)) continue;
-        merge_pairs_device<HD>(a, kvh, pt * 16, n_p, group, inv_group, start, tid, VA_NT);
+        merge_pairs_device<HD, LONG ? ATT_SELF_MERGE_CHUNKS_MFMA : ATT_SELF_MERGE_CHUNKS>(a, kvh, pt * 16, n_p, group, inv_group, start, tid, VA_NT);
     }
 }
 

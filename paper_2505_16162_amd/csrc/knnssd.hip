@@ -252,13 +252,13 @@ extern "C" int32_t knnssd_create(const knnssd_model_cfg *cfg, const knnssd_weigh
         if (ea == hipSuccess)
             ea = hipFuncSetAttribute((const void *)gemm_mfma_kernel<true, true>, hipFuncAttributeMaxDynamicSharedMemorySize, KS_MAX_DYN_LDS);
         if (ea == hipSuccess)
-            ea = hipFuncSetAttribute((const void *)attn_partial_mfma_kernel<128, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)vattn_lds_bytes<128>());
+            ea = hipFuncSetAttribute((const void *)attn_partial_mfma_kernel<128, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)vattn_lds_bytes<128>());
         if (ea == hipSuccess)
-            ea = hipFuncSetAttribute((const void *)attn_partial_mfma_kernel<64, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)vattn_lds_bytes<64>());
+            ea = hipFuncSetAttribute((const void *)attn_partial_mfma_kernel<64, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)vattn_lds_bytes<64>());
         if (ea == hipSuccess)
-            ea = hipFuncSetAttribute((const void *)attn_partial_mfma_kernel<128, 3>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)vattn_lds_bytes<128>());
+            ea = hipFuncSetAttribute((const void *)attn_partial_mfma_kernel<128, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)vattn_lds_bytes<128>());
         if (ea == hipSuccess)
-            ea = hipFuncSetAttribute((const void *)attn_partial_mfma_kernel<64, 3>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)vattn_lds_bytes<64>());
+            ea = hipFuncSetAttribute((const void *)attn_partial_mfma_kernel<64, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)vattn_lds_bytes<64>());
         if (ea == hipSuccess)
             ea = hipFuncSetAttribute((const void *)prefill_gemm_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pf_gemm_lds_bytes(4));
         if (ea == hipSuccess)
@@ -566,11 +566,12 @@ static int32_t run_pass_bf16(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, b
     // Long contexts keep the launch as well: the last workgroup fetches the chunks in serial batches of eight, and at
     // 17 chunks (context 4096) that costs what the launch costs (verification) or 3 us more (draft steps).
     const bool self_merge = c->cfg.attn_merge == KNNSSD_MERGE_FUSED && n_rows * aa.group <= ATT_SELF_MERGE_PAIRS &&
-                            start + n_rows <= ATT_SELF_MERGE_CHUNKS * ATT_CHUNK;
-    // More (pair tile, kv head, chunk) items than two workgroups per compute unit take in one round (long contexts):
-    // the variant compiled for three per unit
-    const int va_items = (n_rows * aa.group + 15) / 16 * ((Hkv * ((start + n_rows + ATT_CHUNK - 1) / ATT_CHUNK) + 7) & ~7);
-    const bool va_wide = va_items > 2 * KS_NWG;
+                            start + n_rows <= (mfma_attn ? ATT_SELF_MERGE_CHUNKS_MFMA : ATT_SELF_MERGE_CHUNKS) * ATT_CHUNK;
+    // More than eight chunks, or more (pair tile, kv head, chunk) items than two workgroups per compute unit take in
+    // one round: the variant compiled for three per unit, whose merge fetches up to 24 chunks together
+    const int va_items = (n_rows * aa.group + 15) / 16 * ((Hkv * n_chunks_now + 7) & ~7);
+    const bool va_long = n_chunks_now > ATT_SELF_MERGE_CHUNKS || va_items > 2 * KS_NWG;
+    const int va_grid = va_items > 2 * KS_NWG ? 3 * KS_NWG : 2 * KS_NWG;
     for (int b = 0; b < g.n_blocks; ++b) {
         bf16_t *kvb = (bf16_t *)(c->kv + (size_t)b * c->kv_block_bytes);
         if (!(mask && mask[2 * b])) {
@@ -584,11 +585,11 @@ static int32_t run_pass_bf16(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, b
             } else if (mfma_attn) {
                 // verification, and draft steps of grouped-query models (one row still brings H / Hkv pairs per kv
                 // head): the pairs of a work item side by side on the matrix cores
-                if (va_wide) {
-                    if (hd == 128) hipLaunchKernelGGL((attn_partial_mfma_kernel<128, 3>), dim3(3 * KS_NWG), dim3(VA_NT), vattn_lds_bytes<128>(), s, aa, ctl);
-                    else hipLaunchKernelGGL((attn_partial_mfma_kernel<64, 3>), dim3(3 * KS_NWG), dim3(VA_NT), vattn_lds_bytes<64>(), s, aa, ctl);
-                } else if (hd == 128) hipLaunchKernelGGL((attn_partial_mfma_kernel<128, 2>), dim3(2 * KS_NWG), dim3(VA_NT), vattn_lds_bytes<128>(), s, aa, ctl);
-                else hipLaunchKernelGGL((attn_partial_mfma_kernel<64, 2>), dim3(2 * KS_NWG), dim3(VA_NT), vattn_lds_bytes<64>(), s, aa, ctl);
+                if (va_long) {
+                    if (hd == 128) hipLaunchKernelGGL((attn_partial_mfma_kernel<128, true>), dim3(va_grid), dim3(VA_NT), vattn_lds_bytes<128>(), s, aa, ctl);
+                    else hipLaunchKernelGGL((attn_partial_mfma_kernel<64, true>), dim3(va_grid), dim3(VA_NT), vattn_lds_bytes<64>(), s, aa, ctl);
+                } else if (hd == 128) hipLaunchKernelGGL((attn_partial_mfma_kernel<128, false>), dim3(2 * KS_NWG), dim3(VA_NT), vattn_lds_bytes<128>(), s, aa, ctl);
+                else hipLaunchKernelGGL((attn_partial_mfma_kernel<64, false>), dim3(2 * KS_NWG), dim3(VA_NT), vattn_lds_bytes<64>(), s, aa, ctl);
             } else if (hd == 128) hipLaunchKernelGGL((attn_partial_kernel<128>), dim3(KS_NWG), dim3(NT), attn_lds_bytes(128), s, aa, ctl);
             else hipLaunchKernelGGL((attn_partial_kernel<64>), dim3(KS_NWG), dim3(NT), attn_lds_bytes(64), s, aa, ctl);
             if (!others || self_merge) {
