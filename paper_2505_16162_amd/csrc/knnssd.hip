@@ -563,8 +563,8 @@ static int32_t run_pass_bf16(knnssd_ctx *c, PassCtl *ctl, const uint8_t *mask, b
     // kernel's three workgroups per unit finish first (13B-shaped, context 4096: 19.8 against 23.1 us per block).
     const int n_chunks_now = (start + n_rows + ATT_CHUNK - 1) / ATT_CHUNK;
     const bool mfma_attn = (!rows1 || aa.group >= 2 || Hkv * n_chunks_now > 2 * KS_NWG) && c->verify_attn_mfma;
-    // Long contexts keep the launch as well: the last workgroup fetches the chunks in serial batches of eight, and at
-    // 17 chunks (context 4096) that costs what the launch costs (verification) or 3 us more (draft steps).
+    // Contexts whose chunks do not fit one batch of the merge's loads keep the launch as well (every batch is a
+    // dependent round trip of the one workgroup): eight chunks on the vector-ALU kernel, 24 on the matrix-core one.
     const bool self_merge = c->cfg.attn_merge == KNNSSD_MERGE_FUSED && n_rows * aa.group <= ATT_SELF_MERGE_PAIRS &&
                             start + n_rows <= (mfma_attn ? ATT_SELF_MERGE_CHUNKS_MFMA : ATT_SELF_MERGE_CHUNKS) * ATT_CHUNK;
     // More than eight chunks, or more (pair tile, kv head, chunk) items than two workgroups per compute unit take in
