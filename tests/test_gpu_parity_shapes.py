@@ -260,7 +260,8 @@ def test_merge_inside_the_attention_launch(gqa):
     KNNSSD_MERGE_FUSED, the default: the workgroup that finishes a group's last chunk does it); the same steps with the
     merge as a launch of its own (KNNSSD_MERGE_SEPARATE) must give the same bits, at one, two, six, seven and nine chunks,
     for draft steps (vector-ALU kernel, or the matrix-core one with grouped-query heads) and for verification passes of
-    1, 3 and 5 rows (more than four pairs per kv head keep the launch), and both are checked against the oracle."""
+    1 to 16 rows (at the last context, 2100 positions = nine chunks, more than four pairs per kv head keep the launch;
+    the rows are compared between the two contexts only), and the draft steps are checked against the oracle."""
     shape = synth.small_shape("fuse_gqa" if gqa else "fuse_mha", n_blocks=2, d_model=512, n_heads=8, n_kv_heads=2 if gqa else 8,
                               head_dim=64, d_ffn=1408, vocab=900, max_seq=2200)
     w, orc, gpu = make_pair(shape, seed=37, std=0.04)
@@ -287,15 +288,18 @@ def test_merge_inside_the_attention_launch(gqa):
             tok = t1
     # verification rows on the three contexts (the matrix-core kernel merges one- and three-row passes itself unless
     # the merge is a launch of its own)
-    rows_in = [first_o] + synth.make_prompt(shape.vocab, 4, seed=8).tolist()
-    for n in (1, 3, 5):
-        got = []
-        for g in (gpu, gpu2):
-            g.knnssd_prefill(prompt)
-            g.knnssd_verify(rows_in[:n], len(prompt))
-            got.append([g.knnssd_get_logits(r).clone() for r in range(n)])
-        for r in range(n):
-            assert torch.equal(got[0][r], got[1][r]), (n, r)
+    rows_in = [first_o] + synth.make_prompt(shape.vocab, 15, seed=8).tolist()
+    for vlen in (283, 1300, 2100):        # two, six and nine chunks
+        vprompt = synth.make_prompt(shape.vocab, vlen, seed=2).tolist()
+        for n in (1, 3, 5, 9, 16):        # 9 and 16 rows: whole tiles of pairs, merged four items per thread
+            print("verify case", gqa, vlen, n, flush=True)
+            got = []
+            for g in (gpu, gpu2):
+                g.knnssd_prefill(vprompt)
+                g.knnssd_verify(rows_in[:n], vlen)
+                got.append([g.knnssd_get_logits(r).clone() for r in range(n)])
+            for r in range(n):
+                assert torch.equal(got[0][r], got[1][r]), (vlen, n, r)
     gpu.close()
     gpu2.close()
 
