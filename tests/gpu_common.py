@@ -33,6 +33,7 @@ MEASURED = {
     "mixed": 6.5e-7, "bf16_mha": 3.4e-5, "bf16_gqa": 1.4e-4, "bf16_mfma": 2.9e-4, "llama7b_w3": 4.1e-4,
     "long_ctx": 4.5e-5, "long_k": 3.1e-4, "narrow": 1.8e-5, "tiles356": 6.8e-5, "va_gqa": 5.4e-4, "va_mha": 1.6e-4,
     "llama13b": 4.2e-3, "llama13b_w2": 3.3e-3, "llama7b_w2": 1.1e-3, "qwen14b_w1": 2.4e-4, "qwen_w4": 1.2e-3,
+    "llama7b": 5.1e-3, "qwen14b": 5.9e-3,      # full depth (32 and 48 blocks)
 }
 DEFAULT_MEASURED = {"fp32": 2e-6, "bf16": 5e-4}
 

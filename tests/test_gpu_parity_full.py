@@ -207,6 +207,52 @@ def test_13b_many_row_prefill_equals_16_row_passes(llama13b):
     gpu2.close()
 
 
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("name", ["llama7b", "qwen14b"])
+def test_full_depth_short_run_matches_oracle(name):
+    """The 7B-shaped and the Qwen-14B-shaped configurations at their full depth (32 and 48 blocks, the benchmark's
+    anchor tables and draft rules) on a prompt short enough for the oracle: first token and its logits, routing of the
+    prompt's own hidden vector, a draft step, a verification pass, and a few generated tokens with their counters."""
+    wl = synth.workload(name)
+    shape = wl.shape
+    print("building", name, flush=True)
+    w = synth.make_weights(shape, device="cuda:0", seed=17)
+    gpu = binding.KnnSsd(shape, w, max_anchors=wl.n_anchors)
+    anchors, labels, _ = synth.make_anchors(shape.d_model, wl.n_anchors, wl.n_domains, wl.anchor_sigma, seed=5)
+    masks = synth.make_block_masks(shape.n_blocks, wl.n_domains, wl.skipped_blocks, seed=4)
+    gpu.knnssd_set_anchors(anchors, labels, masks)
+    print("copying the weights to the host for the oracle", flush=True)
+    orc = O.OracleModel(shape, synth.weights_to(w, "cpu"))
+    prompt = synth.make_prompt(shape.vocab, 24, seed=77).tolist()
+    first_o, hidden_o, row_o = O.prefill(orc, prompt)
+    first_g, hidden_g = gpu.knnssd_prefill(prompt)
+    ok, err = logits_close(gpu.knnssd_get_logits(7).numpy(), row_o, shape)
+    assert ok, err
+    assert first_g == first_o, O.top2_margin(row_o)
+    idx_o, dom_o, mask_o, _ = O.knn_select(hidden_o, anchors.numpy(), labels.numpy(), masks.numpy())
+    assert gpu.knnssd_select_skipset(hidden_g) == (idx_o, dom_o, mask_o.tolist())
+    row = orc.forward([first_o], len(prompt), mask_o)[0]
+    tok_g, p_g = gpu.knnssd_draft_step(first_o, len(prompt))
+    ok, err = logits_close(gpu.knnssd_get_logits(0).numpy(), row, shape)
+    assert ok, err
+    assert tok_g == O.argmax_lowest(row) and abs(p_g - O.top1_prob(row)) <= 1e-2 * O.top1_prob(row)
+    rows_in = [first_o, tok_g, 17, 5]
+    rows_o = orc.forward(rows_in, len(prompt), None)
+    j, nxt, new_len = gpu.knnssd_verify(rows_in, len(prompt))
+    for r in range(4):
+        ok, err = logits_close(gpu.knnssd_get_logits(r).numpy(), rows_o[r], shape)
+        assert ok, (r, err)
+    targets = [O.argmax_lowest(rows_o[r]) for r in range(4)]
+    assert j == O.accept_length(rows_in[1:], targets) and nxt == targets[j] and new_len == len(prompt) + j + 1
+    print("oracle generate", flush=True)
+    res = O.knnssd_generate(orc, prompt, anchors.numpy(), labels.numpy(), masks.numpy(), 5, wl.max_draft, wl.conf_threshold)
+    toks, st = gpu.knnssd_generate(prompt, 5, wl.max_draft, wl.conf_threshold)
+    margins = [min(r.margins) for r in res["rounds"]]
+    assert toks == res["tokens"], f"oracle top-2 margins {margins}"
+    assert (st["rounds"], st["drafted"], st["accepted"]) == (res["stats"].rounds, res["stats"].drafted, res["stats"].accepted)
+    gpu.close()
+
+
 @pytest.mark.timeout(600)
 def test_qwen_widths_gqa_big_vocab_matches_oracle():
     """Qwen-2.5-14B-shaped widths (GQA 40/8, vocab 152064, FFN 13824) at reduced depth so that the oracle
