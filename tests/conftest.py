@@ -31,4 +31,5 @@ def pytest_terminal_summary(terminalreporter):
                                 "largest logit) and the bound enforced:")
     for name, err in sorted(gpu_common.ACHIEVED.items()):
         m = gpu_common.MEASURED.get(name)
-        terminalreporter.write_line("  %-24s %.3e   bound %s" % (name, err, ("%.1e" % (10 * m)) if m else "default"))
+        cap = gpu_common.FP32_ABS_BOUND if name in ("tiny", "fp32_gqa") else gpu_common.BF16_REL_BOUND
+        terminalreporter.write_line("  %-24s %.3e   bound %s" % (name, err, ("%.1e" % min(cap, 10 * m)) if m else "default"))

@@ -212,7 +212,8 @@ def test_13b_many_row_prefill_equals_16_row_passes(llama13b):
 def test_full_depth_short_run_matches_oracle(name):
     """The 7B-shaped and the Qwen-14B-shaped configurations at their full depth (32 and 48 blocks, the benchmark's
     anchor tables and draft rules) on a prompt short enough for the oracle: first token and its logits, routing of the
-    prompt's own hidden vector, a draft step, a verification pass, and a few generated tokens with their counters."""
+    prompt's own hidden vector, a draft step, a verification pass, and a few generated tokens with their counters; then, at
+    the benchmark's prompt length, the properties that need no oracle."""
     wl = synth.workload(name)
     shape = wl.shape
     print("building", name, flush=True)
@@ -250,6 +251,24 @@ def test_full_depth_short_run_matches_oracle(name):
     margins = [min(r.margins) for r in res["rounds"]]
     assert toks == res["tokens"], f"oracle top-2 margins {margins}"
     assert (st["rounds"], st["drafted"], st["accepted"]) == (res["stats"].rounds, res["stats"].drafted, res["stats"].accepted)
+    del orc
+    # at the benchmark's own prompt length, what holds at any size: SSD output = AR output, rows independent of the pass
+    print("benchmark prompt length", flush=True)
+    prompt_b = synth.make_prompt(shape.vocab, wl.prompt_len).tolist()
+    ar, st_ar = gpu.knnssd_generate(prompt_b, 24, 0)
+    assert len(ar) == 24 and st_ar["rounds"] == 23
+    for thr in (wl.conf_threshold, 0.0) if wl.conf_threshold > 0 else (0.0,):
+        toks, st = gpu.knnssd_generate(prompt_b, 24, wl.max_draft, thr)
+        assert toks == ar, thr
+        assert st["emitted"] == 24 and st["accepted"] <= st["drafted"]
+    gpu.knnssd_prefill(prompt_b)
+    rows_b = [ar[0]] + ar[1:9]
+    gpu.knnssd_verify(rows_b, len(prompt_b))
+    many = [gpu.knnssd_get_logits(r).clone() for r in range(9)]
+    gpu.knnssd_prefill(prompt_b)
+    for r in range(3):
+        gpu.knnssd_verify(rows_b[r:r + 1], len(prompt_b) + r)
+        assert torch.equal(gpu.knnssd_get_logits(0), many[r]), r
     gpu.close()
 
 
