@@ -304,6 +304,46 @@ def test_merge_inside_the_attention_launch(gqa):
     gpu2.close()
 
 
+@pytest.mark.parametrize("hd", [64, 128])
+def test_merge_inside_the_attention_launch_up_to_24_chunks(hd):
+    """The matrix-core kernel's build for long contexts merges its own chunks up to 24 of them (6144 positions) in one
+    batch of loads; one position further the merge is a launch of its own. Draft steps and 1- to 4-row verification
+    passes around that edge and at 9 and 17 chunks, fused against separate merge, bit for bit (the separate merge is
+    the one the oracle comparisons at long contexts run)."""
+    shape = synth.small_shape("edge24_%d" % hd, n_blocks=2, d_model=256, n_heads=4, n_kv_heads=2, head_dim=hd, d_ffn=704,
+                              vocab=900, max_seq=6200)
+    w = synth.make_weights(shape, seed=41, gains="random", std=0.05)
+    gpu = binding.KnnSsd(shape, w)
+    gpu2 = binding.KnnSsd(shape, w, separate_merge=True)
+    mask = [0, 1, 0, 0]
+    rows_in = synth.make_prompt(shape.vocab, 4, seed=3).tolist()
+    for plen in (2300, 4200, 6139, 6141, 6144):      # 9 and 17 chunks; 24 chunks exactly, then across the edge
+        print("case", hd, plen, flush=True)
+        prompt = synth.make_prompt(shape.vocab, plen, seed=2).tolist()
+        firsts = []
+        for g in (gpu, gpu2):
+            firsts.append(g.knnssd_prefill(prompt)[0])
+            g.knnssd_set_skipset(mask)
+        assert firsts[0] == firsts[1]
+        tok = firsts[0]
+        for i in range(4):                                   # the steps walk over the edge
+            r1, r2 = gpu.knnssd_draft_step(tok, plen + i), gpu2.knnssd_draft_step(tok, plen + i)
+            assert r1 == r2, (plen, i)
+            assert torch.equal(gpu.knnssd_get_logits(0), gpu2.knnssd_get_logits(0)), (plen, i)
+            tok = r1[0]
+        for n in (1, 2, 4):
+            got = []
+            for g in (gpu, gpu2):
+                g.knnssd_prefill(prompt)
+                res = g.knnssd_verify([firsts[0]] + rows_in[:n - 1], plen)
+                got.append((res, [g.knnssd_get_logits(r).clone() for r in range(n)]))
+            assert got[0][0] == got[1][0], (plen, n)
+            for r in range(n):
+                assert torch.equal(got[0][1][r], got[1][1][r]), (plen, n, r)
+    gpu.close()
+    gpu2.close()
+
+
 @pytest.mark.timeout(900)
 @pytest.mark.parametrize("hd,heads,kv_heads,plen,row_counts", [(64, 32, 32, 4101, (2, 9)), (128, 32, 8, 6200, (9, 2))])
 def test_attention_with_more_work_items_than_workgroups(hd, heads, kv_heads, plen, row_counts):
